@@ -1,0 +1,217 @@
+"""CPU oracle for the group-wise quantized linear layer -- TEST INFRASTRUCTURE.
+
+Thin numpy/ctypes front end of ``qbert_oracle.c``.  Only the tests, the smoke check and the
+benchmark's ``cpu_baseline`` leg may import this package; the product package never does.
+Every function takes and returns numpy arrays; nothing here knows about the GPU.
+"""
+import ctypes
+import numpy as np
+
+from . import build as _build
+
+_I64 = ctypes.c_int64
+_P = ctypes.c_void_p
+_libs = {}
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _lib(openmp=False):
+    if openmp not in _libs:
+        _build.build()
+        lib = ctypes.CDLL(_build.lib_path(openmp))
+        lib.qbo_packed_row_bytes.restype = _I64
+        lib.qbo_packed_row_bytes.argtypes = [_I64, ctypes.c_int]
+        lib.qbo_num_threads.restype = ctypes.c_int
+        _libs[openmp] = lib
+    return _libs[openmp]
+
+
+def _ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise OracleError("%s failed with oracle status %d" % (what, rc))
+
+
+def num_threads(openmp=True):
+    return int(_lib(openmp).qbo_num_threads())
+
+
+def quantize_groupwise(W, bits, groups):
+    """Sec. 3.3 grouping + appendix quantizer. Returns codes[N,K] u8, h[G], m[G], rs_w[N]."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    codes = np.empty((N, K), np.uint8)
+    h = np.empty(groups, np.float32)
+    m = np.empty(groups, np.float32)
+    rs = np.empty(N, np.int32)
+    rc = _lib().qbo_quantize_groupwise(_ptr(W), _I64(N), _I64(K), int(bits), _I64(groups),
+                                       _ptr(codes), _ptr(h), _ptr(m), _ptr(rs))
+    _check(rc, "quantize_groupwise")
+    return codes, h, m, rs
+
+
+def dequantize_groupwise(codes, h, bits):
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    N, K = codes.shape
+    out = np.empty((N, K), np.float64)
+    _check(_lib().qbo_dequantize_groupwise(_ptr(codes), _ptr(h), _I64(N), _I64(K), int(bits),
+                                           _I64(h.shape[0]), _ptr(out)), "dequantize_groupwise")
+    return out
+
+
+def packed_row_bytes(K, bits):
+    return int(_lib().qbo_packed_row_bytes(_I64(K), int(bits)))
+
+
+def pack(codes, bits):
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape
+    out = np.empty((N, packed_row_bytes(K, bits)), np.uint8)
+    _check(_lib().qbo_pack(_ptr(codes), _I64(N), _I64(K), int(bits), _ptr(out)), "pack")
+    return out
+
+
+def unpack(packed, K, bits):
+    packed = _c(packed, np.uint8)
+    N = packed.shape[0]
+    out = np.empty((N, K), np.uint8)
+    _check(_lib().qbo_unpack(_ptr(packed), _I64(N), _I64(K), int(bits), _ptr(out)), "unpack")
+    return out
+
+
+def quantize_act(X, clip):
+    """8-bit activation quantizer. Returns xq[T,K] int8 (= u-128) and rs_x[T] int32."""
+    X = _c(X, np.float32)
+    T, K = X.shape
+    xq = np.empty((T, K), np.int8)
+    rs = np.empty(T, np.int32)
+    _check(_lib().qbo_quantize_act(_ptr(X), _I64(T), _I64(K), ctypes.c_float(clip), _ptr(xq), _ptr(rs)),
+           "quantize_act")
+    return xq, rs
+
+
+def dequantize_act(xq, clip):
+    xq = _c(xq, np.int8)
+    T, K = xq.shape
+    out = np.empty((T, K), np.float64)
+    _check(_lib().qbo_dequantize_act(_ptr(xq), _I64(T), _I64(K), ctypes.c_float(clip), _ptr(out)),
+           "dequantize_act")
+    return out
+
+
+def qlinear_fwd(xq, clip, codes, h, bits, bias=None, openmp=False):
+    """Integer product + de-quantization. Returns Y[T,N] f32, A4[T,N] i32, acc[T,N] i32."""
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == K
+    Y = np.empty((T, N), np.float32)
+    A4 = np.empty((T, N), np.int32)
+    acc = np.empty((T, N), np.int32)
+    rc = _lib(openmp).qbo_qlinear_fwd(_ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(h), int(bits),
+                                      _I64(h.shape[0]), _I64(T), _I64(N), _I64(K), _ptr(bias),
+                                      _ptr(Y), _ptr(A4), _ptr(acc))
+    _check(rc, "qlinear_fwd")
+    return Y, A4, acc
+
+
+def qlinear_fwd_sampled(xq, clip, codes, h, bits, ts, ns, bias=None):
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    ts = _c(ts, np.int64)
+    ns = _c(ns, np.int64)
+    T, K = xq.shape
+    N = codes.shape[0]
+    Y = np.empty(ts.shape[0], np.float32)
+    A4 = np.empty(ts.shape[0], np.int32)
+    rc = _lib().qbo_qlinear_fwd_sampled(_ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(h), int(bits),
+                                        _I64(h.shape[0]), _I64(T), _I64(N), _I64(K), _ptr(bias),
+                                        _ptr(ts), _ptr(ns), _I64(ts.shape[0]), _ptr(Y), _ptr(A4))
+    _check(rc, "qlinear_fwd_sampled")
+    return Y, A4
+
+
+def qlinear_bwd_ste(dY_bf16, xq, clip, codes, h, bits, want_dx=True, want_dw=True, openmp=False):
+    """STE backward in binary64. dY_bf16 holds bfloat16 bit patterns (uint16)."""
+    dY = _c(dY_bf16, np.uint16)
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert dY.shape == (T, N)
+    dX = np.empty((T, K), np.float64) if want_dx else None
+    dW = np.empty((N, K), np.float64) if want_dw else None
+    rc = _lib(openmp).qbo_qlinear_bwd_ste(_ptr(dY), _ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(h),
+                                          int(bits), _I64(h.shape[0]), _I64(T), _I64(N), _I64(K),
+                                          _ptr(dX), _ptr(dW))
+    _check(rc, "qlinear_bwd_ste")
+    return dX, dW
+
+
+def bwd_dx_sampled(dY_bf16, codes, h, bits, ts, js):
+    dY = _c(dY_bf16, np.uint16)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    ts = _c(ts, np.int64)
+    js = _c(js, np.int64)
+    T, N = dY.shape
+    K = codes.shape[1]
+    out = np.empty(ts.shape[0], np.float64)
+    rc = _lib().qbo_bwd_dx_sampled(_ptr(dY), _ptr(codes), _ptr(h), int(bits), _I64(h.shape[0]),
+                                   _I64(T), _I64(N), _I64(K), _ptr(ts), _ptr(js), _I64(ts.shape[0]), _ptr(out))
+    _check(rc, "bwd_dx_sampled")
+    return out
+
+
+def bwd_dw_sampled(dY_bf16, xq, clip, ns, js):
+    dY = _c(dY_bf16, np.uint16)
+    xq = _c(xq, np.int8)
+    ns = _c(ns, np.int64)
+    js = _c(js, np.int64)
+    T, N = dY.shape
+    K = xq.shape[1]
+    out = np.empty(ns.shape[0], np.float64)
+    rc = _lib().qbo_bwd_dw_sampled(_ptr(dY), _ptr(xq), ctypes.c_float(clip), _I64(T), _I64(N), _I64(K),
+                                   _ptr(ns), _ptr(js), _I64(ns.shape[0]), _ptr(out))
+    _check(rc, "bwd_dw_sampled")
+    return out
+
+
+def embedding_quantize(E, groups):
+    E = _c(E, np.float32)
+    V, d = E.shape
+    codes = np.empty((V, d), np.uint8)
+    h = np.empty(groups, np.float32)
+    m = np.empty(groups, np.float32)
+    _check(_lib().qbo_embedding_quantize(_ptr(E), _I64(V), _I64(d), _I64(groups), _ptr(codes), _ptr(h), _ptr(m)),
+           "embedding_quantize")
+    return codes, h, m
+
+
+def embedding_gather(codes, h, ids):
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    ids = _c(ids, np.int64)
+    V, d = codes.shape
+    out = np.empty((ids.shape[0], d), np.float64)
+    _check(_lib().qbo_embedding_gather(_ptr(codes), _ptr(h), _I64(V), _I64(d), _I64(h.shape[0]),
+                                       _ptr(ids), _I64(ids.shape[0]), _ptr(out)), "embedding_gather")
+    return out

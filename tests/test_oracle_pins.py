@@ -1,0 +1,370 @@
+"""Pins of the CPU oracle against things other than itself.
+
+Each test fixes one part of oracle/qbert_oracle.c to a value that the paper or plain
+mathematics determines: closed-form lattices, exact rational arithmetic, brute force with
+Python integers, numpy's own matmul/packbits, special cases of the grouping rule, and the
+model sizes printed in Table 1.  None of them retypes the oracle's float32 formula.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+BITS = (2, 3, 4, 8)
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def exact_levels(m, L):
+    """The 2^k quantized points of the range [-m, m] as exact rationals (App.: q0 + Delta*j)."""
+    m = Fraction(float(m))
+    return [-m + (2 * m / L) * j for j in range(L + 1)]
+
+
+# ---- P1: closed-form lattice --------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("e", (-7, 0, 3))
+def test_lattice_points_map_to_their_index(bits, e):
+    L = 2 ** bits - 1
+    h = np.float32(2.0 ** e)
+    w = np.array([h * (2 * j - L) for j in range(L + 1)], np.float32)  # exact in fp32
+    W = np.tile(w, (2, 3)).astype(np.float32)  # one group, 2 rows
+    codes, hh, mm, rs = oracle.quantize_groupwise(W, bits, 1)
+    assert mm[0] == h * L and hh[0] == h
+    assert (codes == np.tile(np.arange(L + 1, dtype=np.uint8), (2, 3))).all()
+    deq = oracle.dequantize_groupwise(codes, hh, bits)
+    assert (deq == W.astype(np.float64)).all()
+    # sum of (u - 2^(k-1)) over j = 0..L is -(L+1)/2 per period, 3 periods per row
+    assert (rs == -3 * (L + 1) // 2).all()
+
+
+# ---- P2: |w - Q(w)| <= Delta/2, and exact nearest-level property ---------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_error_bound_and_extremes(bits):
+    L = 2 ** bits - 1
+    W = (rng(1).standard_normal((24, 40)) * 0.04).astype(np.float32)
+    W[3, 5] = 0.9  # an outlier
+    G = 4
+    codes, h, m, _ = oracle.quantize_groupwise(W, bits, G)
+    deq = oracle.dequantize_groupwise(codes, h, bits)
+    rows = 24 // G
+    for g in range(G):
+        blk = slice(g * rows, (g + 1) * rows)
+        assert m[g] == np.abs(W[blk]).max()
+        err = np.abs(W[blk].astype(np.float64) - deq[blk])
+        assert err.max() <= float(h[g]) * (1 + 1e-6) + 4 * np.spacing(np.float64(m[g]).astype(np.float32))
+        wb, cb = W[blk], codes[blk]
+        assert set(np.unique(cb[np.abs(wb) == m[g]])) <= {0, L}
+        assert (cb[wb == m[g]] == L).all() and (cb[wb == -m[g]] == 0).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_code_is_nearest_exact_level(bits):
+    """Exact rational arithmetic: the code is the index of the nearest of the 2^k levels."""
+    L = 2 ** bits - 1
+    W = (rng(2).standard_normal((6, 32)) * 0.3).astype(np.float32)
+    codes, h, m, _ = oracle.quantize_groupwise(W, bits, 2)
+    checked = 0
+    for g in range(2):
+        mg = Fraction(float(m[g]))
+        for r in range(3 * g, 3 * g + 3):
+            for j in range(32):
+                t = (Fraction(float(W[r, j])) + mg) * L / (2 * mg)  # exact (w - q0)/Delta
+                frac = t - (t.numerator // t.denominator)
+                if abs(frac - Fraction(1, 2)) < Fraction(1, 10 ** 5):
+                    continue  # too close to a decision boundary for float32 to be held to it
+                assert codes[r, j] == int(round(t))
+                checked += 1
+    assert checked > 150
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_dequantized_value_is_the_exact_level(bits):
+    """Q(w) = Delta*u + q0 evaluated exactly, against the oracle's h*(2u-L), to float32 accuracy."""
+    L = 2 ** bits - 1
+    W = (rng(3).standard_normal((4, 64))).astype(np.float32)
+    codes, h, m, _ = oracle.quantize_groupwise(W, bits, 1)
+    deq = oracle.dequantize_groupwise(codes, h, bits)
+    lv = exact_levels(m[0], L)
+    for r in range(4):
+        for j in range(64):
+            ex = lv[codes[r, j]]
+            assert abs(Fraction(deq[r, j]) - ex) <= abs(ex) * Fraction(1, 2 ** 23)
+
+
+# ---- P3: ties go to the even code; activation zero --------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_ties_round_half_to_even(bits):
+    L = 2 ** bits - 1
+    h = np.float32(0.25)
+    mids = np.array([h * (2 * j + 1 - L) for j in range(L)], np.float32)  # t = j + 1/2 exactly
+    W = np.concatenate([[-h * L, h * L], mids]).astype(np.float32)[None, :]
+    codes, hh, mm, _ = oracle.quantize_groupwise(W, bits, 1)
+    assert hh[0] == h
+    expect = np.array([j if j % 2 == 0 else j + 1 for j in range(L)], np.uint8)
+    assert (codes[0, 2:] == expect).all()
+
+
+def test_activation_special_values():
+    clip = 6.0
+    X = np.array([[0.0, -0.0, 6.0, -6.0, 100.0, -100.0, np.inf, -np.inf]], np.float32)
+    xq, rs = oracle.quantize_act(X, clip)
+    # x = 0 sits exactly between codes 127 and 128: half-to-even picks 128, stored 128-128 = 0
+    assert xq[0].tolist() == [0, 0, 127, -128, 127, -128, 127, -128]
+    assert rs[0] == sum(xq[0].tolist())
+
+
+def test_activation_lattice_and_exact_nearest():
+    clip = np.float32(255 / 64.0)  # h_x = 1/64 exactly
+    u = np.arange(256)
+    X = ((2 * u - 255) / 64.0).astype(np.float32)[None, :]
+    xq, rs = oracle.quantize_act(X, float(clip))
+    assert (xq[0].astype(np.int64) + 128 == u).all()
+    Xh = oracle.dequantize_act(xq, float(clip))
+    assert (Xh == X.astype(np.float64)).all()
+    # random values: nearest of 256 exact levels
+    X = (rng(4).standard_normal((3, 50)) * 2).astype(np.float32)
+    xq, _ = oracle.quantize_act(X, 6.0)
+    c = Fraction(6)
+    for r in range(3):
+        for j in range(50):
+            x = min(max(Fraction(float(X[r, j])), -c), c)
+            t = (x + c) * 255 / (2 * c)
+            fr = t - (t.numerator // t.denominator)
+            if abs(fr - Fraction(1, 2)) < Fraction(1, 10 ** 4):
+                continue
+            assert int(xq[r, j]) + 128 == int(round(t))
+
+
+# ---- P4: idempotence ---------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_quantize_dequantize_idempotent(bits):
+    W = (rng(5).standard_normal((16, 48)) * 0.05).astype(np.float32)
+    codes, h, m, _ = oracle.quantize_groupwise(W, bits, 4)
+    Wq = oracle.dequantize_groupwise(codes, h, bits).astype(np.float32)
+    codes2, h2, m2, _ = oracle.quantize_groupwise(Wq, bits, 4)
+    assert (codes2 == codes).all()
+    Wq2 = oracle.dequantize_groupwise(codes2, h2, bits).astype(np.float32)
+    assert np.allclose(Wq2, Wq, rtol=3e-7, atol=0)
+
+
+# ---- P5: code range and count --------------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_code_range_and_all_levels_used(bits):
+    L = 2 ** bits - 1
+    W = rng(6).uniform(-1, 1, (8, 512)).astype(np.float32)
+    codes, _, _, rs = oracle.quantize_groupwise(W, bits, 2)
+    assert codes.max() <= L
+    for g in range(2):
+        assert len(np.unique(codes[4 * g:4 * g + 4])) == L + 1
+    assert (rs == (codes.astype(np.int64) - 2 ** (bits - 1)).sum(1)).all()
+
+
+def test_all_zero_group():
+    W = np.zeros((4, 8), np.float32)
+    W[2:] = 0.5
+    codes, h, m, rs = oracle.quantize_groupwise(W, 4, 2)
+    assert m[0] == 0 and h[0] == 0 and (codes[:2] == 0).all()
+    assert (oracle.dequantize_groupwise(codes, h, 4)[:2] == 0).all()
+    assert (codes[2:] == 15).all()
+
+
+# ---- P6: special cases of the grouping rule (Fig. 3; Table 2's 1/12/128/768 groups) ---------------
+@pytest.mark.parametrize("bits", (2, 4))
+@pytest.mark.parametrize("G", (1, 12, 24, 128, 768))
+def test_groups_equal_separately_quantized_row_blocks(bits, G):
+    N, K = 768, 32
+    W = (rng(7).standard_normal((N, K)) * 0.04).astype(np.float32)
+    codes, h, m, rs = oracle.quantize_groupwise(W, bits, G)
+    rows = N // G
+    for g in (0, G // 2, G - 1):
+        blk = slice(g * rows, (g + 1) * rows)
+        c1, h1, m1, rs1 = oracle.quantize_groupwise(W[blk], bits, 1)
+        assert (c1 == codes[blk]).all() and h1[0] == h[g] and m1[0] == m[g] and (rs1 == rs[blk]).all()
+        assert m[g] == np.abs(W[blk]).max()
+    if G == 768:  # one range per output neuron: per-channel quantization
+        assert (m == np.abs(W).max(axis=1)).all()
+    if G == 12:   # one range per head: blocks of d/N_h = 64 neurons
+        assert rows == 64
+
+
+# ---- P7 / P8: scale equivariance, monotonicity -------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_power_of_two_equivariance_and_monotone(bits):
+    W = (rng(8).standard_normal((8, 64)) * 0.04).astype(np.float32)
+    c1, h1, m1, _ = oracle.quantize_groupwise(W, bits, 2)
+    c2, h2, m2, _ = oracle.quantize_groupwise(W * np.float32(16), bits, 2)
+    assert (c1 == c2).all() and (h2 == h1 * 16).all() and (m2 == m1 * 16).all()
+    for g in range(2):
+        w = W[4 * g:4 * g + 4].ravel()
+        c = c1[4 * g:4 * g + 4].ravel()
+        order = np.argsort(w, kind="stable")
+        assert (np.diff(c[order].astype(int)) >= 0).all()
+
+
+# ---- P9: packing against numpy.packbits, and the paper's printed sizes ----------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_pack_matches_little_endian_bitstream(bits):
+    codes = rng(9).integers(0, 2 ** bits, (5, 64), dtype=np.uint8)
+    packed = oracle.pack(codes, bits)
+    assert packed.shape == (5, 64 * bits // 8)
+    bitsarr = ((codes[:, :, None] >> np.arange(bits)[None, None, :]) & 1).astype(np.uint8)
+    ref = np.packbits(bitsarr.reshape(5, -1), axis=1, bitorder="little")
+    assert (packed == ref).all()
+    assert (oracle.unpack(packed, 64, bits) == codes).all()
+
+
+def test_model_sizes_match_table_1():
+    """Packed bytes = parameters * k / 8 reproduces the size columns of Table 1."""
+    rows = {}
+    with open(os.path.join(GOLDEN, "table1_sizes.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            wb, eb, total, enc = line.split()
+            rows[wb] = (float(total), float(enc))
+    MiB = 2.0 ** 20
+    d, ffn, layers = 768, 3072, 12
+    per_layer_matrix = 4 * d * d + 2 * d * ffn            # quantized matrix elements
+    per_layer_all = per_layer_matrix + (4 * d + ffn + d) + 4 * d  # + biases + 2 LayerNorms
+    assert per_layer_matrix == 7077888 and per_layer_all == 7087872
+    enc_params = layers * per_layer_all
+    assert abs(enc_params * 4 / MiB - rows["32"][1]) < 0.06
+    K = 768
+    for bits in BITS:
+        # bytes of one packed row as the oracle lays it out
+        assert oracle.packed_row_bytes(K, bits) * 8 == K * bits
+        # printed to one decimal; the 2-bit row (20.4 against 20.28) is the loosest
+        assert abs(enc_params * bits / 8 / MiB - rows[str(bits)][1]) < 0.15
+    from paper_1909_05840_amd import workloads
+    for key, table in (("2/3", workloads.PAPER_BITS_2_3), ("2/4", workloads.PAPER_BITS_2_4)):
+        size = sum(per_layer_all * b / 8 for b in table["SST-2"]) / MiB
+        assert abs(size - rows[key][1]) < 0.15
+    emb_8bit = rows["8"][0] - rows["8"][1]
+    for wb in ("4", "3", "2", "2/3", "2/4"):
+        assert abs((rows[wb][0] - rows[wb][1]) - emb_8bit) < 0.11  # every row carries the same 8-bit embedding
+
+
+# ---- P10: brute-force integer product ------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("G", (1, 2, 6))
+def test_integer_product_brute_force(bits, G):
+    T, N, K = 5, 6, 9
+    L = 2 ** bits - 1
+    r = rng(10 + bits)
+    xq = r.integers(-128, 128, (T, K)).astype(np.int8)
+    xq[0, :] = -128
+    xq[1, :] = 127
+    codes = r.integers(0, L + 1, (N, K)).astype(np.uint8)
+    codes[0, :] = L
+    codes[1, :] = 0
+    h = (r.uniform(0.001, 0.01, G)).astype(np.float32)
+    clip = 6.0
+    Y, A4, acc = oracle.qlinear_fwd(xq, clip, codes, h, bits)
+    hx = Fraction(float(np.float32(clip) / np.float32(255)))
+    for t in range(T):
+        for n in range(N):
+            a4 = sum((2 * int(xq[t, j]) + 1) * (2 * int(codes[n, j]) - L) for j in range(K))
+            a = sum(int(xq[t, j]) * (int(codes[n, j]) - 2 ** (bits - 1)) for j in range(K))
+            assert A4[t, n] == a4 and acc[t, n] == a
+            y = hx * Fraction(float(h[n // (N // G)])) * a4
+            assert abs(Fraction(float(Y[t, n])) - y) <= abs(y) * Fraction(1, 2 ** 23)
+    ts = np.array([0, 4, 2], np.int64)
+    ns = np.array([5, 0, 3], np.int64)
+    Ys, A4s = oracle.qlinear_fwd_sampled(xq, clip, codes, h, bits, ts, ns)
+    assert (A4s == A4[ts, ns]).all() and (Ys == Y[ts, ns]).all()
+
+
+# ---- P11: the layer equals a textbook GEMM on the de-quantized operands ----------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_forward_and_backward_equal_fp64_gemm(bits):
+    T, N, K, G = 33, 24, 64, 4
+    W = (rng(20).standard_normal((N, K)) * 0.04).astype(np.float32)
+    X = rng(21).standard_normal((T, K)).astype(np.float32)
+    bias = rng(22).standard_normal(N).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    xq, rs_x = oracle.quantize_act(X, 6.0)
+    What = oracle.dequantize_groupwise(codes, h, bits)
+    Xhat = oracle.dequantize_act(xq, 6.0)
+    Y, A4, acc = oracle.qlinear_fwd(xq, 6.0, codes, h, bits)
+    ref = Xhat @ What.T
+    assert np.abs(Y - ref).max() <= 1e-6 * np.abs(ref).max()
+    assert np.allclose(Y, ref, rtol=1e-6, atol=1e-9)
+    assert (A4 == 4 * acc.astype(np.int64) + 2 * rs_x[:, None] + 2 * rs_w[None, :] + K).all()
+    Yb, _, _ = oracle.qlinear_fwd(xq, 6.0, codes, h, bits, bias=bias)
+    assert np.allclose(Yb, ref + bias[None, :], rtol=1e-6, atol=1e-7)
+    # quantization error of the whole layer is small at 8 bits (sanity of the operand roles)
+    if bits == 8:
+        full = X.astype(np.float64) @ W.astype(np.float64).T
+        assert np.linalg.norm(ref - full) / np.linalg.norm(full) < 0.05
+    # backward: gradients of a plain GEMM
+    dYf = (rng(23).standard_normal((T, N)) * 1e-2).astype(np.float32)
+    dY_bits = (dYf.view(np.uint32) >> 16).astype(np.uint16)  # truncation is a valid bf16 value
+    dY = (dY_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    dX, dW = oracle.qlinear_bwd_ste(dY_bits, xq, 6.0, codes, h, bits)
+    assert np.allclose(dX, dY @ What, rtol=1e-12, atol=1e-15)
+    assert np.allclose(dW, dY.T @ Xhat, rtol=1e-12, atol=1e-15)
+    ts = np.array([0, 32, 7]); js = np.array([63, 0, 11]); ns = np.array([23, 0, 5])
+    assert np.allclose(oracle.bwd_dx_sampled(dY_bits, codes, h, bits, ts, js), dX[ts, js], rtol=1e-12)
+    assert np.allclose(oracle.bwd_dw_sampled(dY_bits, xq, 6.0, ns, js), dW[ns, js], rtol=1e-12)
+    # finite-difference check of the STE reading: d<Y,dY>/dXhat = dX, d<Y,dY>/dWhat = dW
+    eps = 1e-3
+    E = np.zeros_like(Xhat); E[3, 5] = eps
+    num = (((Xhat + E) @ What.T - ref) * dY).sum() / eps
+    assert abs(num - dX[3, 5]) <= 1e-9 + 1e-6 * abs(dX[3, 5])
+
+
+# ---- P12: backward is linear in dY ---------------------------------------------------------------------------------
+def test_backward_linearity():
+    T, N, K = 8, 6, 16
+    r = rng(30)
+    xq = r.integers(-128, 128, (T, K)).astype(np.int8)
+    codes = r.integers(0, 8, (N, K)).astype(np.uint8)
+    h = r.uniform(0.01, 0.02, 2).astype(np.float32)
+
+    def bf(x):  # exact bf16 values: small integers / 64
+        return (np.asarray(x, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    d1 = r.integers(-8, 9, (T, N)) / 64.0
+    d2 = r.integers(-8, 9, (T, N)) / 64.0
+    a = 2.0
+    X1, W1 = oracle.qlinear_bwd_ste(bf(d1), xq, 6.0, codes, h, 3)
+    X2, W2 = oracle.qlinear_bwd_ste(bf(d2), xq, 6.0, codes, h, 3)
+    X3, W3 = oracle.qlinear_bwd_ste(bf(a * d1 + d2), xq, 6.0, codes, h, 3)
+    assert np.allclose(X3, a * X1 + X2, rtol=1e-12, atol=1e-15)
+    assert np.allclose(W3, a * W1 + W2, rtol=1e-12, atol=1e-15)
+
+
+# ---- P13: embedding = weight quantizer on the transposed table; gather = row select -----------------------------------
+def test_embedding_is_weight_grouping_on_transpose():
+    V, d, G = 50, 32, 8
+    E = (rng(40).standard_normal((V, d)) * 0.02).astype(np.float32)
+    codes, h, m = oracle.embedding_quantize(E, G)
+    cT, hT, mT, _ = oracle.quantize_groupwise(np.ascontiguousarray(E.T), 8, G)
+    assert (codes == cT.T).all() and (h == hT).all() and (m == mT).all()
+    cols = d // G
+    for g in range(G):
+        assert m[g] == np.abs(E[:, g * cols:(g + 1) * cols]).max()
+    ids = np.array([3, 3, 49, 0, 17], np.int64)
+    out = oracle.embedding_gather(codes, h, ids)
+    full = oracle.dequantize_groupwise(cT, hT, 8).T
+    assert (out == full[ids]).all()
+    assert np.abs(out - E[ids]).max() <= h.max() * (1 + 1e-6)
+
+
+def test_argument_errors():
+    W = np.zeros((6, 8), np.float32)
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_groupwise(W, 5, 2)
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_groupwise(W, 4, 4)  # 6 rows do not split into 4 groups
+    W[0, 0] = np.nan
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_groupwise(W, 4, 2)
+    with pytest.raises(oracle.OracleError):
+        oracle.quantize_act(np.zeros((2, 2), np.float32), -1.0)
