@@ -1,0 +1,145 @@
+/*
+ * qbert.h -- C ABI of the MI355X (gfx950) library for the group-wise k-bit quantized linear
+ * layer of Q-BERT (arXiv 1909.05840).
+ *
+ * Notation: T tokens (rows of X), K input features, N output neurons, W[N,K] row-major
+ * (one row per output neuron), G groups, k = bits, L = 2^k - 1.
+ *
+ * Conventions that hold for every entry point unless its comment says otherwise
+ *   - Pointers are DEVICE pointers into memory the caller owns; the library allocates nothing,
+ *     keeps no state between calls and is re-entrant.  Base pointers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue
+ *     kernels on it: they never synchronise, never use another stream, and may be captured
+ *     into a HIP graph.
+ *   - Arguments are validated on the host before anything is launched.  On any status other
+ *     than QB_OK nothing has been enqueued and no output has been written.
+ *   - Inputs must be finite (activations may be +-inf, which the clamp removes; NaN is not
+ *     allowed).  Faults on the device are not detected.
+ *   - Matrices are dense row-major.  K must be a multiple of QB_K_ALIGN.
+ */
+#ifndef QBERT_H
+#define QBERT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QB_K_ALIGN 64          /* K (and the embedding dimension d) must be a multiple of this */
+#define QB_N_BLOCK 32          /* packed weights are stored in blocks of this many rows      */
+#define QB_MAX_K 32768         /* keeps |A4| <= 255^2 * K inside int32                       */
+
+typedef enum {
+    QB_OK = 0,
+    QB_ERR_NULL = 1,       /* a required pointer is NULL                                     */
+    QB_ERR_BITS = 2,       /* bits not in {2,3,4,8}                                           */
+    QB_ERR_SHAPE = 3,      /* non-positive dim, K % QB_K_ALIGN != 0, K > QB_MAX_K, N % G != 0  */
+    QB_ERR_CLIP = 4,       /* activation range not a positive finite number                  */
+    QB_ERR_WORKSPACE = 5,  /* workspace NULL or misaligned although the call needs one       */
+    QB_ERR_HIP = 6         /* the HIP runtime refused a launch (hipGetLastError is kept)     */
+} qb_status;
+
+/* Host, pure.  Static string for a status. */
+const char *qb_status_string(qb_status s);
+
+/* Host, pure.  Bytes of the packed weight buffer of an N x K matrix at `bits` bits:
+ * ceil(N / QB_N_BLOCK) * QB_N_BLOCK * K * bits / 8, i.e. exactly N*K*bits/8 (the size
+ * arithmetic behind the paper's Table 1) whenever N is a multiple of QB_N_BLOCK.  Returns 0
+ * for invalid arguments.  The layout inside the buffer is private to the library
+ * (qb_unpack_codes gives the codes back in row-major order). */
+size_t qb_packed_nbytes(int64_t N, int64_t K, int bits);
+
+/* Host, pure.  Bytes of scratch that qb_qlinear_bwd_ste needs for the given shape (the other
+ * calls need none).  Returns 0 for invalid arguments. */
+size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K);
+
+/*
+ * Group-wise symmetric uniform weight quantization and packing.
+ * Paper: Sec. 3.3 (consecutive output neurons share one quantization range; 12 heads x
+ * sub-groups of 6 neurons = 128 groups per matrix, Fig. 3) and App. "Detailed quantization
+ * process" (X' = Clamp(X, q0, q_{2^k-1}); X^I = round((X' - q0)/Delta);
+ * Delta = (q_{2^k-1} - q0)/(2^k - 1)), with the range of group g taken as [-m_g, +m_g],
+ * m_g = max |w| over rows [g*N/G, (g+1)*N/G), and round = round-half-to-even.
+ *   W       in   [N,K] fp32
+ *   packed  out  qb_packed_nbytes(N,K,bits) bytes: the codes u in 0..L
+ *   h       out  [G] fp32, h_g = m_g / L (half of Delta); Q(w) = h_g * (2u - L)
+ *   m       out  [G] fp32, m_g
+ *   rs_w    out  [N] int32, sum over the row of (u - 2^(k-1))
+ * An all-zero group gets m = h = 0 and codes 0.  Requires N % groups == 0.
+ */
+qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int groups,
+                                void *packed, float *h, float *m, int32_t *rs_w, void *stream);
+
+/*
+ * 8-bit activation quantization (Table 1 caption: all models use 8-bit activations; same
+ * appendix formulas with k = 8 and the caller-given range [-clip, +clip]).
+ *   X     in   [T,K] fp32
+ *   Xq    out  [T,K] int8, the code minus 128 (u in 0..255); Q(x) = h_x * (2*Xq + 1),
+ *              h_x = clip / 255 evaluated in fp32
+ *   rs_x  out  [T] int32, sum over the row of Xq
+ */
+qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float clip,
+                          int8_t *Xq, int32_t *rs_x, void *stream);
+
+/*
+ * Forward of the quantized linear layer (App., last paragraph: integer matrix product on the
+ * codes followed by one de-quantization).  With x' = Xq and c' = u - 2^(k-1),
+ *   acc[t,n] = sum_j x'[t,j] * c'[n,j]                       (int8 x int8 -> int32)
+ *   A4[t,n]  = 4*acc + 2*rs_x[t] + 2*rs_w[n] + K  = sum_j (2x'+1)(2c'+1)
+ *   Y[t,n]   = (h_x * h_{g(n)}) * float(A4[t,n])  (+ bias[n])
+ * which is sum_j Q(x)[t,j] * Q(w)[n,j] with the sum taken exactly.
+ *   Xq, rs_x            from qb_quantize_act with the same clip
+ *   packed, h, rs_w     from qb_quantize_groupwise with the same N, K, bits, groups
+ *   bias      in   [N] fp32 or NULL
+ *   Y         out  [T,N] fp32
+ *   A4_debug  out  [T,N] int32 or NULL: the exact integer, for bit-exact checks
+ */
+qb_status qb_qlinear_fwd(const int8_t *Xq, const int32_t *rs_x, float clip,
+                         const void *packed, const float *h, const int32_t *rs_w,
+                         int bits, int groups, int64_t T, int64_t N, int64_t K,
+                         const float *bias, float *Y, int32_t *A4_debug, void *stream);
+
+/*
+ * Straight-through-estimator backward (Sec. 3.1, last paragraph; App., last sentence): both
+ * quantizers pass the gradient through unchanged, so
+ *   dX[t,j] = sum_n dY[t,n] * Q(w)[n,j]        dW[n,j] = sum_t dY[t,n] * Q(x)[t,j]
+ * computed on bf16 matrix cores with fp32 accumulation.
+ *   dY   in   [T,N] bfloat16 (bit patterns)
+ *   dX   out  [T,K] bfloat16 or NULL
+ *   dW   out  [N,K] fp32 or NULL; overwritten, not accumulated into
+ *   workspace  qb_bwd_workspace_nbytes(T,N,K) bytes, 256-byte aligned; contents undefined
+ *              before and after the call
+ */
+qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
+                             const void *packed, const float *h, int bits, int groups,
+                             int64_t T, int64_t N, int64_t K,
+                             uint16_t *dX, float *dW, void *workspace, void *stream);
+
+/* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
+ * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */
+qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits,
+                          uint8_t *codes, void *stream);
+
+/*
+ * 8-bit group-wise embedding table (Sec. 3 "embedding ... 8 bits"; App. "Mixed Precision
+ * Quantization for Embedding": the d output neurons of the embedding are bucketed into
+ * groups).  Group g = columns [g*d/G, (g+1)*d/G) over all V rows; same quantizer, k = 8.
+ *   E      in   [V,d] fp32       codes  out  [V,d] uint8 (u in 0..255)
+ *   h, m   out  [G] fp32
+ * Requires d % groups == 0 and d % QB_K_ALIGN == 0.
+ */
+qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups,
+                                uint8_t *codes, float *h, float *m, void *stream);
+
+/* Lookup with de-quantization: out[i,j] = h[g(j)] * (2*codes[ids[i],j] - 255).
+ *   ids  in  [n_ids] int64, each in [0,V) (not checked: an id outside reads out of bounds)
+ *   out  out [n_ids,d] fp32.   n_ids == 0 is allowed and does nothing. */
+qb_status qb_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int groups,
+                              const int64_t *ids, int64_t n_ids, float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QBERT_H */

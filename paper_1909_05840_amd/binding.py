@@ -1,0 +1,193 @@
+"""ctypes binding of libqbert.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point declared in include/qbert.h and
+takes torch tensors that live on the GPU.  Outputs may be passed in (they are then written in
+place) or are allocated here with torch; every step of the computation runs in the library's
+HIP kernels on torch's current stream.  There is no fallback of any kind: if the shared
+library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqbert.so")
+_lib = None
+
+QB_K_ALIGN = 64
+QB_N_BLOCK = 32
+EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
+           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_bwd_ste", "qb_unpack_codes",
+           "qb_embedding_quantize", "qb_embedding_gather")
+
+
+class QBError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("qbert status %d: %s" % (status, message))
+        self.status = status
+
+
+def load_library():
+    """Load libqbert.so; raises (never substitutes another implementation) if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libqbert.so is not built: run `python -m paper_1909_05840_amd.build` "
+                           "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci, cf = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.qb_status_string.restype = ctypes.c_char_p
+    lib.qb_status_string.argtypes = [ci]
+    lib.qb_packed_nbytes.restype = ctypes.c_size_t
+    lib.qb_packed_nbytes.argtypes = [i64, i64, ci]
+    lib.qb_bwd_workspace_nbytes.restype = ctypes.c_size_t
+    lib.qb_bwd_workspace_nbytes.argtypes = [i64, i64, i64]
+    lib.qb_quantize_groupwise.restype = ci
+    lib.qb_quantize_groupwise.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
+    lib.qb_quantize_act.restype = ci
+    lib.qb_quantize_act.argtypes = [vp, i64, i64, cf, vp, vp, vp]
+    lib.qb_qlinear_fwd.restype = ci
+    lib.qb_qlinear_fwd.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_bwd_ste.restype = ci
+    lib.qb_qlinear_bwd_ste.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_unpack_codes.restype = ci
+    lib.qb_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.qb_embedding_quantize.restype = ci
+    lib.qb_embedding_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    lib.qb_embedding_gather.restype = ci
+    lib.qb_embedding_gather.argtypes = [vp, vp, i64, i64, ci, vp, i64, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise QBError(status, load_library().qb_status_string(status).decode())
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
+    return t
+
+
+def qb_status_string(status):
+    return load_library().qb_status_string(int(status)).decode()
+
+
+def qb_packed_nbytes(N, K, bits):
+    return int(load_library().qb_packed_nbytes(N, K, bits))
+
+
+def qb_bwd_workspace_nbytes(T, N, K):
+    return int(load_library().qb_bwd_workspace_nbytes(T, N, K))
+
+
+def qb_quantize_groupwise(W, bits, groups, packed=None, h=None, m=None, rs_w=None):
+    """W[N,K] fp32 -> (packed uint8 buffer, h[G], m[G], rs_w[N])."""
+    lib = load_library()
+    _dev(W, torch.float32, "W")
+    N, K = W.shape
+    dev = W.device
+    if packed is None:
+        packed = torch.empty(max(qb_packed_nbytes(N, K, bits), 1), dtype=torch.uint8, device=dev)
+    if h is None:
+        h = torch.empty(max(groups, 1), dtype=torch.float32, device=dev)
+    if m is None:
+        m = torch.empty(max(groups, 1), dtype=torch.float32, device=dev)
+    if rs_w is None:
+        rs_w = torch.empty(N, dtype=torch.int32, device=dev)
+    _check(lib.qb_quantize_groupwise(_p(W), N, K, bits, groups, _p(packed), _p(h), _p(m), _p(rs_w), _stream()))
+    return packed, h, m, rs_w
+
+
+def qb_quantize_act(X, clip, Xq=None, rs_x=None):
+    """X[T,K] fp32 -> (Xq[T,K] int8, rs_x[T] int32)."""
+    lib = load_library()
+    _dev(X, torch.float32, "X")
+    T, K = X.shape
+    if Xq is None:
+        Xq = torch.empty((T, K), dtype=torch.int8, device=X.device)
+    if rs_x is None:
+        rs_x = torch.empty(T, dtype=torch.int32, device=X.device)
+    _check(lib.qb_quantize_act(_p(X), T, K, float(clip), _p(Xq), _p(rs_x), _stream()))
+    return Xq, rs_x
+
+
+def qb_qlinear_fwd(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, bias=None, Y=None, A4_debug=None,
+                   want_a4=False):
+    """Integer product + de-quantization. Returns Y[T,N] fp32 (and A4[T,N] int32 if asked)."""
+    lib = load_library()
+    _dev(Xq, torch.int8, "Xq")
+    T, K = Xq.shape
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=Xq.device)
+    if want_a4 and A4_debug is None:
+        A4_debug = torch.empty((T, N), dtype=torch.int32, device=Xq.device)
+    _check(lib.qb_qlinear_fwd(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(h), _p(rs_w), bits, groups,
+                              T, N, K, _p(bias), _p(Y), _p(A4_debug), _stream()))
+    return (Y, A4_debug) if A4_debug is not None else Y
+
+
+def qb_qlinear_bwd_ste(dY, Xq, clip, packed, h, bits, groups, want_dx=True, want_dw=True, dX=None, dW=None,
+                       workspace=None):
+    """dY[T,N] bf16 -> (dX[T,K] bf16 or None, dW[N,K] fp32 or None)."""
+    lib = load_library()
+    _dev(dY, torch.bfloat16, "dY")
+    _dev(Xq, torch.int8, "Xq")
+    T, N = dY.shape
+    K = Xq.shape[1]
+    dev = dY.device
+    if want_dx and dX is None:
+        dX = torch.empty((T, K), dtype=torch.bfloat16, device=dev)
+    if want_dw and dW is None:
+        dW = torch.empty((N, K), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
+    _check(lib.qb_qlinear_bwd_ste(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
+                                  _p(dX), _p(dW), _p(workspace), _stream()))
+    return dX, dW
+
+
+def qb_unpack_codes(packed, N, K, bits, codes=None):
+    lib = load_library()
+    if codes is None:
+        codes = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib.qb_unpack_codes(_p(packed), N, K, bits, _p(codes), _stream()))
+    return codes
+
+
+def qb_embedding_quantize(E, groups, codes=None, h=None, m=None):
+    lib = load_library()
+    _dev(E, torch.float32, "E")
+    V, d = E.shape
+    if codes is None:
+        codes = torch.empty((V, d), dtype=torch.uint8, device=E.device)
+    if h is None:
+        h = torch.empty(max(groups, 1), dtype=torch.float32, device=E.device)
+    if m is None:
+        m = torch.empty(max(groups, 1), dtype=torch.float32, device=E.device)
+    _check(lib.qb_embedding_quantize(_p(E), V, d, groups, _p(codes), _p(h), _p(m), _stream()))
+    return codes, h, m
+
+
+def qb_embedding_gather(codes, h, groups, ids, out=None):
+    lib = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(ids, torch.int64, "ids")
+    V, d = codes.shape
+    n = ids.shape[0]
+    if out is None:
+        out = torch.empty((n, d), dtype=torch.float32, device=codes.device)
+    _check(lib.qb_embedding_gather(_p(codes), _p(h), V, d, groups, _p(ids), n, _p(out), _stream()))
+    return out

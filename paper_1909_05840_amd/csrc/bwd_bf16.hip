@@ -1,0 +1,343 @@
+// Straight-through backward of the group-quantized linear layer on the gfx950 bf16 matrix
+// cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+//   dX[t,j] = sum_n dY[t,n] * What[n,j]     What[n,j] = h_g(n) * (2u[n,j] - L)
+//   dW[n,j] = sum_t dY[t,n] * Xhat[t,j]     Xhat[t,j] = h_x * (2x'[t,j] + 1)
+//
+// Both products are brought to the form C[M,Nc] = sum_k A[M,k] * B[Nc,k] (both operands
+// contiguous along the contraction) by staging operands in the caller's workspace:
+//   WT  [K, Np]   bf16(What) transposed, Np = N rounded up to 64, zero padded
+//   dYp [T, Np]   dY zero padded along n (only when N is not a multiple of 64)
+//   dYT [N, Tp]   dY transposed, Tp = T rounded up to 64, zero padded
+//   XT  [K, Tp]   (2x'+1) transposed; |2x'+1| <= 255 is exact in bf16, h_x goes to the epilogue
+// dW splits the long contraction over T across workgroups; partial sums are written to the
+// workspace and added in a fixed order, so results do not change from run to run.
+#include "qb_common.hpp"
+
+namespace qb {
+namespace {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+// packed slots -> WT[j][n] = bf16(h_g * (2u - L)); one thread per (n, 32-code run); n < Np
+template <int BITS>
+__global__ __launch_bounds__(256) void dequant_transpose_kernel(const uint8_t *__restrict__ packed,
+                                                                const float *__restrict__ h, int N, int Np, int K,
+                                                                int rows_per_group, uint16_t *__restrict__ WT)
+{
+    const int runs = K >> 5;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)Np * runs) return;
+    const int rc = (int)(id / Np), n = (int)(id % Np);  // consecutive threads: consecutive n
+    uint16_t *dst = WT + (size_t)(rc * 32) * Np + n;
+    if (n >= N) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) dst[(size_t)i * Np] = 0;
+        return;
+    }
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(packed + slot_index(n, rc, K) * (size_t)(4 * BITS));
+    uint32_t in[BITS], d[8];
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) in[i] = src[i];
+    unpack_run<BITS>(in, d);
+    const float hg = h[n / rows_per_group];
+    constexpr int L = (1 << BITS) - 1;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const int u = (int)((d[i >> 2] >> (8 * (i & 3))) & 255u);
+        dst[(size_t)i * Np] = f32_to_bf16_rne(hg * (float)(2 * u - L));
+    }
+}
+
+// out[c][r] = conv(in[r][c]) for r < R, c < C; out has leading dimension ldo >= R, columns
+// r in [R, ldo) are zero filled.  MODE 0: bf16 copy, MODE 1: int8 x' -> bf16(2x'+1).
+template <int MODE>
+__global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__ in, int R, int C, int ldo,
+                                                        uint16_t *__restrict__ out)
+{
+    __shared__ uint16_t tile[64][66];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int r = r0 + i, c = c0 + tx;
+        uint16_t v = 0;
+        if (r < R && c < C) {
+            if (MODE == 0) {
+                v = static_cast<const uint16_t *>(in)[(size_t)r * C + c];
+            } else {
+                const int x = static_cast<const int8_t *>(in)[(size_t)r * C + c];
+                v = (uint16_t)(__float_as_uint((float)(2 * x + 1)) >> 16);  // exact: 8 significant bits
+            }
+        }
+        tile[i][tx] = v;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i, r = r0 + tx;
+        if (c < C && r < ldo) out[(size_t)c * ldo + r] = tile[tx][i];
+    }
+}
+
+// dYp[t][n] = dY[t][n] for n < N, 0 for N <= n < Np
+__global__ __launch_bounds__(256) void pad_rows_kernel(const uint16_t *__restrict__ in, int64_t T, int N, int Np,
+                                                       uint16_t *__restrict__ out)
+{
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= T * Np) return;
+    const int64_t t = id / Np;
+    const int n = (int)(id % Np);
+    out[id] = n < N ? in[t * N + n] : (uint16_t)0;
+}
+
+// C[M,Nc] = sum_k A[M,k] * B[Nc,k]; A, B bf16 row-major with leading dimensions lda, ldb
+// (multiples of 8), contraction range [z*ksplit, min(Kc, (z+1)*ksplit)) for blockIdx.y = z,
+// Kc and ksplit multiples of 64.  OUT 0: bf16 C (ldc = Nc);  OUT 1: fp32 C * scale;
+// OUT 2: fp32 partial sums at part + z*M*Nc.
+template <int TM, int TN, int WM, int WN, int OUT>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_nt_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int Nc, int Kc, int lda, int ldb,
+    int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n)
+{
+    constexpr int THREADS = 64 * WM * WN;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BKB = 128, LD = BKB + 16;  // 64 bf16 per step
+    constexpr int A_PER_THREAD = BM * 8 / THREADS, B_PER_THREAD = BN * 8 / THREADS;
+    static_assert(BM * 8 % THREADS == 0 && BN * 8 % THREADS == 0, "tiles must split evenly");
+    __shared__ __align__(16) uint8_t lds_a[2][BM * LD];
+    __shared__ __align__(16) uint8_t lds_b[2][BN * LD];
+
+    const int nwg = tiles_m * tiles_n;
+    int logical;
+    {
+        const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
+        const int q = nwg >> 3, r = nwg & 7;
+        logical = xcd * q + (xcd < r ? xcd : r) + idx;
+    }
+    const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+    const int z = blockIdx.y;
+    const int k_begin = z * ksplit;
+    const int k_end = (k_begin + ksplit < Kc) ? k_begin + ksplit : Kc;
+    const int nsteps = (k_end - k_begin) >> 6;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int l32 = lane & 31, hf = lane >> 5;
+
+    const uint8_t *a_src[A_PER_THREAD], *b_src[B_PER_THREAD];
+    int a_dst[A_PER_THREAD], b_dst[B_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        const int c = tid + i * THREADS, row = c >> 3, kc = c & 7;
+        int r = tile_m * BM + row;
+        r = r < M ? r : M - 1;
+        a_src[i] = reinterpret_cast<const uint8_t *>(A + (size_t)r * lda + k_begin) + kc * 16;
+        a_dst[i] = row * LD + kc * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER_THREAD; ++i) {
+        const int c = tid + i * THREADS, row = c >> 3, kc = c & 7;
+        int r = tile_n * BN + row;
+        r = r < Nc ? r : Nc - 1;
+        b_src[i] = reinterpret_cast<const uint8_t *>(B + (size_t)r * ldb + k_begin) + kc * 16;
+        b_dst[i] = row * LD + kc * 16;
+    }
+
+    v16f acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.0f;
+
+    uint4 areg[A_PER_THREAD], breg[B_PER_THREAD];
+    auto load_global = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) areg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + (size_t)step * BKB);
+#pragma unroll
+        for (int i = 0; i < B_PER_THREAD; ++i) breg[i] = *reinterpret_cast<const uint4 *>(b_src[i] + (size_t)step * BKB);
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) *reinterpret_cast<uint4 *>(&lds_a[buf][a_dst[i]]) = areg[i];
+#pragma unroll
+        for (int i = 0; i < B_PER_THREAD; ++i) *reinterpret_cast<uint4 *>(&lds_b[buf][b_dst[i]]) = breg[i];
+    };
+
+    if (nsteps > 0) {
+        load_global(0);
+        store_lds(0);
+    }
+    __syncthreads();
+    const int a_base = (wm * TM * 32 + l32) * LD + hf * 16;
+    const int b_base = (wn * TN * 32 + l32) * LD + hf * 16;
+    for (int s = 0; s < nsteps; ++s) {
+        if (s + 1 < nsteps) load_global(s + 1);
+        const uint8_t *pa = lds_a[s & 1], *pb = lds_b[s & 1];
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+            v8bf a[TM], b[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) a[tm] = *reinterpret_cast<const v8bf *>(pa + a_base + tm * 32 * LD + sub * 32);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) b[tn] = *reinterpret_cast<const v8bf *>(pb + b_base + tn * 32 * LD + sub * 32);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+        }
+        if (s + 1 < nsteps) store_lds((s + 1) & 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = r0 + 8 * (i >> 2) + (i & 3);
+                if (r < M && n < Nc) {
+                    const size_t at = (size_t)r * Nc + n;
+                    if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][tn][i]);
+                    else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][tn][i] * scale;
+                    else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][tn][i];
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int64_t n, int splits,
+                                                              float scale, float *__restrict__ out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.0f;
+    for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
+    out[i] = s * scale;
+}
+
+template <int OUT>
+void launch_gemm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
+                 float scale, void *C, hipStream_t st)
+{
+    const long big = (long)((M + 255) / 256) * ((Nc + 127) / 128) * splits;
+    if (big >= 192) {
+        const int tm = (M + 255) / 256, tn = (Nc + 127) / 128;
+        hipLaunchKernelGGL((gemm_bf16_nt_kernel<4, 2, 2, 2, OUT>), dim3(tm * tn, splits), dim3(256), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn);
+    } else {
+        const int tm = (M + 127) / 128, tn = (Nc + 127) / 128;
+        hipLaunchKernelGGL((gemm_bf16_nt_kernel<2, 2, 2, 2, OUT>), dim3(tm * tn, splits), dim3(256), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn);
+    }
+}
+
+struct BwdPlan {
+    int64_t Np, Tp;
+    int splits, ksplit;
+    size_t off_wt, off_dyp, off_dyt, off_xt, off_part, total;
+};
+
+BwdPlan make_plan(int64_t T, int64_t N, int64_t K)
+{
+    BwdPlan p;
+    p.Np = round_up(N, 64);
+    p.Tp = round_up(T, 64);
+    // split the contraction over T so that about 512 workgroups exist, at least 256 rows each
+    const int64_t tiles = ((N + 127) / 128) * ((K + 127) / 128);
+    int64_t s = (512 + tiles - 1) / tiles;
+    const int64_t max_s = (p.Tp + 255) / 256;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    p.ksplit = (int)round_up((p.Tp + s - 1) / s, 64);
+    p.splits = (int)((p.Tp + p.ksplit - 1) / p.ksplit);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+    p.off_wt = take((size_t)K * p.Np * 2);
+    p.off_dyp = take(N % 64 ? (size_t)T * p.Np * 2 : 0);
+    p.off_dyt = take((size_t)N * p.Tp * 2);
+    p.off_xt = take((size_t)K * p.Tp * 2);
+    p.off_part = take(p.splits > 1 ? (size_t)p.splits * N * K * 4 : 0);
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+}  // namespace qb
+
+using namespace qb;
+
+extern "C" size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K)
+{
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K)) return 0;
+    return make_plan(T, N, K).total;
+}
+
+extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
+                                        const float *h, int bits, int groups, int64_t T, int64_t N, int64_t K,
+                                        uint16_t *dX, float *dW, void *workspace, void *stream)
+{
+    if (!dY || !Xq || !packed || !h) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0)
+        return QB_ERR_SHAPE;
+    if (!(clip > 0.0f) || !(clip < 3.0e38f)) return QB_ERR_CLIP;
+    if (!dX && !dW) return QB_OK;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return QB_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const BwdPlan p = make_plan(T, N, K);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const int rpg = (int)(N / groups);
+    const int Np = (int)p.Np, Tp = (int)p.Tp;
+
+    if (dX) {
+        uint16_t *WT = reinterpret_cast<uint16_t *>(ws + p.off_wt);
+        const uint8_t *pk = static_cast<const uint8_t *>(packed);
+        const unsigned blocks = (unsigned)(((int64_t)Np * (K / 32) + 255) / 256);
+        switch (bits) {
+            case 2: hipLaunchKernelGGL(dequant_transpose_kernel<2>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
+            case 3: hipLaunchKernelGGL(dequant_transpose_kernel<3>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
+            case 4: hipLaunchKernelGGL(dequant_transpose_kernel<4>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
+            default: hipLaunchKernelGGL(dequant_transpose_kernel<8>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
+        }
+        const uint16_t *Aop = dY;
+        if (N % 64) {
+            uint16_t *dYp = reinterpret_cast<uint16_t *>(ws + p.off_dyp);
+            hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((T * Np + 255) / 256)), dim3(256), 0, st, dY, T, (int)N, Np, dYp);
+            Aop = dYp;
+        }
+        launch_gemm<0>(Aop, WT, (int)T, (int)K, Np, Np, Np, 1, Np, 1.0f, dX, st);
+    }
+    if (dW) {
+        uint16_t *dYT = reinterpret_cast<uint16_t *>(ws + p.off_dyt);
+        uint16_t *XT = reinterpret_cast<uint16_t *>(ws + p.off_xt);
+        hipLaunchKernelGGL(transpose_kernel<0>, dim3((unsigned)(Tp / 64), (unsigned)((N + 63) / 64)), dim3(256), 0, st,
+                           static_cast<const void *>(dY), (int)T, (int)N, Tp, dYT);
+        hipLaunchKernelGGL(transpose_kernel<1>, dim3((unsigned)(Tp / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, st,
+                           static_cast<const void *>(Xq), (int)T, (int)K, Tp, XT);
+        const float hx = clip / 255.0f;
+        if (p.splits > 1) {
+            float *part = reinterpret_cast<float *>(ws + p.off_part);
+            launch_gemm<2>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, p.splits, p.ksplit, 1.0f, part, st);
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((N * K + 255) / 256)), dim3(256), 0, st, part,
+                               N * K, p.splits, hx, dW);
+        } else {
+            launch_gemm<1>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, 1, Tp, hx, dW, st);
+        }
+    }
+    return launch_status();
+}

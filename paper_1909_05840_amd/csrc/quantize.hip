@@ -1,0 +1,439 @@
+// Quantize / pack kernels for gfx950: group-wise k-bit weights, 8-bit activations, the
+// unpack test hook and the 8-bit column-grouped embedding table.
+//
+// All of them are bound by HBM traffic.  The weight kernel therefore reads each fp32 weight
+// from memory exactly once: one workgroup owns one group (a contiguous block of N/G rows),
+// keeps it in registers between the max-abs reduction and the quantization, and routes the
+// codes through LDS only to regroup them into the 32-code slots of the packed layout.
+//
+// Every floating-point step that decides a code is a single correctly rounded binary32
+// operation (add, divide, round-half-even), in the order the paper's appendix gives them
+// (X' - q0, / Delta, round), so the codes do not depend on how the work is split over lanes.
+#include "qb_common.hpp"
+
+namespace qb {
+namespace {
+
+// (w - q0)/Delta rounded half-to-even and clamped to 0..L; q0 = -m.  `delta` must be non-zero
+// (callers pass 1 for an all-zero group, which yields code 0 because w + m = 0).
+__device__ __forceinline__ uint32_t quantize_code(float w, float m, float delta, float Lf)
+{
+    const float s = __fadd_rn(w, m);
+    const float t = __fdiv_rn(s, delta);
+    float r = rintf(t);
+    r = fminf(fmaxf(r, 0.0f), Lf);
+    return (uint32_t)r;
+}
+
+__device__ __forceinline__ uint32_t quantize4(const float4 v, float m, float delta, float Lf)
+{
+    return quantize_code(v.x, m, delta, Lf) | (quantize_code(v.y, m, delta, Lf) << 8) |
+           (quantize_code(v.z, m, delta, Lf) << 16) | (quantize_code(v.w, m, delta, Lf) << 24);
+}
+
+__device__ __forceinline__ float absmax4(const float4 v, float mx)
+{
+    return fmaxf(fmaxf(fmaxf(mx, fabsf(v.x)), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
+}
+
+// floor(e / d) for 0 <= e < 2^22 without an integer divide; inv = 1/d rounded.
+__device__ __forceinline__ int fast_div(int e, int d, float inv)
+{
+    int q = (int)((float)e * inv);
+    if ((q + 1) * d <= e) ++q;
+    if (q * d > e) --q;
+    return q;
+}
+
+// One workgroup quantizes and packs a panel of `prow` consecutive rows that lie inside one
+// group.  FUSED: the panel is the whole group, max-abs is found here and m/h are written.
+// Otherwise m was found by absmax_slices_kernel and only the panel starting a group writes h.
+// LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then THREADS/64 floats.
+template <int BITS, int THREADS, int V, bool FUSED>
+__global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
+    const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
+    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int stride = K + 16;
+    int *rowsum = reinterpret_cast<int *>(smem + (size_t)prow * stride);
+    float *red = reinterpret_cast<float *>(rowsum + prow);
+
+    const int row0 = blockIdx.x * prow;  // first row of the panel
+    const int g = row0 / rows_per_group;
+    const float4 *src = reinterpret_cast<const float4 *>(W + (size_t)row0 * K);
+    const int n4 = prow * (K >> 2);
+    constexpr float Lf = (float)((1 << BITS) - 1);
+
+    float4 v[V];
+    float mx = 0.0f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int idx = tid + i * THREADS;
+        if (idx < n4) {
+            v[i] = src[idx];
+            if (FUSED) mx = absmax4(v[i], mx);
+        }
+    }
+    for (int r = tid; r < prow; r += THREADS) rowsum[r] = 0;
+
+    float mg;
+    if (FUSED) {
+        mx = wave_max(mx);
+        if ((tid & 63) == 0) red[tid >> 6] = mx;
+        __syncthreads();
+        mg = red[0];
+#pragma unroll
+        for (int w = 1; w < THREADS / 64; ++w) mg = fmaxf(mg, red[w]);
+    } else {
+        mg = m[g];
+        __syncthreads();
+    }
+    const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, Lf);
+    const float delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;
+    if (tid == 0 && row0 % rows_per_group == 0) {
+        h[g] = hg;
+        if (FUSED) m[g] = mg;
+    }
+
+    // codes, four per dword, into the LDS image of the panel
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int idx = tid + i * THREADS;
+        if (idx < n4) {
+            const int e = idx << 2;
+            const int r = fast_div(e, K, inv_K);
+            const int c = e - r * K;
+            *reinterpret_cast<uint32_t *>(smem + (size_t)r * stride + c) = quantize4(v[i], mg, delta, Lf);
+        }
+    }
+    __syncthreads();
+
+    // regroup into 32-code slots; consecutive threads take consecutive rows of one column run
+    const int nruns = prow * (K >> 5);
+    for (int id = tid; id < nruns; id += THREADS) {
+        const int rc = fast_div(id, prow, inv_prow);
+        const int r = id - rc * prow;
+        const uint4 lo = *reinterpret_cast<const uint4 *>(smem + (size_t)r * stride + rc * 32);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(smem + (size_t)r * stride + rc * 32 + 16);
+        const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        uint32_t sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum = __builtin_amdgcn_sad_u8(d[i], 0u, sum);
+        atomicAdd(&rowsum[r], (int)sum);
+        uint32_t out[BITS];
+        pack_run<BITS>(d, out);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(packed + slot_index(row0 + r, rc, K) * (size_t)(4 * BITS));
+        if constexpr (BITS == 8) {
+            reinterpret_cast<uint4 *>(dst)[0] = make_uint4(out[0], out[1], out[2], out[3]);
+            reinterpret_cast<uint4 *>(dst)[1] = make_uint4(out[4], out[5], out[6], out[7]);
+        } else if constexpr (BITS == 4) {
+            reinterpret_cast<uint4 *>(dst)[0] = make_uint4(out[0], out[1], out[2], out[3]);
+        } else if constexpr (BITS == 2) {
+            reinterpret_cast<uint2 *>(dst)[0] = make_uint2(out[0], out[1]);
+        } else {
+            dst[0] = out[0];
+            dst[1] = out[1];
+            dst[2] = out[2];
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < prow; r += THREADS) rs_w[row0 + r] = rowsum[r] - K * (1 << (BITS - 1));
+}
+
+// Two-pass path for groups too large for one workgroup's registers: slices of a group reduce
+// |w| and combine through an integer atomic max on the bit pattern (order-preserving for
+// non-negative floats).  m must have been zero-filled.
+__global__ __launch_bounds__(256) void absmax_slices_kernel(const float *__restrict__ W, int64_t group_elems,
+                                                            int slices, float *__restrict__ m)
+{
+    __shared__ float red[4];
+    const int g = blockIdx.x / slices, s = blockIdx.x % slices;
+    const int64_t n4 = group_elems >> 2;
+    const int64_t per = (n4 + slices - 1) / slices;
+    const int64_t lo = (int64_t)s * per, hi = (lo + per < n4) ? lo + per : n4;
+    const float4 *src = reinterpret_cast<const float4 *>(W + (int64_t)g * group_elems);
+    float mx = 0.0f;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 256) mx = absmax4(src[i], mx);
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        atomicMax(reinterpret_cast<unsigned int *>(m) + g, __float_as_uint(mx));
+    }
+}
+
+__global__ void fill_zero_kernel(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// ---- activations: one wavefront per token row -----------------------------------------------------
+__global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restrict__ X, int T, int K, float clip,
+                                                           float delta, int8_t *__restrict__ Xq,
+                                                           int32_t *__restrict__ rs_x)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= T) return;
+    const float4 *src = reinterpret_cast<const float4 *>(X + (size_t)row * K);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(Xq + (size_t)row * K);
+    const int k4 = K >> 2;
+    uint32_t sum = 0;
+    for (int base = 0; base < k4; base += 256) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * 64 + lane;
+            if (idx < k4) v[u] = src[idx];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * 64 + lane;
+            if (idx < k4) {
+                float4 c = v[u];
+                c.x = fminf(fmaxf(c.x, -clip), clip);
+                c.y = fminf(fmaxf(c.y, -clip), clip);
+                c.z = fminf(fmaxf(c.z, -clip), clip);
+                c.w = fminf(fmaxf(c.w, -clip), clip);
+                const uint32_t q = quantize4(c, clip, delta, 255.0f);
+                sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
+                dst[idx] = q ^ 0x80808080u;  // u - 128 as int8
+            }
+        }
+    }
+    const int total = wave_sum((int)sum);
+    if (lane == 0) rs_x[row] = total - 128 * K;
+}
+
+// ---- test hook: slots -> row-major codes -----------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(256) void unpack_codes_kernel(const uint8_t *__restrict__ packed, int N, int K,
+                                                           uint8_t *__restrict__ codes)
+{
+    const int runs = K >> 5;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)N * runs) return;
+    const int n = (int)(id / runs), rc = (int)(id % runs);
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(packed + slot_index(n, rc, K) * (size_t)(4 * BITS));
+    uint32_t in[BITS], d[8];
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) in[i] = src[i];
+    unpack_run<BITS>(in, d);
+    uint4 *dst = reinterpret_cast<uint4 *>(codes + (size_t)n * K + rc * 32);
+    dst[0] = make_uint4(d[0], d[1], d[2], d[3]);
+    dst[1] = make_uint4(d[4], d[5], d[6], d[7]);
+}
+
+// ---- embedding table: groups are column blocks --------------------------------------------------------
+// pass 1: each thread owns four columns and walks a slice of the rows; m zero-filled before.
+__global__ __launch_bounds__(256) void embedding_absmax_kernel(const float *__restrict__ E, int64_t V, int d,
+                                                               int cols_per_group, int rows_per_block,
+                                                               float *__restrict__ m)
+{
+    const int d4 = d >> 2;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r1 = (r0 + rows_per_block < V) ? r0 + rows_per_block : V;
+    for (int c4 = blockIdx.x * 256 + threadIdx.x; c4 < d4; c4 += gridDim.x * 256) {
+        const float4 *src = reinterpret_cast<const float4 *>(E) + c4;
+        float4 mx = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int64_t r = r0; r < r1; ++r) {
+            const float4 v = src[r * d4];
+            mx.x = fmaxf(mx.x, fabsf(v.x));
+            mx.y = fmaxf(mx.y, fabsf(v.y));
+            mx.z = fmaxf(mx.z, fabsf(v.z));
+            mx.w = fmaxf(mx.w, fabsf(v.w));
+        }
+        unsigned int *mb = reinterpret_cast<unsigned int *>(m);
+        const int c = c4 << 2;
+        const int lanes_per_group = cols_per_group >> 2;
+        if ((cols_per_group & 3) == 0 && lanes_per_group <= 64 && (lanes_per_group & (lanes_per_group - 1)) == 0 &&
+            d4 % 64 == 0) {
+            // the four columns and lanes_per_group neighbouring lanes share one group: combine first
+            float v = fmaxf(fmaxf(mx.x, mx.y), fmaxf(mx.z, mx.w));
+            for (int o = 1; o < lanes_per_group; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+            if ((threadIdx.x & (lanes_per_group - 1)) == 0) atomicMax(mb + c / cols_per_group, __float_as_uint(v));
+        } else {
+            atomicMax(mb + (c + 0) / cols_per_group, __float_as_uint(mx.x));
+            atomicMax(mb + (c + 1) / cols_per_group, __float_as_uint(mx.y));
+            atomicMax(mb + (c + 2) / cols_per_group, __float_as_uint(mx.z));
+            atomicMax(mb + (c + 3) / cols_per_group, __float_as_uint(mx.w));
+        }
+    }
+}
+
+// pass 2: codes, and h = m/255
+__global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__restrict__ E, int64_t V, int d,
+                                                                 int cols_per_group, int groups,
+                                                                 const float *__restrict__ m, float *__restrict__ h,
+                                                                 uint8_t *__restrict__ codes)
+{
+    const int64_t n4 = V * (int64_t)(d >> 2);
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id < groups) {
+        const float mg = m[id];
+        h[id] = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
+    }
+    if (id >= n4) return;
+    const int c = (int)(id % (d >> 2)) << 2;
+    const float4 v = reinterpret_cast<const float4 *>(E)[id];
+    float mg, delta;
+    uint32_t q;
+    group_scale(m, (c + 0) / cols_per_group, mg, delta);
+    q = quantize_code(v.x, mg, delta, 255.0f);
+    group_scale(m, (c + 1) / cols_per_group, mg, delta);
+    q |= quantize_code(v.y, mg, delta, 255.0f) << 8;
+    group_scale(m, (c + 2) / cols_per_group, mg, delta);
+    q |= quantize_code(v.z, mg, delta, 255.0f) << 16;
+    group_scale(m, (c + 3) / cols_per_group, mg, delta);
+    q |= quantize_code(v.w, mg, delta, 255.0f) << 24;
+    reinterpret_cast<uint32_t *>(codes)[id] = q;
+}
+
+__global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__restrict__ codes,
+                                                               const float *__restrict__ h, int64_t V, int d,
+                                                               int cols_per_group, const int64_t *__restrict__ ids,
+                                                               int64_t n_ids, float *__restrict__ out)
+{
+    const int d4 = d >> 2;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= n_ids * d4) return;
+    const int64_t i = id / d4;
+    const int c = (int)(id % d4) << 2;
+    const int64_t tok = ids[i];
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tok >= 0 && tok < V) {
+        const uint32_t q = *reinterpret_cast<const uint32_t *>(codes + tok * d + c);
+        o.x = h[(c + 0) / cols_per_group] * (float)(2 * (int)(q & 255u) - 255);
+        o.y = h[(c + 1) / cols_per_group] * (float)(2 * (int)((q >> 8) & 255u) - 255);
+        o.z = h[(c + 2) / cols_per_group] * (float)(2 * (int)((q >> 16) & 255u) - 255);
+        o.w = h[(c + 3) / cols_per_group] * (float)(2 * (int)(q >> 24) - 255);
+    }
+    reinterpret_cast<float4 *>(out)[id] = o;
+}
+
+constexpr int kMaxFusedElems = 256 * 4 * 32;  // one group in the registers of 256 threads
+
+template <int BITS, int V, bool FUSED>
+void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h,
+                  float *m, int32_t *rs_w, hipStream_t st)
+{
+    const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 16;
+    hipLaunchKernelGGL((quantize_panel_kernel<BITS, 256, V, FUSED>), dim3(panels), dim3(256), lds, st, W, K,
+                       rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w);
+}
+
+template <int BITS, bool FUSED>
+void launch_panel_v(int elems, const float *W, int K, int rpg, int prow, int panels, uint8_t *packed, float *h,
+                    float *m, int32_t *rs_w, hipStream_t st)
+{
+    const int need = (elems / 4 + 255) / 256;  // float4 per thread
+    if (need <= 2) launch_panel<BITS, 2, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
+    else if (need <= 4) launch_panel<BITS, 4, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
+    else if (need <= 8) launch_panel<BITS, 8, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
+    else if (need <= 16) launch_panel<BITS, 16, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
+    else launch_panel<BITS, 32, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
+}
+
+template <int BITS>
+qb_status quantize_groupwise_impl(const float *W, int64_t N, int64_t K, int groups, uint8_t *packed, float *h,
+                                  float *m, int32_t *rs_w, hipStream_t st)
+{
+    const int rpg = (int)(N / groups);
+    const int64_t gelems = (int64_t)rpg * K;
+    if (gelems <= kMaxFusedElems) {
+        launch_panel_v<BITS, true>((int)gelems, W, (int)K, rpg, rpg, groups, packed, h, m, rs_w, st);
+        return launch_status();
+    }
+    // large groups: max-abs by slices, then panels of whole rows that divide the group
+    int prow = 1;
+    for (int p = rpg; p >= 1; --p)
+        if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
+    const int slices = (int)((gelems + 65535) / 65536);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, m, groups);
+    hipLaunchKernelGGL(absmax_slices_kernel, dim3(groups * slices), dim3(256), 0, st, W, gelems, slices, m);
+    launch_panel_v<BITS, false>((int)(prow * K), W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace qb
+
+using namespace qb;
+
+extern "C" qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int groups, void *packed,
+                                           float *h, float *m, int32_t *rs_w, void *stream)
+{
+    if (!W || !packed || !h || !m || !rs_w) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *p = static_cast<uint8_t *>(packed);
+    switch (bits) {
+        case 2: return quantize_groupwise_impl<2>(W, N, K, groups, p, h, m, rs_w, st);
+        case 3: return quantize_groupwise_impl<3>(W, N, K, groups, p, h, m, rs_w, st);
+        case 4: return quantize_groupwise_impl<4>(W, N, K, groups, p, h, m, rs_w, st);
+        default: return quantize_groupwise_impl<8>(W, N, K, groups, p, h, m, rs_w, st);
+    }
+}
+
+extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float clip, int8_t *Xq, int32_t *rs_x,
+                                     void *stream)
+{
+    if (!X || !Xq || !rs_x) return QB_ERR_NULL;
+    if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
+    if (!(clip > 0.0f) || !(clip < 3.0e38f)) return QB_ERR_CLIP;
+    const float hx = clip / 255.0f;
+    hipLaunchKernelGGL(quantize_act_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), X, (int)T, (int)K, clip, 2.0f * hx, Xq, rs_x);
+    return launch_status();
+}
+
+extern "C" qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits, uint8_t *codes, void *stream)
+{
+    if (!packed || !codes) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (N <= 0 || N > (1 << 24) || !k_ok(K)) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    const unsigned blocks = (unsigned)((N * (K / 32) + 255) / 256);
+    switch (bits) {
+        case 2: hipLaunchKernelGGL(unpack_codes_kernel<2>, dim3(blocks), dim3(256), 0, st, p, (int)N, (int)K, codes); break;
+        case 3: hipLaunchKernelGGL(unpack_codes_kernel<3>, dim3(blocks), dim3(256), 0, st, p, (int)N, (int)K, codes); break;
+        case 4: hipLaunchKernelGGL(unpack_codes_kernel<4>, dim3(blocks), dim3(256), 0, st, p, (int)N, (int)K, codes); break;
+        default: hipLaunchKernelGGL(unpack_codes_kernel<8>, dim3(blocks), dim3(256), 0, st, p, (int)N, (int)K, codes); break;
+    }
+    return launch_status();
+}
+
+extern "C" qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups, uint8_t *codes, float *h,
+                                           float *m, void *stream)
+{
+    if (!E || !codes || !h || !m) return QB_ERR_NULL;
+    if (V <= 0 || V > (1 << 30) || !k_ok(d) || groups <= 0 || d % groups != 0) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int cpg = (int)(d / groups);
+    const int rows_per_block = 128;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, m, groups);
+    hipLaunchKernelGGL(embedding_absmax_kernel, dim3((unsigned)((d / 4 + 255) / 256), (unsigned)((V + rows_per_block - 1) / rows_per_block)),
+                       dim3(256), 0, st, E, V, (int)d, cpg, rows_per_block, m);
+    const int64_t n4 = V * (d / 4);
+    hipLaunchKernelGGL(embedding_quantize_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, E, V, (int)d, cpg,
+                       groups, m, h, codes);
+    return launch_status();
+}
+
+extern "C" qb_status qb_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int groups,
+                                         const int64_t *ids, int64_t n_ids, float *out, void *stream)
+{
+    if (!codes || !h || (n_ids > 0 && (!ids || !out))) return QB_ERR_NULL;
+    if (V <= 0 || !k_ok(d) || groups <= 0 || d % groups != 0 || n_ids < 0 || n_ids > (1 << 30)) return QB_ERR_SHAPE;
+    if (n_ids == 0) return QB_OK;
+    const int64_t n4 = n_ids * (d / 4);
+    hipLaunchKernelGGL(embedding_gather_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), codes, h, V, (int)d, (int)(d / groups), ids, n_ids, out);
+    return launch_status();
+}
