@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the group-quantized linear hot path on one MI355X.
+
+Workload (benchmark configs[1]): the four linears of one BERT-base encoder layer
+(QKV 768->2304, out 768->768, FFN 768->3072, 3072->768) on 32x128 = 4096 tokens, 128 groups per
+matrix, weight bit-widths {2,3,4,8}, forward only, synthetic seeded data.
+
+One step = one pass of the forward hot path over that batch for every bit-width of the sweep:
+  16 x quantize/pack of the fp32 master weights, 4 x 8-bit activation quantize,
+  16 x int8 MFMA GEMM with the scale epilogue.
+All inputs are resident in HBM before the timed region.  `value` = int8 GEMM operations of the
+step (2*T*N*K summed) divided by the wall time of the whole step, in TOPS.
+
+The three stages of a step are enqueued as three captured HIP graphs (they hold kernels only)
+separated by HIP events on the launch stream, so the per-kernel averages in `roofline` and
+`kernels` come from the timed region itself.  --no-graph launches every kernel eagerly.
+
+Also printed on the same JSON line: the STE backward (configs[2]) and the embedding path
+(configs[4]) timed outside the K steps, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+T_TOKENS = 4096
+GROUPS = 128
+CLIP = 6.0
+BITS_SWEEP = (2, 3, 4, 8)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1909_05840_amd as qb
+    from paper_1909_05840_amd import workloads as wl
+
+    qb.load_library()   # raises if the HIP library is not built: there is no other path
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    linears = wl.BERT_BASE_LINEARS
+    T = T_TOKENS
+
+    # ---- inputs, resident in HBM ---------------------------------------------------------------
+    Ws = [wl.weight(N, K, seed=wl.config_seed(1, i)).to(dev) for i, (_, N, K) in enumerate(linears)]
+    Xs = [wl.activation(T, K, seed=wl.config_seed(1, 10 + i)).to(dev) for i, (_, N, K) in enumerate(linears)]
+    # ---- outputs, allocated once -----------------------------------------------------------------
+    q = {}
+    for b in BITS_SWEEP:
+        for i, (_, N, K) in enumerate(linears):
+            q[(b, i)] = dict(packed=torch.empty(qb.qb_packed_nbytes(N, K, b), dtype=torch.uint8, device=dev),
+                             h=torch.empty(GROUPS, dtype=torch.float32, device=dev),
+                             m=torch.empty(GROUPS, dtype=torch.float32, device=dev),
+                             rs_w=torch.empty(N, dtype=torch.int32, device=dev))
+    acts = [dict(Xq=torch.empty((T, K), dtype=torch.int8, device=dev),
+                 rs_x=torch.empty(T, dtype=torch.int32, device=dev)) for (_, N, K) in linears]
+    Ys = [torch.empty((T, N), dtype=torch.float32, device=dev) for (_, N, K) in linears]
+
+    def stage_quantize():
+        for b in BITS_SWEEP:
+            for i in range(len(linears)):
+                o = q[(b, i)]
+                qb.qb_quantize_groupwise(Ws[i], b, GROUPS, o["packed"], o["h"], o["m"], o["rs_w"])
+
+    def stage_act():
+        for i in range(len(linears)):
+            qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
+
+    def stage_gemm():
+        for b in BITS_SWEEP:
+            for i, (_, N, K) in enumerate(linears):
+                o = q[(b, i)]
+                qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
+                                  Y=Ys[i])
+
+    stages = [stage_quantize, stage_act, stage_gemm]
+    stream = torch.cuda.Stream(device=dev)   # default priority
+    use_graph = not args.no_graph
+    with torch.cuda.stream(stream):
+        for s in stages:
+            s()
+        stream.synchronize()
+        runners = stages
+        if use_graph:
+            graphs = []
+            for s in stages:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    s()
+                graphs.append(g)
+            runners = [g.replay for g in graphs]
+
+        def one_step(ev=None):
+            if ev is not None:
+                ev[0].record(stream)
+            for j, r in enumerate(runners):
+                r()
+                if ev is not None:
+                    ev[j + 1].record(stream)
+
+        for _ in range(args.warmup):
+            one_step()
+        stream.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            one_step(events[k])
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+
+    wall = t1 - t0
+    ms_per_step = wall * 1e3 / args.steps
+    seg_ms = [sum(ev[j].elapsed_time(ev[j + 1]) for ev in events) / args.steps for j in range(3)]
+
+    # ---- algorithmic work of one step ----------------------------------------------------------------
+    gemm_ops = sum(2.0 * T * N * K for (_, N, K) in linears) * len(BITS_SWEEP)
+    quant_bytes = sum(N * K * (4.0 + b / 8.0) + GROUPS * 8 + N * 4 for b in BITS_SWEEP for (_, N, K) in linears)
+    act_bytes = sum(T * K * 5.0 + T * 4 for (_, N, K) in linears)
+    n_gemm, n_quant, n_act = 16, 16, 4
+    gemm_tops = gemm_ops / (seg_ms[2] * 1e-3) / 1e12
+    quant_gbs = quant_bytes / (seg_ms[0] * 1e-3) / 1e9
+    act_gbs = act_bytes / (seg_ms[1] * 1e-3) / 1e9
+    value = gemm_ops / (wall / args.steps) / 1e12
+
+    out = {
+        "metric": "group-quant int8 GEMM TOPS & % int8 MFMA peak; quantize/pack GB/s",
+        "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "configs[1]: BERT-base encoder layer, 4 linears (QKV 768->2304, out 768->768, "
+                               "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
+                               "step = 16 quantize/pack + 4 act-quant + 16 int8 GEMM+epilogue",
+                   "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph},
+        "roofline": {"kernel": "qgemm_i8_kernel (int8 MFMA GEMM + scale epilogue), 16 launches per step",
+                     "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": None,
+                     "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
+                     "ops_per_launch": gemm_ops / n_gemm},
+        "kernels": {
+            "quantize_pack": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                              "frac": round(quant_gbs / PEAK_HBM_GBS, 4),
+                              "avg_launch_us": round(seg_ms[0] * 1e3 / n_quant, 3),
+                              "bytes_per_launch": quant_bytes / n_quant},
+            "quantize_act": {"bound": "hbm", "achieved": round(act_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(act_gbs / PEAK_HBM_GBS, 4),
+                             "avg_launch_us": round(seg_ms[1] * 1e3 / n_act, 3),
+                             "bytes_per_launch": act_bytes / n_act},
+        },
+    }
+
+    if not args.no_extras:
+        out["shapes"] = per_shape(torch, qb, wl, dev)
+        out["backward"] = backward_leg(torch, qb, wl, dev)
+        out["embedding"] = embedding_leg(torch, qb, wl, dev)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+def time_launches(torch, fn, iters=50, warm=5):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / iters
+
+
+def per_shape(torch, qb, wl, dev):
+    """Each GEMM shape on its own (back-to-back launches between two events), against
+    min(int8 MFMA peak, HBM peak x intensity) for its algorithmic bytes; BERT-base at T = 4096
+    and, as the asymptotic case, BERT-large FFN-down at T = 32768."""
+    res = []
+    cases = [(T_TOKENS, N, K, 4) for (_, N, K) in wl.BERT_BASE_LINEARS] + [(T_TOKENS, 768, 3072, b) for b in (2, 3, 8)]
+    cases += [(32768, 1024, 4096, 2), (32768, 4096, 1024, 3)]
+    for (T, N, K, b) in cases:
+        W = wl.weight(N, K, seed=N + K).to(dev)
+        X = wl.activation(T, K, seed=T + K).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        Y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        sec = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        ops = 2.0 * T * N * K
+        byts = T * K + N * K * b / 8.0 + 4.0 * T * N + 4 * T + 4 * N
+        roof = min(PEAK_INT8_TOPS, PEAK_HBM_GBS * 1e9 * (ops / byts) / 1e12)
+        res.append({"T": T, "N": N, "K": K, "bits": b, "us": round(sec * 1e6, 2), "tops": round(ops / sec / 1e12, 1),
+                    "frac_int8_peak": round(ops / sec / 1e12 / PEAK_INT8_TOPS, 4),
+                    "roofline_tops": round(roof, 1), "frac_roofline": round(ops / sec / 1e12 / roof, 4),
+                    "gbs": round(byts / sec / 1e9, 1)})
+        del W, X, Y, Xq
+    return res
+
+
+def backward_leg(torch, qb, wl, dev):
+    """configs[2]: STE backward of the same layer, 3-bit weights, dY bf16; flops = 4*T*N*K."""
+    T, b = T_TOKENS, 3
+    tot_sec, tot_flops, rows = 0.0, 0.0, []
+    for i, (name, N, K) in enumerate(wl.BERT_BASE_LINEARS):
+        W = wl.weight(N, K, seed=wl.config_seed(2, i)).to(dev)
+        X = wl.activation(T, K, seed=wl.config_seed(2, 10 + i)).to(dev)
+        dY = wl.grad_output_bf16(T, N, seed=wl.config_seed(2, 20 + i)).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        dX = torch.empty((T, K), dtype=torch.bfloat16, device=dev)
+        dW = torch.empty((N, K), dtype=torch.float32, device=dev)
+        ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=dev)
+        sec = time_launches(torch, lambda: qb.qb_qlinear_bwd_ste(dY, Xq, CLIP, packed, h, b, GROUPS, dX=dX, dW=dW,
+                                                                 workspace=ws), iters=20)
+        fl = 4.0 * T * N * K
+        rows.append({"linear": name, "us": round(sec * 1e6, 1), "tflops": round(fl / sec / 1e12, 1)})
+        tot_sec += sec
+        tot_flops += fl
+    return {"workload": "configs[2]: dX and dW for the four linears, T=4096, 3-bit, bf16 MFMA / fp32 accumulate",
+            "tflops": round(tot_flops / tot_sec / 1e12, 1), "frac_bf16_peak": round(tot_flops / tot_sec / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "us_per_layer": round(tot_sec * 1e6, 1), "per_linear": rows}
+
+
+def embedding_leg(torch, qb, wl, dev):
+    """configs[4]: 8-bit grouped embedding table 30522 x 1024 and a 32768-id de-quantized gather."""
+    V, d, n = 30522, 1024, 32768
+    E = wl.embedding_table(V, d, seed=wl.config_seed(4, 0)).to(dev)
+    ids = wl.token_ids(n, V, seed=wl.config_seed(4, 1)).to(dev)
+    codes = torch.empty((V, d), dtype=torch.uint8, device=dev)
+    h = torch.empty(GROUPS, dtype=torch.float32, device=dev)
+    m = torch.empty(GROUPS, dtype=torch.float32, device=dev)
+    out = torch.empty((n, d), dtype=torch.float32, device=dev)
+    sq = time_launches(torch, lambda: qb.qb_embedding_quantize(E, GROUPS, codes, h, m), iters=20)
+    sg = time_launches(torch, lambda: qb.qb_embedding_gather(codes, h, GROUPS, ids, out), iters=20)
+    return {"quantize_us": round(sq * 1e6, 1), "quantize_gbs": round(V * d * 5.0 / sq / 1e9, 1),
+            "gather_us": round(sg * 1e6, 1), "gather_gbs": round(n * d * 5.0 / sg / 1e9, 1),
+            "note": "algorithmic bytes: 4 read + 1 written per table element; 1 read + 4 written per gathered element"}
+
+
+def cpu_baseline(wl):
+    """The CPU oracle (OpenMP build of the same source, untuned) on a bounded sample of the step:
+    the first 1024 of the 4096 token rows, all four linears, all four bit-widths."""
+    import numpy as np
+    import oracle
+    Ts = 1024
+    linears = wl.BERT_BASE_LINEARS
+    Ws = [wl.weight(N, K, seed=wl.config_seed(1, i)).numpy() for i, (_, N, K) in enumerate(linears)]
+    Xs = [wl.activation(Ts, K, seed=wl.config_seed(1, 10 + i)).numpy() for i, (_, N, K) in enumerate(linears)]
+    threads = oracle.num_threads(True)
+    t0 = time.perf_counter()
+    acts = [oracle.quantize_act(X, CLIP) for X in Xs]
+    ops = 0.0
+    for b in BITS_SWEEP:
+        for i, (_, N, K) in enumerate(linears):
+            codes, h, m, rs_w = oracle.quantize_groupwise(Ws[i], b, GROUPS)
+            oracle.qlinear_fwd(acts[i][0], CLIP, codes, h, b, openmp=True)
+            ops += 2.0 * Ts * N * K
+    sec = time.perf_counter() - t0
+    return {"value": round(ops / sec / 1e12, 5), "unit": "TOPS", "cores": threads, "kind": "oracle",
+            "sample": "first 1024 of 4096 token rows, all 4 linears x 4 bit-widths, incl. quantize steps; %.1f s" % sec,
+            "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -265,6 +265,13 @@ __global__ __launch_bounds__(256) void embedding_absmax_kernel(const float *__re
     }
 }
 
+__device__ __forceinline__ void group_scale(const float *m, int g, float &mg, float &delta)
+{
+    mg = m[g];
+    const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
+    delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;
+}
+
 // pass 2: codes, and h = m/255
 __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__restrict__ E, int64_t V, int d,
                                                                  int cols_per_group, int groups,
