@@ -7,7 +7,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqbert.so")
 SOURCES = ("api.hip", "quantize.hip", "qgemm_i8.hip", "bwd_bf16.hip")
 # packed-fp32 instructions are switched off for every device translation unit
-COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the quantizers need one rounding per operation: no fused multiply-add contraction there
 PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}

@@ -33,6 +33,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     int tiles_m, int tiles_n)
 {
     constexpr int THREADS = 64 * WM * WN;
+    constexpr bool QB_SKIP_STORES = false;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64 * KU, LDA = BK + 16;
     constexpr int CHUNKS_PER_ROW = BK / 16;
     constexpr int A_PER_THREAD = BM * CHUNKS_PER_ROW / THREADS;
@@ -177,7 +178,12 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int t0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
-            if (interior) {
+            if constexpr (QB_SKIP_STORES) {
+                int sum = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
+                if (sum == 0x12345678) Y[0] = 1.0f;
+            } else if (interior) {
                 int rx[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) rx[i] = rs_x[t0 + 8 * (i >> 2) + (i & 3)];
@@ -205,54 +211,144 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     }
 }
 
-#define QB_GLOBAL_TO_LDS16(gptr, lptr)                                                                   \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr),             \
-                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+// global -> LDS copy by the load unit: every lane supplies its own global address, the data of
+// lane l lands at LDS address m0 + 16*l (also for the 12-byte form).  Written as inline assembly
+// on purpose: the compiler then keeps no book on these copies, and the kernel states itself, with
+// wait_vmcnt, which of them must have landed before a barrier.
+__device__ __forceinline__ void copy16_to_lds(const void *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void copy12_to_lds(const void *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
 
-// Main kernel, K a multiple of 128.  One K-step is 128 features: two 64-code units per lane.
-template <int BITS, int TM, int TN, int WM, int WN>
+template <int BITS> struct SlotRead;  // one lane's slot (32 codes) out of LDS
+template <> struct SlotRead<2> {
+    static __device__ __forceinline__ void get(const uint8_t *p, uint32_t (&o)[2])
+    {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        o[0] = v.x; o[1] = v.y;
+    }
+};
+template <> struct SlotRead<3> {
+    typedef unsigned int v3u __attribute__((ext_vector_type(3)));
+    static __device__ __forceinline__ void get(const uint8_t *p, uint32_t (&o)[3])
+    {
+        const v3u v = *reinterpret_cast<const v3u *>(p);
+        o[0] = v[0]; o[1] = v[1]; o[2] = v[2];
+    }
+};
+template <> struct SlotRead<4> {
+    static __device__ __forceinline__ void get(const uint8_t *p, uint32_t (&o)[4])
+    {
+        const v4u v = *reinterpret_cast<const v4u *>(p);
+        o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
+    }
+};
+template <> struct SlotRead<8> {
+    static __device__ __forceinline__ void get(const uint8_t *p, uint32_t (&o)[8])
+    {
+        const v4u a = *reinterpret_cast<const v4u *>(p), b = *reinterpret_cast<const v4u *>(p + 16);
+        o[0] = a[0]; o[1] = a[1]; o[2] = a[2]; o[3] = a[3];
+        o[4] = b[0]; o[5] = b[1]; o[6] = b[2]; o[7] = b[3];
+    }
+};
+
+// vmcnt(N) with the other counters left alone (gfx9 encoding of s_waitcnt's immediate)
+template <int N, bool ENABLE = true>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    if constexpr (!ENABLE) return;
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+
+// Main kernel, K a multiple of 128.  One K-step is 128 features = two 64-code units.
+// Both operands are copied global -> LDS by the load unit (no staging registers):
+//   tokens : dense rows of 128 bytes, 16-byte chunks XOR-swizzled with the row number
+//   weights: the packed slots as they are, [32-neuron block][unit][lane][slot]; a wavefront
+//            then reads one slot per lane (conflict free) and expands it in registers
+// The copies run NSTAGE-1 steps ahead of the matrix cores through a ring of NSTAGE stage
+// buffers; a step ends with "the copies for the next step have landed" (vmcnt leaves the younger
+// ones in flight; copies return in issue order) and a workgroup barrier.
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int SKIP = 0>
 __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
     int tiles_m, int tiles_n)
 {
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
+    constexpr bool QB_SKIP_STORES = (SKIP & 4) != 0;  // SKIP is non-zero only in developer timing builds
     constexpr int NW = WM * WN;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 128;
-    constexpr int DMA_PER_WAVE = BM / 8 / NW;  // each DMA instruction of a wave fills 8 rows of 128 bytes
+    constexpr int A_DMA = BM / 8 / NW;          // per wavefront and step; each fills 8 rows of 128 bytes
     static_assert(BM % (8 * NW) == 0, "token tile must split into 8-row blocks per wavefront");
-    constexpr int SLOT = 4 * BITS;
+    constexpr int SLOT = 4 * BITS;               // bytes per slot in memory
+    constexpr int CH = (BITS == 3) ? 12 : 16;    // bytes one lane moves per weight copy instruction
+    constexpr int LSLOT = (BITS == 3) ? 16 : SLOT;  // bytes per slot in LDS: a 12-byte copy lands at a 16-byte stride
+    constexpr int PAIR = 128 * SLOT;             // bytes of one 32-neuron block x two units (contiguous in memory)
+    constexpr int LPAIR = 128 * LSLOT;           // the same block in LDS
+    constexpr int PARTS = PAIR / (64 * CH);      // copy instructions per pair; each fills 1024 bytes of LDS
+    constexpr int B_TOTAL = (BN / 32) * PARTS;   // copy instructions per step for the whole workgroup
+    constexpr int B_DMA = (B_TOTAL + NW - 1) / NW;
+    constexpr int PER = A_DMA + B_DMA;           // copy instructions per wavefront and step
+    constexpr int D = NSTAGE - 1;                // how many steps the copies run ahead
+    constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR;
 
-    // two separate objects: accesses to one are known not to alias the copy in flight to the other
-    __shared__ __align__(1024) uint8_t lds0[BM * BK];
-    __shared__ __align__(1024) uint8_t lds1[BM * BK];
-
-    const int nwg = tiles_m * tiles_n;
-    int logical;
-    {
-        const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
-        const int q = nwg >> 3, r = nwg & 7;
-        logical = xcd * q + (xcd < r ? xcd : r) + idx;
-    }
-    const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;  // tokens first, then weights
+    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave - wm * WN;
     const int l32 = lane & 31, hf = lane >> 5;
 
-    // ---- token tile: lane l of a DMA instruction fills physical chunk l%8 of row l/8 of an 8-row
-    // block, which holds logical chunk (l%8) ^ (row%8)
+    // Workgroups are persistent: each walks over tiles work = blockIdx.x, + gridDim.x, ... (the
+    // grid is a multiple of 8, so a workgroup stays on the tiles of its own XCD's range).
+    const int nwg = tiles_m * tiles_n;
+    for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
+    long long ts_[6];
+    if constexpr (SKIP & 8) ts_[0] = __builtin_readcyclecounter();
+    int logical;
+    {
+        const int xcd = work & 7, idx = work >> 3;
+        const int q = nwg >> 3, r = nwg & 7;
+        logical = xcd * q + (xcd < r ? xcd : r) + idx;
+    }
+    const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+
+    // ---- token tile copies: lane l of an instruction fills physical chunk l%8 of row l/8 of an
+    // 8-row block, which holds logical chunk (l%8) ^ (row%8)
     const int8_t *a_base = Xq + (size_t)tile_m * BM * K;
     const int last_row = T - 1 - tile_m * BM;  // rows past the end re-read the last one; outputs masked
-    uint32_t a_off[DMA_PER_WAVE];
+    uint32_t a_off[A_DMA];
 #pragma unroll
-    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+    for (int i = 0; i < A_DMA; ++i) {
         int row = (i * NW + wave) * 8 + (lane >> 3);
         row = row < last_row ? row : last_row;
         a_off[i] = (uint32_t)row * (uint32_t)K + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 16);
     }
-    // fragment reads: row = wm*TM*32 + tm*32 + l32, logical chunk = kk*4 + hf*2 + sub
+    // ---- weight copies: instruction j moves part j%PARTS of the pair of block j/PARTS.  Every
+    // wavefront issues the same number of copies (the vmcnt arithmetic relies on it): surplus
+    // ones repeat an earlier copy, writing the same bytes to the same place.
+    const int kunits = K >> 6;
+    const int ncb = (N + 31) >> 5;
+    const uint8_t *b_gsrc[B_DMA];
+    int b_ldst[B_DMA];
+#pragma unroll
+    for (int i = 0; i < B_DMA; ++i) {
+        const int j = (i * NW + wave) % B_TOTAL;
+        const int pair = j / PARTS, part = j - pair * PARTS;
+        int cb = tile_n * (BN / 32) + pair;
+        cb = cb < ncb ? cb : ncb - 1;  // blocks past the end re-read the last one; outputs masked
+        b_gsrc[i] = packed + (size_t)cb * kunits * 64 * SLOT + part * 64 * CH + lane * CH;
+        b_ldst[i] = pair * LPAIR + part * 1024;
+    }
+    // ---- fragment reads.  tokens: row = wm*TM*32 + tm*32 + l32, logical chunk = kk*4 + hf*2 + sub
     const int p0 = (hf * 2) ^ (l32 & 7);
     const int frag_row = (wm * TM * 32 + l32) * BK;
     int a_frag[4];
@@ -260,16 +356,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     a_frag[1] = frag_row + ((p0 ^ 1) << 4);  // kk 0, sub 1
     a_frag[2] = frag_row + ((p0 ^ 4) << 4);  // kk 1, sub 0
     a_frag[3] = frag_row + ((p0 ^ 5) << 4);  // kk 1, sub 1
-
-    const int kunits = K >> 6;
-    const int ncb = (N + 31) >> 5;
-    const uint8_t *b_src[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        int cb = tile_n * (BN / 32) + wn * TN + tn;
-        cb = cb < ncb ? cb : ncb - 1;
-        b_src[tn] = packed + ((size_t)cb * kunits * 64 + lane) * SLOT;
-    }
+    const int b_frag = wn * TN * LPAIR + lane * LSLOT;  // + tn*LPAIR + kk*64*LSLOT
 
     v16i acc[TM][TN];
 #pragma unroll
@@ -279,34 +366,35 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
 
-    uint32_t b0[TN][2][BITS], b1[TN][2][BITS];
-
-#define QB_FETCH(step, BDST, LDSDST)                                                                      \
-    {                                                                                                     \
-        _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                                 \
-            _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                            \
-                const uint32_t *p_ =                                                                      \
-                    reinterpret_cast<const uint32_t *>(b_src[tn] + (size_t)((step) * 2 + kk) * 64 * SLOT); \
-                _Pragma("unroll") for (int i = 0; i < BITS; ++i) BDST[tn][kk][i] = p_[i];                 \
-            }                                                                                             \
-        _Pragma("unroll") for (int i = 0; i < DMA_PER_WAVE; ++i)                                          \
-            QB_GLOBAL_TO_LDS16(a_base + a_off[i] + (size_t)(step) * BK, LDSDST + (i * NW + wave) * 1024); \
-        __builtin_amdgcn_sched_barrier(0); /* fetches stay ahead of the MFMAs that hide their latency */ \
+#define QB_FETCH(step, stage)                                                                             \
+    if constexpr (!(SKIP & 1)) {                                                                          \
+        const uint32_t st_ = lds_base + (stage) * STAGE_BYTES;                                            \
+        _Pragma("unroll") for (int i = 0; i < B_DMA; ++i) {                                               \
+            if constexpr (BITS == 3) copy12_to_lds(b_gsrc[i] + (size_t)(step) * PAIR, st_ + A_BYTES + b_ldst[i]); \
+            else copy16_to_lds(b_gsrc[i] + (size_t)(step) * PAIR, st_ + A_BYTES + b_ldst[i]);             \
+        }                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < A_DMA; ++i)                                                 \
+            copy16_to_lds(a_base + a_off[i] + (size_t)(step) * BK, st_ + (i * NW + wave) * 1024);         \
     }
-#define QB_MMA(LDSSRC, BSRC)                                                                              \
+#define QB_MMA(stage)                                                                                     \
     {                                                                                                     \
+        const uint8_t *lds_a = lds + (stage) * STAGE_BYTES, *lds_b = lds_a + A_BYTES;                     \
         _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                \
             uint32_t d[TN][8];                                                                            \
             _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                           \
-                unpack_run<BITS>(BSRC[tn][kk], d[tn]);                                                    \
+                uint32_t raw[BITS];                                                                       \
+                SlotRead<BITS>::get(lds_b + b_frag + tn * LPAIR + kk * 64 * LSLOT, raw);                  \
+                unpack_run<BITS>(raw, d[tn]);                                                             \
                 if constexpr (BITS == 8) {                                                                \
                     _Pragma("unroll") for (int i = 0; i < 8; ++i) d[tn][i] ^= 0x80808080u;                \
                 }                                                                                         \
             }                                                                                             \
             _Pragma("unroll") for (int sub = 0; sub < 2; ++sub) {                                         \
                 v4i a[TM], b[TN];                                                                         \
-                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm) a[tm] =                                 \
-                    *reinterpret_cast<const v4i *>(LDSSRC + a_frag[kk * 2 + sub] + tm * 32 * BK);         \
+                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm) {                                       \
+                    if constexpr (SKIP & 2) { a[tm][0] = lane + tm; a[tm][1] = sub; a[tm][2] = kk; a[tm][3] = 1; } \
+                    else a[tm] = *reinterpret_cast<const v4i *>(lds_a + a_frag[kk * 2 + sub] + tm * 32 * BK); \
+                }                                                                                         \
                 _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                       \
                     b[tn][0] = (int)d[tn][4 * sub + 0];                                                   \
                     b[tn][1] = (int)d[tn][4 * sub + 1];                                                   \
@@ -319,78 +407,139 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
             }                                                                                             \
         }                                                                                                 \
     }
-// all copies issued so far have landed (vmcnt = 0), then let every wavefront see them
-#define QB_JOIN()                                                                                         \
+
+// End of a step.  A bare s_barrier, not __syncthreads(): the fence inside the latter would wait
+// for every copy in flight (vmcnt 0) and with that undo the run-ahead.  What the barrier has to
+// order is already ordered: this wavefront's LDS reads of the step have returned (the MFMAs that
+// consume them are issued before it) and its copies for the next step have landed (wait_vmcnt).
+// The empty asm keeps the compiler from moving LDS reads of the next step above the barrier.
+#define QB_STEP_BARRIER()                                                                                 \
     {                                                                                                     \
-        __builtin_amdgcn_s_waitcnt(0x0F70);                                                               \
-        __syncthreads();                                                                                  \
+        __builtin_amdgcn_s_barrier();                                                                     \
+        asm volatile("" ::: "memory");                                                                    \
     }
 
     const int nsteps = K / BK;
-    QB_FETCH(0, b0, lds0)
-    QB_JOIN()
+    // prologue: start the copies of the first D steps, wait for step 0 only
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        if (u < nsteps) QB_FETCH(u, u)
+    if constexpr (SKIP & 8) ts_[1] = __builtin_readcyclecounter();
+    if (nsteps >= D) wait_vmcnt<(D - 1) * PER, !(SKIP & 1)>();
+    else wait_vmcnt<0, !(SKIP & 1)>();
+    QB_STEP_BARRIER();
+    if constexpr (SKIP & 8) ts_[2] = __builtin_readcyclecounter();
+
     int s = 0;
-    for (; s + 2 < nsteps; s += 2) {
-        QB_FETCH(s + 1, b1, lds1)
-        QB_MMA(lds0, b0)
-        QB_JOIN()
-        QB_FETCH(s + 2, b0, lds0)
-        QB_MMA(lds1, b1)
-        QB_JOIN()
+    for (; s + NSTAGE <= nsteps; s += NSTAGE) {
+#pragma unroll
+        for (int u = 0; u < NSTAGE; ++u) {
+            const bool more = s + u + D < nsteps;  // uniform
+            if (more) QB_FETCH(s + u + D, (u + D) % NSTAGE)
+            QB_MMA(u)
+            if (more) wait_vmcnt<(D - 1) * PER, !(SKIP & 1)>();  // copies for the next step have landed, younger ones fly on
+            else wait_vmcnt<0, !(SKIP & 1)>();
+            QB_STEP_BARRIER();
+        }
     }
-    if (nsteps - s == 2) {
-        QB_FETCH(s + 1, b1, lds1)
-        QB_MMA(lds0, b0)
-        QB_JOIN()
-        QB_MMA(lds1, b1)
-    } else {
-        QB_MMA(lds0, b0)
-    }
+    // tail: fewer than NSTAGE steps left, all their copies are already issued
+#pragma unroll
+    for (int u = 0; u < NSTAGE - 1; ++u)
+        if (s + u < nsteps) {
+            QB_MMA(u)
+            wait_vmcnt<0, !(SKIP & 1)>();
+            QB_STEP_BARRIER();
+        }
 #undef QB_FETCH
 #undef QB_MMA
-#undef QB_JOIN
+#undef QB_STEP_BARRIER
 
-    // ---- epilogue: exact integer corrections, then one scale per column
+    if constexpr (SKIP & 8) ts_[3] = __builtin_readcyclecounter();
+    // ---- epilogue: exact integer corrections, then one scale per column.  Everything the
+    // stores depend on is loaded first: a load issued between two stores would make the wavefront
+    // wait for the older store to complete (loads and stores share one in-order counter) and turn
+    // the write-out into a chain of round trips.
     constexpr int L = (1 << BITS) - 1;
     constexpr int E2 = (BITS == 8) ? 2 : -2 * L;  // 2*e
     const bool interior = (tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N;  // uniform over the workgroup
+    int coln[TN];
+    float scale[TN], bv[TN];
+    bool n_ok[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
-        const bool n_ok = n < N;
-        const int nn = n_ok ? n : N - 1;
-        const int coln = 2 * rs_w[nn] + K;
-        const float scale = hx * h[nn / rows_per_group];
-        const float bv = bias ? bias[nn] : 0.0f;
+        n_ok[tn] = n < N;
+        const int nn = n_ok[tn] ? n : N - 1;
+        coln[tn] = 2 * rs_w[nn] + K;
+        scale[tn] = hx * h[nn / rows_per_group];
+        bv[tn] = bias ? bias[nn] : 0.0f;
+    }
+    if (interior && (A4out == nullptr || (SKIP & 8))) {
+        // fast path (uniform branch): straight-line code, one scalar base per 32x32 block and one
+        // 32-bit lane offset per accumulator register
+        const int t_wave = tile_m * BM + wm * TM * 32, n_wave = tile_n * BN + wn * TN * 32;
+        float *y_wave = Y + (size_t)t_wave * N + n_wave;
+        const int32_t *rx_wave = rs_x + t_wave;
+        uint32_t voff[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            voff[i] = ((uint32_t)(4 * hf + 8 * (i >> 2) + (i & 3)) * (uint32_t)N + (uint32_t)l32) * 4u;
+        int rx[TM][16];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) rx[tm][i] = rx_wave[tm * 32 + 4 * hf + 8 * (i >> 2) + (i & 3)];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                char *y_blk = reinterpret_cast<char *>(y_wave + (size_t)tm * 32 * N + tn * 32);
+                if constexpr (QB_SKIP_STORES) {
+                    int sum = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
+                    if (sum == 0x12345678) Y[0] = 1.0f;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int a4 = 4 * acc[tm][tn][i] + E2 * rx[tm][i] + coln[tn];
+                        *reinterpret_cast<float *>(y_blk + voff[i]) = scale[tn] * (float)a4 + bv[tn];
+                    }
+                }
+            }
+    } else {
+        // edge tiles and the debug output: every element checked
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int t0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
-            if (interior) {
-                int rx[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) rx[i] = rs_x[t0 + 8 * (i >> 2) + (i & 3)];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int t = t0 + 8 * (i >> 2) + (i & 3);
-                    const int a4 = 4 * acc[tm][tn][i] + E2 * rx[i] + coln;
-                    const size_t at = (size_t)t * N + n;
-                    Y[at] = scale * (float)a4 + bv;
-                    if (A4out) A4out[at] = a4;
-                }
-            } else {
+            for (int tn = 0; tn < TN; ++tn) {
+                const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
-                    if (t < T && n_ok) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                    if (t < T && n_ok[tn]) {
+                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln[tn];
                         const size_t at = (size_t)t * N + n;
-                        Y[at] = scale * (float)a4 + bv;
+                        Y[at] = scale[tn] * (float)a4 + bv[tn];
                         if (A4out) A4out[at] = a4;
                     }
                 }
             }
         }
     }
+    if constexpr (SKIP & 8) {
+        ts_[4] = __builtin_readcyclecounter();
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        ts_[5] = __builtin_readcyclecounter();
+        if (tid == 0) {
+            long long *dbg = reinterpret_cast<long long *>(A4out) + (size_t)work * 8;
+            for (int i = 0; i < 6; ++i) dbg[i] = ts_[i];
+            dbg[6] = __builtin_amdgcn_s_getreg((3 << 11) | (6 << 6) | 4) /* HW_ID: cu/se bits */;
+        }
+    }
+    }  // persistent tile loop
 }
 
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
@@ -403,13 +552,17 @@ void launch_cfg(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, co
                        Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n);
 }
 
-template <int BITS, int TM, int TN, int WM, int WN>
+// grid_cap: upper bound of workgroups (a multiple of 8); 0 = one workgroup per tile
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int SKIP = 0>
 void launch_dma(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
-                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st)
+                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
+                int grid_cap = 0)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL((qgemm_i8_dma_kernel<BITS, TM, TN, WM, WN>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), 0, st,
+    int grid = tiles_m * tiles_n;
+    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
+    hipLaunchKernelGGL((qgemm_i8_dma_kernel<BITS, TM, TN, WM, WN, NSTAGE, SKIP>), dim3(grid), dim3(64 * WM * WN), 0, st,
                        Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n);
 }
 
@@ -421,11 +574,70 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
         return;
     }
-    const long big_tiles = (long)((T + 255) / 256) * ((N + 127) / 128);
-    if (big_tiles >= 192) launch_dma<BITS, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
-    else launch_dma<BITS, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+    // Tile choice.  Each CU can keep only a few tens of KB of copies in flight, so the bytes copied
+    // per MFMA decide the speed: 256x256 tiles (half the bytes of 128x128) whenever they still give
+    // every CU at least two tiles, 128x128 otherwise.  Grids are persistent (a multiple of 8 so that
+    // a workgroup stays inside its XCD's tile range).
+    const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
+    if (tiles256 >= 512) launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
+    else launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
 }
 
+#ifdef QB_TUNE
+}  // namespace
+}  // namespace qb
+// developer hook for tile sweeps (only in builds made with -DQB_TUNE, never in the shipped library)
+extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
+                                   const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N, int64_t K, float *Y,
+                                   void *stream);
+extern "C" int qb_tune_timeline(int stages, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
+                                const int32_t *rs_w, int64_t T, int64_t N, int64_t K, float *Y, long long *dbg, void *stream)
+{
+    using namespace qb;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    const int rpg = (int)(N / 128);
+    const float hx = 6.0f / 255.0f;
+    int32_t *d = reinterpret_cast<int32_t *>(dbg);
+    if (stages == 2) launch_dma<4, 2, 2, 2, 2, 2, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
+    else if (stages == 3) launch_dma<4, 2, 2, 2, 2, 3, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
+    else launch_dma<4, 2, 2, 2, 2, 4, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
+    return hipGetLastError() == hipSuccess ? 0 : 6;
+}
+extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
+                                   const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N, int64_t K, float *Y,
+                                   void *stream)
+{
+    using namespace qb;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    const int rpg = (int)(N / groups);
+    const float hx = 6.0f / 255.0f;
+    const int cap = (cfg / 100) * 256;  // cfg = variant + 100 * (workgroups per CU of the persistent grid; 0 = one per tile)
+#define QB_T(B, a, b, c, d, e, f) launch_dma<B, a, b, c, d, e, f>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
+#define QB_TB(a, b, c, d, e, f) { if (bits == 2) QB_T(2, a, b, c, d, e, f); else if (bits == 3) QB_T(3, a, b, c, d, e, f); else if (bits == 4) QB_T(4, a, b, c, d, e, f); else QB_T(8, a, b, c, d, e, f); }
+    switch (cfg % 100) {
+        case 0: QB_TB(2, 2, 2, 2, 2, 0) break;   // 128x128 2 stages
+        case 1: QB_TB(2, 2, 2, 2, 3, 0) break;   // 128x128 3 stages
+        case 2: QB_TB(2, 2, 2, 2, 4, 0) break;   // 128x128 4 stages
+        case 3: QB_TB(4, 2, 2, 2, 3, 0) break;   // 256x128 3 stages
+        case 4: QB_TB(2, 4, 2, 2, 3, 0) break;   // 128x256 3 stages
+        case 5: QB_TB(4, 4, 2, 2, 2, 0) break;   // 256x256 2 stages
+        case 6: QB_TB(2, 1, 2, 2, 4, 0) break;   // 128x64 4 stages
+        case 7: QB_TB(1, 2, 4, 2, 3, 0) break;   // 128x128 8 waves 3 stages
+        case 8: QB_TB(2, 2, 4, 2, 3, 0) break;   // 256x128 8 waves 3 stages
+        case 9: QB_TB(4, 2, 2, 4, 2, 0) break;   // 256x256 8 waves 2 stages
+        // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
+        case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
+        case 12: QB_TB(2, 2, 2, 2, 2, 4) break;
+        case 14: QB_TB(2, 2, 2, 2, 2, 7) break;
+        default: return -1;
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 6;
+}
+namespace qb {
+namespace {
+#endif
 }  // namespace
 }  // namespace qb
 
