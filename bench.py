@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference dispatch for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -91,6 +93,13 @@ def main():
                 o = q[(b, i)]
                 qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
                                   Y=Ys[i])
+
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     stages = [stage_quantize, stage_act, stage_gemm]
     stream = torch.cuda.Stream(device=dev)   # default priority
@@ -152,9 +161,9 @@ def main():
                                "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
                                "step = 16 quantize/pack + 4 act-quant + 16 int8 GEMM+epilogue",
                    "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph},
-        "roofline": {"kernel": "qgemm_i8_kernel (int8 MFMA GEMM + scale epilogue), 16 launches per step",
+        "roofline": {"kernel": "qgemm_i8_dma_kernel (int8 MFMA GEMM + scale epilogue), 16 launches per step",
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": None,
+                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
                      "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
                      "ops_per_launch": gemm_ops / n_gemm},
         "kernels": {
@@ -176,6 +185,17 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` on this workload, from the committed rocprofv3 counter
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if not measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_config2.json")
+    try:
+        with open(path) as f:
+            return json.load(f)[kernel]["bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def time_launches(torch, fn, iters=50, warm=5):
