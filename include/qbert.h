@@ -38,7 +38,7 @@ typedef enum {
     QB_ERR_SHAPE = 3,      /* non-positive dim, K % QB_K_ALIGN != 0, K > QB_MAX_K, N % G != 0  */
     QB_ERR_CLIP = 4,       /* activation range not a positive finite number                  */
     QB_ERR_WORKSPACE = 5,  /* workspace NULL or misaligned although the call needs one       */
-    QB_ERR_HIP = 6         /* the HIP runtime refused a launch (hipGetLastError is kept)     */
+    QB_ERR_HIP = 6         /* the HIP runtime refused a launch (its error state is cleared) */
 } qb_status;
 
 /* Host, pure.  Static string for a status. */
@@ -71,6 +71,25 @@ size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K);
  */
 qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int groups,
                                 void *packed, float *h, float *m, int32_t *rs_w, void *stream);
+
+/*
+ * The same operation for several matrices in as few launches as possible (quantization-aware
+ * fine-tuning re-quantizes every matrix of the model from its fp32 master copy each step, each
+ * layer at its own bit-width: Sec. 3.2 mixed precision, Tables 6 and 7).  `jobs` is a HOST array of
+ * n_jobs descriptors whose pointer fields are DEVICE pointers with the meaning of the arguments
+ * of qb_quantize_groupwise; the array is read during the call only.  Jobs must not overlap in
+ * their outputs.  All jobs are validated before anything is launched.
+ */
+#define QB_MAX_BATCH 16        /* jobs per launch; longer lists are split */
+typedef struct {
+    const float *W;
+    int64_t N, K;
+    int bits, groups;
+    void *packed;
+    float *h, *m;
+    int32_t *rs_w;
+} qb_quant_job;
+qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
 
 /*
  * 8-bit activation quantization (Table 1 caption: all models use 8-bit activations; same
@@ -134,7 +153,7 @@ qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups
                                 uint8_t *codes, float *h, float *m, void *stream);
 
 /* Lookup with de-quantization: out[i,j] = h[g(j)] * (2*codes[ids[i],j] - 255).
- *   ids  in  [n_ids] int64, each in [0,V) (not checked: an id outside reads out of bounds)
+ *   ids  in  [n_ids] int64; an id outside [0,V) yields a row of zeros
  *   out  out [n_ids,d] fp32.   n_ids == 0 is allowed and does nothing. */
 qb_status qb_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int groups,
                               const int64_t *ids, int64_t n_ids, float *out, void *stream);

@@ -18,8 +18,15 @@ _lib = None
 QB_K_ALIGN = 64
 QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
+           "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather")
+
+
+class _QuantJob(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("bits", ctypes.c_int),
+                ("groups", ctypes.c_int), ("packed", ctypes.c_void_p), ("h", ctypes.c_void_p), ("m", ctypes.c_void_p),
+                ("rs_w", ctypes.c_void_p)]
 
 
 class QBError(RuntimeError):
@@ -46,6 +53,8 @@ def load_library():
     lib.qb_bwd_workspace_nbytes.argtypes = [i64, i64, i64]
     lib.qb_quantize_groupwise.restype = ci
     lib.qb_quantize_groupwise.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
+    lib.qb_quantize_groupwise_batched.restype = ci
+    lib.qb_quantize_groupwise_batched.argtypes = [ctypes.POINTER(_QuantJob), ci, vp]
     lib.qb_quantize_act.restype = ci
     lib.qb_quantize_act.argtypes = [vp, i64, i64, cf, vp, vp, vp]
     lib.qb_qlinear_fwd.restype = ci
@@ -109,6 +118,29 @@ def qb_quantize_groupwise(W, bits, groups, packed=None, h=None, m=None, rs_w=Non
         rs_w = torch.empty(N, dtype=torch.int32, device=dev)
     _check(lib.qb_quantize_groupwise(_p(W), N, K, bits, groups, _p(packed), _p(h), _p(m), _p(rs_w), _stream()))
     return packed, h, m, rs_w
+
+
+def qb_quantize_groupwise_batched(jobs):
+    """jobs: list of dicts with W, bits, groups and optionally packed, h, m, rs_w (allocated here if absent).
+    Returns the list of (packed, h, m, rs_w) tuples."""
+    lib = load_library()
+    arr = (_QuantJob * max(len(jobs), 1))()
+    outs = []
+    for i, j in enumerate(jobs):
+        W = _dev(j["W"], torch.float32, "W")
+        N, K = W.shape
+        bits, groups = int(j["bits"]), int(j["groups"])
+        dev = W.device
+        packed = j.get("packed")
+        if packed is None:
+            packed = torch.empty(max(qb_packed_nbytes(N, K, bits), 1), dtype=torch.uint8, device=dev)
+        h = j.get("h") if j.get("h") is not None else torch.empty(max(groups, 1), dtype=torch.float32, device=dev)
+        m = j.get("m") if j.get("m") is not None else torch.empty(max(groups, 1), dtype=torch.float32, device=dev)
+        rs = j.get("rs_w") if j.get("rs_w") is not None else torch.empty(N, dtype=torch.int32, device=dev)
+        arr[i] = _QuantJob(W.data_ptr(), N, K, bits, groups, packed.data_ptr(), h.data_ptr(), m.data_ptr(), rs.data_ptr())
+        outs.append((packed, h, m, rs))
+    _check(lib.qb_quantize_groupwise_batched(arr, len(jobs), _stream()))
+    return outs
 
 
 def qb_quantize_act(X, clip, Xq=None, rs_x=None):

@@ -14,22 +14,51 @@
 namespace qb {
 namespace {
 
-// (w - q0)/Delta rounded half-to-even and clamped to 0..L; q0 = -m.  `delta` must be non-zero
-// (callers pass 1 for an all-zero group, which yields code 0 because w + m = 0).
-__device__ __forceinline__ uint32_t quantize_code(float w, float m, float delta, float Lf)
-{
-    const float s = __fadd_rn(w, m);
-    const float t = __fdiv_rn(s, delta);
-    float r = rintf(t);
-    r = fminf(fmaxf(r, 0.0f), Lf);
-    return (uint32_t)r;
-}
-
-__device__ __forceinline__ uint32_t quantize4(const float4 v, float m, float delta, float Lf)
-{
-    return quantize_code(v.x, m, delta, Lf) | (quantize_code(v.y, m, delta, Lf) << 8) |
-           (quantize_code(v.z, m, delta, Lf) << 16) | (quantize_code(v.w, m, delta, Lf) << 24);
-}
+// The quantizer of one range [-m, +m] (q0 = -m): code = clamp(rint(fl((w + m) / Delta)), 0, L),
+// every step one correctly rounded binary32 operation.
+//
+// The division is the expensive step (these kernels have ~20 ALU operations per element to spend
+// at HBM speed), so the common case multiplies by rinv = fl(1/Delta) instead, and falls back to
+// the true division exactly when the two could disagree:
+//   t  = fl(s/Delta)  = (s/Delta)(1+e3),           |e| <= 2^-24 each
+//   t' = fl(s*rinv)   = (s/Delta)(1+e1)(1+e2)
+//   |t' - t| <= (s/Delta) * 3.0001 * 2^-24 <= 255.0001 * 3.0001 * 2^-24 < 4.6e-5
+// (s/Delta <= L(1+2^-23) <= 255.0001).  With n = rint(t') and d = t' - n (exact by Sterbenz),
+// |d| <= 0.4999 puts t' at least 1e-4 away from every half-integer, hence t strictly on the same
+// side of it: rint(t) = n, and no tie is involved.  Otherwise the lane redoes the step with the
+// IEEE division.  `fast` is off for ranges whose reciprocal is not a normal number.
+struct Quantizer {
+    float m, delta, rinv, Lf;
+    bool fast;
+    __device__ __forceinline__ void set(float mg, float L)
+    {
+        m = mg;
+        Lf = L;
+        const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, L);
+        delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;  // all-zero group: w + m = 0 gives code 0 with any Delta
+        rinv = __fdiv_rn(1.0f, delta);
+        fast = delta >= 1.0e-30f && delta <= 1.0e30f;
+    }
+    __device__ __forceinline__ float half_step() const { return (m == 0.0f) ? 0.0f : __fdiv_rn(m, Lf); }
+    __device__ __forceinline__ uint32_t code(float w) const
+    {
+        const float s = __fadd_rn(w, m);
+        float r;
+        if (fast) {
+            const float tp = __fmul_rn(s, rinv);
+            r = rintf(tp);
+            if (!(fabsf(tp - r) <= 0.4999f)) r = rintf(__fdiv_rn(s, delta));  // rare; also catches NaN
+        } else {
+            r = rintf(__fdiv_rn(s, delta));
+        }
+        r = fminf(fmaxf(r, 0.0f), Lf);
+        return (uint32_t)r;
+    }
+    __device__ __forceinline__ uint32_t code4(const float4 v) const
+    {
+        return code(v.x) | (code(v.y) << 8) | (code(v.z) << 16) | (code(v.w) << 24);
+    }
+};
 
 __device__ __forceinline__ float absmax4(const float4 v, float mx)
 {
@@ -50,17 +79,17 @@ __device__ __forceinline__ int fast_div(int e, int d, float inv)
 // Otherwise m was found by absmax_slices_kernel and only the panel starting a group writes h.
 // LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then THREADS/64 floats.
 template <int BITS, int THREADS, int V, bool FUSED>
-__global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
+__device__ __forceinline__ void quantize_panel_body(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
-    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w)
+    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
+    int panel, uint8_t *smem)
 {
-    extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x;
     const int stride = K + 16;
     int *rowsum = reinterpret_cast<int *>(smem + (size_t)prow * stride);
     float *red = reinterpret_cast<float *>(rowsum + prow);
 
-    const int row0 = blockIdx.x * prow;  // first row of the panel
+    const int row0 = panel * prow;  // first row of the panel
     const int g = row0 / rows_per_group;
     const float4 *src = reinterpret_cast<const float4 *>(W + (size_t)row0 * K);
     const int n4 = prow * (K >> 2);
@@ -90,10 +119,10 @@ __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
         mg = m[g];
         __syncthreads();
     }
-    const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, Lf);
-    const float delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;
+    Quantizer qz;
+    qz.set(mg, Lf);
     if (tid == 0 && row0 % rows_per_group == 0) {
-        h[g] = hg;
+        h[g] = qz.half_step();
         if (FUSED) m[g] = mg;
     }
 
@@ -105,7 +134,7 @@ __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
             const int e = idx << 2;
             const int r = fast_div(e, K, inv_K);
             const int c = e - r * K;
-            *reinterpret_cast<uint32_t *>(smem + (size_t)r * stride + c) = quantize4(v[i], mg, delta, Lf);
+            *reinterpret_cast<uint32_t *>(smem + (size_t)r * stride + c) = qz.code4(v[i]);
         }
     }
     __syncthreads();
@@ -142,6 +171,49 @@ __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
     for (int r = tid; r < prow; r += THREADS) rs_w[row0 + r] = rowsum[r] - K * (1 << (BITS - 1));
 }
 
+template <int BITS, int THREADS, int V, bool FUSED>
+__global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
+    const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
+    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    quantize_panel_body<BITS, THREADS, V, FUSED>(W, K, rows_per_group, prow, inv_K, inv_prow, packed, h, m, rs_w,
+                                                 blockIdx.x, smem);
+}
+
+// Several matrices in one launch (a fine-tuning step re-quantizes every matrix of the model):
+// workgroup w serves group w - first_wg[j] of job j.  Passed by value as the kernel argument.
+struct QuantBatch {
+    int n;
+    int first_wg[QB_MAX_BATCH + 1];
+    const float *W[QB_MAX_BATCH];
+    uint8_t *packed[QB_MAX_BATCH];
+    float *h[QB_MAX_BATCH];
+    float *m[QB_MAX_BATCH];
+    int32_t *rs_w[QB_MAX_BATCH];
+    int K[QB_MAX_BATCH];
+    int rows_per_group[QB_MAX_BATCH];
+    int bits[QB_MAX_BATCH];
+    float inv_K[QB_MAX_BATCH];
+    float inv_rows[QB_MAX_BATCH];
+};
+
+template <int V>
+__global__ __launch_bounds__(256) void quantize_batched_kernel(const QuantBatch b)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    int j = 0;
+    while (j + 1 < b.n && (int)blockIdx.x >= b.first_wg[j + 1]) ++j;
+    const int g = blockIdx.x - b.first_wg[j];
+    const int rpg = b.rows_per_group[j];
+    switch (b.bits[j]) {
+        case 2: quantize_panel_body<2, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 3: quantize_panel_body<3, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 4: quantize_panel_body<4, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        default: quantize_panel_body<8, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+    }
+}
+
 // Two-pass path for groups too large for one workgroup's registers: slices of a group reduce
 // |w| and combine through an integer atomic max on the bit pattern (order-preserving for
 // non-negative floats).  m must have been zero-filled.
@@ -173,12 +245,13 @@ __global__ void fill_zero_kernel(float *p, int n)
 
 // ---- activations: one wavefront per token row -----------------------------------------------------
 __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restrict__ X, int T, int K, float clip,
-                                                           float delta, int8_t *__restrict__ Xq,
-                                                           int32_t *__restrict__ rs_x)
+                                                           int8_t *__restrict__ Xq, int32_t *__restrict__ rs_x)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= T) return;
+    Quantizer qz;
+    qz.set(clip, 255.0f);
     const float4 *src = reinterpret_cast<const float4 *>(X + (size_t)row * K);
     uint32_t *dst = reinterpret_cast<uint32_t *>(Xq + (size_t)row * K);
     const int k4 = K >> 2;
@@ -199,7 +272,7 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
                 c.y = fminf(fmaxf(c.y, -clip), clip);
                 c.z = fminf(fmaxf(c.z, -clip), clip);
                 c.w = fminf(fmaxf(c.w, -clip), clip);
-                const uint32_t q = quantize4(c, clip, delta, 255.0f);
+                const uint32_t q = qz.code4(c);
                 sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
                 dst[idx] = q ^ 0x80808080u;  // u - 128 as int8
             }
@@ -265,13 +338,6 @@ __global__ __launch_bounds__(256) void embedding_absmax_kernel(const float *__re
     }
 }
 
-__device__ __forceinline__ void group_scale(const float *m, int g, float &mg, float &delta)
-{
-    mg = m[g];
-    const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
-    delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;
-}
-
 // pass 2: codes, and h = m/255
 __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__restrict__ E, int64_t V, int d,
                                                                  int cols_per_group, int groups,
@@ -287,16 +353,19 @@ __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__
     if (id >= n4) return;
     const int c = (int)(id % (d >> 2)) << 2;
     const float4 v = reinterpret_cast<const float4 *>(E)[id];
-    float mg, delta;
-    uint32_t q;
-    group_scale(m, (c + 0) / cols_per_group, mg, delta);
-    q = quantize_code(v.x, mg, delta, 255.0f);
-    group_scale(m, (c + 1) / cols_per_group, mg, delta);
-    q |= quantize_code(v.y, mg, delta, 255.0f) << 8;
-    group_scale(m, (c + 2) / cols_per_group, mg, delta);
-    q |= quantize_code(v.z, mg, delta, 255.0f) << 16;
-    group_scale(m, (c + 3) / cols_per_group, mg, delta);
-    q |= quantize_code(v.w, mg, delta, 255.0f) << 24;
+    const float w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t q = 0;
+    int g_prev = -1;
+    Quantizer qz;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int g = (c + i) / cols_per_group;
+        if (g != g_prev) {
+            qz.set(m[g], 255.0f);
+            g_prev = g;
+        }
+        q |= qz.code(w[i]) << (8 * i);
+    }
     reinterpret_cast<uint32_t *>(codes)[id] = q;
 }
 
@@ -387,15 +456,69 @@ extern "C" qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K,
     }
 }
 
+static qb_status check_quant_job(const qb_quant_job &j)
+{
+    if (!j.W || !j.packed || !j.h || !j.m || !j.rs_w) return QB_ERR_NULL;
+    if (!bits_ok(j.bits)) return QB_ERR_BITS;
+    if (j.N <= 0 || j.N > (1 << 24) || !k_ok(j.K) || j.groups <= 0 || j.N % j.groups != 0) return QB_ERR_SHAPE;
+    return QB_OK;
+}
+
+extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream)
+{
+    if (n_jobs < 0) return QB_ERR_SHAPE;
+    if (n_jobs == 0) return QB_OK;
+    if (!jobs) return QB_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        const qb_status s = check_quant_job(jobs[i]);
+        if (s != QB_OK) return s;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    QuantBatch b;
+    auto flush = [&](int max_elems, size_t lds) {
+        if (b.n == 0) return;
+        const int need = (max_elems / 4 + 255) / 256;
+        const dim3 grid(b.first_wg[b.n]);
+        if (need <= 8) hipLaunchKernelGGL(quantize_batched_kernel<8>, grid, dim3(256), lds, st, b);
+        else if (need <= 16) hipLaunchKernelGGL(quantize_batched_kernel<16>, grid, dim3(256), lds, st, b);
+        else hipLaunchKernelGGL(quantize_batched_kernel<32>, grid, dim3(256), lds, st, b);
+        b.n = 0;
+    };
+    b.n = 0;
+    int max_elems = 0;
+    size_t lds = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const qb_quant_job &j = jobs[i];
+        const int rpg = (int)(j.N / j.groups);
+        const int64_t gelems = (int64_t)rpg * j.K;
+        if (gelems > kMaxFusedElems) {  // group too large for one workgroup: the two-pass path, on its own
+            const qb_status s = qb_quantize_groupwise(j.W, j.N, j.K, j.bits, j.groups, j.packed, j.h, j.m, j.rs_w, stream);
+            if (s != QB_OK) return s;
+            continue;
+        }
+        if (b.n == 0) { max_elems = 0; lds = 0; b.first_wg[0] = 0; }
+        const int k = b.n++;
+        b.W[k] = j.W; b.packed[k] = static_cast<uint8_t *>(j.packed); b.h[k] = j.h; b.m[k] = j.m; b.rs_w[k] = j.rs_w;
+        b.K[k] = (int)j.K; b.rows_per_group[k] = rpg; b.bits[k] = j.bits;
+        b.inv_K[k] = 1.0f / (float)j.K; b.inv_rows[k] = 1.0f / (float)rpg;
+        b.first_wg[k + 1] = b.first_wg[k] + j.groups;
+        if ((int)gelems > max_elems) max_elems = (int)gelems;
+        const size_t need_lds = (size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 16;
+        if (need_lds > lds) lds = need_lds;
+        if (b.n == QB_MAX_BATCH) flush(max_elems, lds);
+    }
+    flush(max_elems, lds);
+    return launch_status();
+}
+
 extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float clip, int8_t *Xq, int32_t *rs_x,
                                      void *stream)
 {
     if (!X || !Xq || !rs_x) return QB_ERR_NULL;
     if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
     if (!(clip > 0.0f) || !(clip < 3.0e38f)) return QB_ERR_CLIP;
-    const float hx = clip / 255.0f;
     hipLaunchKernelGGL(quantize_act_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), X, (int)T, (int)K, clip, 2.0f * hx, Xq, rs_x);
+                       static_cast<hipStream_t>(stream), X, (int)T, (int)K, clip, Xq, rs_x);
     return launch_status();
 }
 

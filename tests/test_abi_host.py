@@ -81,6 +81,18 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, ctypes.c_void_p(0x1010), NULL) == 5
     assert lib.qb_qlinear_bwd_ste(P, NULL, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, P, NULL) == 1
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, NULL, NULL, NULL, NULL) == 0  # nothing asked
+    # batched quantize: host array of descriptors, every job checked before any launch
+    from paper_1909_05840_amd.binding import _QuantJob
+    good = _QuantJob(0x1000, 768, 768, 4, 128, 0x1000, 0x1000, 0x1000, 0x1000)
+    bad_bits = _QuantJob(0x1000, 768, 768, 6, 128, 0x1000, 0x1000, 0x1000, 0x1000)
+    bad_null = _QuantJob(0x1000, 768, 768, 4, 128, 0, 0x1000, 0x1000, 0x1000)
+    arr = (_QuantJob * 2)(good, bad_bits)
+    assert lib.qb_quantize_groupwise_batched(arr, 2, NULL) == 2
+    arr = (_QuantJob * 2)(good, bad_null)
+    assert lib.qb_quantize_groupwise_batched(arr, 2, NULL) == 1
+    assert lib.qb_quantize_groupwise_batched(arr, 0, NULL) == 0
+    assert lib.qb_quantize_groupwise_batched(arr, -1, NULL) == 3
+    assert lib.qb_quantize_groupwise_batched(None, 1, NULL) == 1
     # unpack / embedding
     assert lib.qb_unpack_codes(P, 768, 768, 1, P, NULL) == 2
     assert lib.qb_embedding_quantize(P, 100, 1024, 100, P, P, P, NULL) == 3   # 1024 % 100

@@ -69,6 +69,63 @@ def test_quantize_zero_group_ties_and_extremes(qb):
         check_quantize(qb, Wt, bits, 8)
 
 
+def test_quantize_batched_matches_single_calls(qb):
+    """Configuration 4 style: 12 layers x 4 linears, each layer at its own bit-width, in batched launches
+    (more jobs than one launch holds, mixed bits, one job with groups too large for the fused path)."""
+    bits_list = wl.layer_bits(12, seed=wl.config_seed(3, 0))
+    jobs, singles = [], []
+    for layer in range(5):
+        for i, (_, N, K) in enumerate(wl.BERT_BASE_LINEARS):
+            W = wl.weight(N, K, seed=100 * layer + i).to(DEV)
+            jobs.append({"W": W, "bits": bits_list[layer], "groups": 128})
+    jobs.append({"W": wl.weight_uniform(768, 768, seed=9).to(DEV), "bits": 3, "groups": 1})  # two-pass job
+    say("batched quantize", len(jobs), "jobs")
+    outs = qb.qb_quantize_groupwise_batched(jobs)
+    for j, (packed, h, m, rs) in zip(jobs, outs):
+        p1, h1, m1, r1 = qb.qb_quantize_groupwise(j["W"], j["bits"], j["groups"])
+        torch.cuda.synchronize()
+        assert torch.equal(packed, p1) and torch.equal(h, h1) and torch.equal(m, m1) and torch.equal(rs, r1)
+    # and against the oracle for two of them
+    for idx in (0, 7):
+        j = jobs[idx]
+        N, K = j["W"].shape
+        oc, oh, om, ors = oracle.quantize_groupwise(j["W"].cpu().numpy(), j["bits"], j["groups"])
+        codes = qb.qb_unpack_codes(outs[idx][0], N, K, j["bits"])
+        assert (codes.cpu().numpy() == oc).all() and (outs[idx][3].cpu().numpy() == ors).all()
+
+
+def test_hip_graph_replays_match_eager(qb):
+    """The calls only enqueue kernels, so a captured graph must give the eager result on every replay."""
+    T, N, K, G, bits = 512, 768, 768, 128, 4
+    W = wl.weight(N, K, seed=21).to(DEV)
+    X = wl.activation(T, K, seed=22).to(DEV)
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W, bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+    Y_eager = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N).clone()
+    p_eager = packed.clone()
+    torch.cuda.synchronize()
+    Y = torch.empty_like(Y_eager)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            qb.qb_quantize_groupwise_batched([{"W": W, "bits": bits, "groups": G, "packed": packed, "h": h, "m": m,
+                                               "rs_w": rs_w}])
+            qb.qb_quantize_act(X, CLIP, Xq, rs_x)
+            qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, Y=Y)
+        for rep in range(4):
+            Y.zero_()
+            packed.zero_()
+            stream.synchronize()
+            g.replay()
+            stream.synchronize()
+            assert torch.equal(Y, Y_eager) and torch.equal(packed, p_eager), rep
+            # eager work of the program between replays
+            Y2 = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N)
+            stream.synchronize()
+            assert torch.equal(Y2, Y_eager)
+
+
 # ---- activations ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("shape", [(1024, 768), (4096, 768), (4096, 3072), (1, 64), (1023, 768), (7, 1024), (130, 4096)])
 def test_quantize_act(qb, shape):
