@@ -542,6 +542,323 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     }  // persistent tile loop
 }
 
+// Epilogue shared by the role-split kernels.  acc[tm][tn][r] belongs to neuron n_base + 32*tn (n_base
+// already contains the lane's column l32) and token t_base + 32*tm + 8*(r/4) + (r%4) (t_base already
+// contains 4*hf): for one register the lanes 0..31 cover 32 consecutive neurons of one token, i.e.
+// one full 128-byte line of Y, and lanes 32..63 the line four tokens further down.
+//   A4 = 4*acc + 2e*rs_x[t] + 2*rs_w[n] + K (exact),  Y = (h_x*h_g(n)) * float(A4) + bias[n]
+// Everything the stores depend on is loaded before the first store: a load issued between two
+// stores would wait for the older store to complete (loads and stores share one in-order counter)
+// and turn the write-out into a chain of round trips.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_fast(const v16i (&acc)[TM][TN], int e2, int t_base, int n_base, int N, int K,
+                                                int rows_per_group, float hx, const float *__restrict__ h,
+                                                const int32_t *__restrict__ rs_x, const int32_t *__restrict__ rs_w,
+                                                const float *__restrict__ bias, float *__restrict__ Y)
+{
+    int coln[TN];
+    float scale[TN], bv[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int n = n_base + tn * 32;
+        coln[tn] = 2 * rs_w[n] + K;
+        scale[tn] = hx * h[n / rows_per_group];
+        bv[tn] = bias ? bias[n] : 0.0f;
+    }
+    int rx[TM][16];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int4 v = *reinterpret_cast<const int4 *>(rs_x + t_base + tm * 32 + 8 * q);
+            rx[tm][4 * q + 0] = e2 * v.x;
+            rx[tm][4 * q + 1] = e2 * v.y;
+            rx[tm][4 * q + 2] = e2 * v.z;
+            rx[tm][4 * q + 3] = e2 * v.w;
+        }
+    uint32_t voff[16];  // byte offset of register r's element inside a 32x32 block
+#pragma unroll
+    for (int r = 0; r < 16; ++r) voff[r] = (uint32_t)(8 * (r >> 2) + (r & 3)) * (uint32_t)N * 4u;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t_base + tm * 32) * N + n_base + tn * 32);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int a4 = 4 * acc[tm][tn][r] + rx[tm][r] + coln[tn];
+                *reinterpret_cast<float *>(y_blk + voff[r]) = scale[tn] * (float)a4 + bv[tn];
+            }
+        }
+}
+
+// the same for edge tiles and the debug output: every element checked
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_checked(const v16i (&acc)[TM][TN], int e2, int t_base, int n_base, int T,
+                                                   int N, int K, int rows_per_group, float hx,
+                                                   const float *__restrict__ h, const int32_t *__restrict__ rs_x,
+                                                   const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
+                                                   float *__restrict__ Y, int32_t *__restrict__ A4out)
+{
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int n = n_base + tn * 32;
+        if (n >= N) continue;
+        const int coln = 2 * rs_w[n] + K;
+        const float scale = hx * h[n / rows_per_group];
+        const float bv = bias ? bias[n] : 0.0f;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = t_base + tm * 32 + 8 * (r >> 2) + (r & 3);
+                if (t < T) {
+                    const int a4 = 4 * acc[tm][tn][r] + e2 * rs_x[t] + coln;
+                    const size_t at = (size_t)t * N + n;
+                    Y[at] = scale * (float)a4 + bv;
+                    if (A4out) A4out[at] = a4;
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Main kernel (K a multiple of 128): the same data path as above with the work split by role.
+//   consumer wavefronts (WM x WN of them): LDS fragment reads, code expansion, MFMA, epilogue
+//   producer wavefronts (NPROD): nothing but the global -> LDS copies and the waiting for them
+// A copy instruction keeps the issuing wavefront busy for tens of cycles while the texture path
+// accepts its 64 addresses; issued from an MFMA wavefront that time is lost to the matrix cores,
+// issued from a producer it is free.  Producers also run ahead across tiles: while the consumers
+// write tile i out, the first stages of tile i+1 are already being filled.
+// Protocol per tile (n steps, ring of NSTAGE stages, copies run D = NSTAGE-1 steps ahead); every
+// wavefront executes exactly n+1 barriers:
+//   producer: start copies 0..D-1; wait copy 0; BARRIER;
+//             for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
+//                    wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
+//   consumer: BARRIER; for s: MMA on stage s % NSTAGE; BARRIER
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD>
+__global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
+    const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
+    const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
+    float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
+    int tiles_m, int tiles_n)
+{
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
+    constexpr int NC = WM * WN;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 128;
+    constexpr int SLOT = 4 * BITS;                  // bytes per slot in memory
+    constexpr int CH = (BITS == 3) ? 12 : 16;       // bytes one lane moves per weight copy instruction
+    constexpr int LSLOT = (BITS == 3) ? 16 : SLOT;  // a 12-byte copy lands at a 16-byte stride in LDS
+    constexpr int PAIR = 128 * SLOT;                // one 32-neuron block x two units, contiguous in memory
+    constexpr int LPAIR = 128 * LSLOT;
+    constexpr int PARTS = PAIR / (64 * CH);         // copy instructions per pair; each fills 1024 bytes of LDS
+    constexpr int A_TOTAL = BM / 8, B_TOTAL = (BN / 32) * PARTS;  // copy instructions per step
+    constexpr int A_PER = (A_TOTAL + NPROD - 1) / NPROD, B_PER = (B_TOTAL + NPROD - 1) / NPROD;
+    constexpr int PERP = A_PER + B_PER;             // per producer and step
+    constexpr int D = NSTAGE - 1;
+    constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
+    static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
+
+    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nsteps = K / BK;
+    const int kunits = K >> 6;
+    const int ncb = (N + 31) >> 5;
+    const int nwg = tiles_m * tiles_n;
+
+    if (wave >= NC) {
+        // ================================ producer ================================
+        const int p = wave - NC;
+        for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
+            int logical;
+            {
+                const int xcd = work & 7, idx = work >> 3;
+                const int q = nwg >> 3, r = nwg & 7;
+                logical = xcd * q + (xcd < r ? xcd : r) + idx;
+            }
+            const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+            // token rows: lane l of a copy fills physical chunk l%8 of row l/8 of an 8-row block; the
+            // chunk holds logical chunk (l%8) ^ ((row/2)%8): the swizzle that makes 16 consecutive
+            // rows of one logical chunk land in 16 different 16-byte bank groups
+            const int last_row = T - 1 - tile_m * BM;  // rows past the end re-read the last one; outputs masked
+            const int8_t *a_src[A_PER];
+            uint32_t a_dst[A_PER];
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int blk = (i * NPROD + p) % A_TOTAL;  // surplus copies repeat one: same bytes, same place
+                int row = blk * 8 + (lane >> 3);
+                const int key = (row >> 1) & 7;
+                row = row < last_row ? row : last_row;
+                a_src[i] = Xq + ((size_t)tile_m * BM + row) * K + (((lane & 7) ^ key) * 16);
+                a_dst[i] = blk * 1024;
+            }
+            const uint8_t *b_src[B_PER];
+            uint32_t b_dst[B_PER];
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int j = (i * NPROD + p) % B_TOTAL;
+                const int pair = j / PARTS, part = j - pair * PARTS;
+                int cb = tile_n * (BN / 32) + pair;
+                cb = cb < ncb ? cb : ncb - 1;  // blocks past the end re-read the last one; outputs masked
+                b_src[i] = packed + (size_t)cb * kunits * 64 * SLOT + part * 64 * CH + lane * CH;
+                b_dst[i] = A_BYTES + pair * LPAIR + part * 1024;
+            }
+            auto fetch = [&](int step, int stage) {
+                const uint32_t st_ = lds_base + stage * STAGE_BYTES;
+#pragma unroll
+                for (int i = 0; i < B_PER; ++i) {
+                    if constexpr (BITS == 3) copy12_to_lds(b_src[i] + (size_t)step * PAIR, st_ + b_dst[i]);
+                    else copy16_to_lds(b_src[i] + (size_t)step * PAIR, st_ + b_dst[i]);
+                }
+#pragma unroll
+                for (int i = 0; i < A_PER; ++i) copy16_to_lds(a_src[i] + (size_t)step * BK, st_ + a_dst[i]);
+            };
+#pragma unroll
+            for (int u = 0; u < D; ++u)
+                if (u < nsteps) fetch(u, u);
+            if (nsteps >= D) wait_vmcnt<(D - 1) * PERP>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            int stage = D % NSTAGE;  // stage of step s + D
+            for (int s = 0; s < nsteps; ++s) {
+                if (s + D < nsteps) {
+                    fetch(s + D, stage);
+                    wait_vmcnt<(D - 1) * PERP>();
+                } else {
+                    wait_vmcnt<0>();
+                }
+                stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+                __builtin_amdgcn_s_barrier();
+            }
+        }
+        return;
+    }
+
+    // ================================ consumer ================================
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int l32 = lane & 31, hf = lane >> 5;
+    // token fragments: row = wm*TM*32 + tm*32 + l32, logical chunk = kk*4 + hf*2 + sub
+    const int p0 = (hf * 2) ^ ((l32 >> 1) & 7);
+    const int frag_row = (wm * TM * 32 + l32) * BK;
+    int a_frag[4];
+    a_frag[0] = frag_row + ((p0 ^ 0) << 4);  // kk 0, sub 0
+    a_frag[1] = frag_row + ((p0 ^ 1) << 4);  // kk 0, sub 1
+    a_frag[2] = frag_row + ((p0 ^ 4) << 4);  // kk 1, sub 0
+    a_frag[3] = frag_row + ((p0 ^ 5) << 4);  // kk 1, sub 1
+    const int b_frag = A_BYTES + wn * TN * LPAIR + lane * LSLOT;  // + tn*LPAIR + kk*64*LSLOT
+
+    for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
+        int logical;
+        {
+            const int xcd = work & 7, idx = work >> 3;
+            const int q = nwg >> 3, r = nwg & 7;
+            logical = xcd * q + (xcd < r ? xcd : r) + idx;
+        }
+        const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+
+        v16i acc[TM][TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
+
+// One step: every LDS read of the step is issued first (12 reads in flight, their latency paid once),
+// then the 16 MFMAs run while the later reads are still arriving.  The scheduling barrier keeps the
+// compiler from folding the reads back into a read-wait-multiply chain.
+#define QB_MMA(stage)                                                                                     \
+    {                                                                                                     \
+        const uint8_t *st_ = lds + (stage) * STAGE_BYTES;                                                 \
+        uint32_t raw[2][TN][BITS];                                                                        \
+        v4i afr[2][2][TM];                                                                                \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn)                                             \
+                SlotRead<BITS>::get(st_ + b_frag + tn * LPAIR + kk * 64 * LSLOT, raw[kk][tn]);            \
+            _Pragma("unroll") for (int sub = 0; sub < 2; ++sub)                                           \
+                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm) afr[kk][sub][tm] =                      \
+                    *reinterpret_cast<const v4i *>(st_ + a_frag[kk * 2 + sub] + tm * 32 * BK);            \
+        }                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk) {                                                \
+            uint32_t d[TN][8];                                                                            \
+            _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                           \
+                unpack_run<BITS>(raw[kk][tn], d[tn]);                                                     \
+                if constexpr (BITS == 8) {                                                                \
+                    _Pragma("unroll") for (int i = 0; i < 8; ++i) d[tn][i] ^= 0x80808080u;                \
+                }                                                                                         \
+            }                                                                                             \
+            _Pragma("unroll") for (int sub = 0; sub < 2; ++sub) {                                         \
+                v4i b[TN];                                                                                \
+                _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                       \
+                    b[tn][0] = (int)d[tn][4 * sub + 0];                                                   \
+                    b[tn][1] = (int)d[tn][4 * sub + 1];                                                   \
+                    b[tn][2] = (int)d[tn][4 * sub + 2];                                                   \
+                    b[tn][3] = (int)d[tn][4 * sub + 3];                                                   \
+                }                                                                                         \
+                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm)                                         \
+                    _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) acc[tm][tn] =                       \
+                        __builtin_amdgcn_mfma_i32_32x32x32_i8(afr[kk][sub][tm], b[tn], acc[tm][tn], 0, 0, 0); \
+            }                                                                                             \
+        }                                                                                                 \
+    }
+// a bare barrier (no fence: the producers' vmcnt wait is what makes the copies visible); the empty
+// asm keeps the compiler from moving LDS reads across it
+#define QB_BARRIER()                                                                                      \
+    {                                                                                                     \
+        asm volatile("" ::: "memory");                                                                    \
+        __builtin_amdgcn_s_barrier();                                                                     \
+        asm volatile("" ::: "memory");                                                                    \
+    }
+
+        QB_BARRIER()
+        int s = 0;
+        for (; s + NSTAGE <= nsteps; s += NSTAGE) {
+#pragma unroll
+            for (int u = 0; u < NSTAGE; ++u) {
+                QB_MMA(u)
+                QB_BARRIER()
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NSTAGE - 1; ++u)
+            if (s + u < nsteps) {
+                QB_MMA(u)
+                QB_BARRIER()
+            }
+#undef QB_MMA
+#undef QB_BARRIER
+
+        // ---- epilogue
+        constexpr int L = (1 << BITS) - 1;
+        constexpr int E2 = (BITS == 8) ? 2 : -2 * L;  // 2*e
+        const int t_base = tile_m * BM + wm * TM * 32 + 4 * hf;
+        const int n_base = tile_n * BN + wn * TN * 32 + l32;
+        if ((tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N && A4out == nullptr)
+            store_tile_fast<TM, TN>(acc, E2, t_base, n_base, N, K, rows_per_group, hx, h, rs_x, rs_w, bias, Y);
+        else
+            store_tile_checked<TM, TN>(acc, E2, t_base, n_base, T, N, K, rows_per_group, hx, h, rs_x, rs_w, bias, Y, A4out);
+    }
+}
+
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD>
+void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
+               const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
+               int grid_cap)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    int grid = tiles_m * tiles_n;
+    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD>), dim3(grid),
+                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
+                       tiles_m, tiles_n);
+}
+
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
 void launch_cfg(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                 const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st)
@@ -574,13 +891,18 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
         return;
     }
-    // Tile choice.  Each CU can keep only a few tens of KB of copies in flight, so the bytes copied
-    // per MFMA decide the speed: 256x256 tiles (half the bytes of 128x128) whenever they still give
-    // every CU at least two tiles, 128x128 otherwise.  Grids are persistent (a multiple of 8 so that
-    // a workgroup stays inside its XCD's tile range).
+    // Tile choice (measured).  A CU pulls token tiles out of L2 / the last-level cache at a limited
+    // rate, so the bytes copied per MFMA decide the speed: 256x256 tiles (half the bytes of 128x128)
+    // whenever they still give every CU at least two tiles, 128x128 otherwise.  Grids are persistent
+    // (a multiple of 8 so that a workgroup stays inside its XCD's tile range).
     const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
-    if (tiles256 >= 512) launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
-    else launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
+    const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
+    if (tiles256 >= 512)
+        launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
+    else if (K >= 2048 && tiles128 <= 1024)  // few tiles with a long contraction: copies by dedicated wavefronts
+        launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
+    else
+        launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
 }
 
 #ifdef QB_TUNE
@@ -627,6 +949,16 @@ extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_
         case 7: QB_TB(1, 2, 4, 2, 3, 0) break;   // 128x128 8 waves 3 stages
         case 8: QB_TB(2, 2, 4, 2, 3, 0) break;   // 256x128 8 waves 3 stages
         case 9: QB_TB(4, 2, 2, 4, 2, 0) break;   // 256x256 8 waves 2 stages
+#define QB_W(B, a, b, c, d, e, f) launch_ws<B, a, b, c, d, e, f>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
+#define QB_WB(a, b, c, d, e, f) { if (bits == 2) QB_W(2, a, b, c, d, e, f); else if (bits == 3) QB_W(3, a, b, c, d, e, f); else if (bits == 4) QB_W(4, a, b, c, d, e, f); else QB_W(8, a, b, c, d, e, f); }
+        case 30: QB_WB(2, 2, 2, 2, 2, 1) break;   // ws 128x128 2 stages 1 producer
+        case 31: QB_WB(2, 2, 2, 2, 2, 2) break;   // ws 128x128 2 stages 2 producers
+        case 32: QB_WB(2, 2, 2, 2, 3, 2) break;   // ws 128x128 3 stages 2 producers
+        case 33: QB_WB(2, 2, 2, 2, 3, 4) break;   // ws 128x128 3 stages 4 producers
+        case 34: QB_WB(4, 2, 2, 2, 3, 2) break;   // ws 256x128 3 stages 2 producers
+        case 35: QB_WB(4, 4, 2, 2, 2, 2) break;   // ws 256x256 2 stages 2 producers
+        case 36: QB_WB(4, 4, 2, 2, 2, 4) break;   // ws 256x256 2 stages 4 producers
+        case 37: QB_WB(2, 2, 2, 2, 4, 2) break;   // ws 128x128 4 stages 2 producers
         // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
         case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
         case 12: QB_TB(2, 2, 2, 2, 2, 4) break;

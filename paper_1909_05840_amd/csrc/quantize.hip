@@ -181,6 +181,8 @@ __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
                                                  blockIdx.x, smem);
 }
 
+constexpr int kMaxFusedElems = 1024 * 4 * 8;  // one group in the registers of 1024 threads, 8 float4 each
+
 // Several matrices in one launch (a fine-tuning step re-quantizes every matrix of the model):
 // workgroup w serves group w - first_wg[j] of job j.  Passed by value as the kernel argument.
 struct QuantBatch {
@@ -198,8 +200,8 @@ struct QuantBatch {
     float inv_rows[QB_MAX_BATCH];
 };
 
-template <int V>
-__global__ __launch_bounds__(256) void quantize_batched_kernel(const QuantBatch b)
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void quantize_batched_kernel(const QuantBatch b)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     int j = 0;
@@ -207,10 +209,10 @@ __global__ __launch_bounds__(256) void quantize_batched_kernel(const QuantBatch 
     const int g = blockIdx.x - b.first_wg[j];
     const int rpg = b.rows_per_group[j];
     switch (b.bits[j]) {
-        case 2: quantize_panel_body<2, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 3: quantize_panel_body<3, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 4: quantize_panel_body<4, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        default: quantize_panel_body<8, 256, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 2: quantize_panel_body<2, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 3: quantize_panel_body<3, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 4: quantize_panel_body<4, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        default: quantize_panel_body<8, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
     }
 }
 
@@ -391,47 +393,33 @@ __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__
     reinterpret_cast<float4 *>(out)[id] = o;
 }
 
-constexpr int kMaxFusedElems = 256 * 4 * 32;  // one group in the registers of 256 threads
 
-template <int BITS, int V, bool FUSED>
-void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h,
-                  float *m, int32_t *rs_w, hipStream_t st)
+template <int BITS, int THREADS>
+void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h, float *m,
+                  int32_t *rs_w, hipStream_t st)
 {
-    const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 16;
-    hipLaunchKernelGGL((quantize_panel_kernel<BITS, 256, V, FUSED>), dim3(panels), dim3(256), lds, st, W, K,
+    const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 64;
+    hipLaunchKernelGGL((quantize_panel_kernel<BITS, THREADS, 8, false>), dim3(panels), dim3(THREADS), lds, st, W, K,
                        rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w);
 }
 
-template <int BITS, bool FUSED>
-void launch_panel_v(int elems, const float *W, int K, int rpg, int prow, int panels, uint8_t *packed, float *h,
-                    float *m, int32_t *rs_w, hipStream_t st)
-{
-    const int need = (elems / 4 + 255) / 256;  // float4 per thread
-    if (need <= 2) launch_panel<BITS, 2, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
-    else if (need <= 4) launch_panel<BITS, 4, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
-    else if (need <= 8) launch_panel<BITS, 8, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
-    else if (need <= 16) launch_panel<BITS, 16, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
-    else launch_panel<BITS, 32, FUSED>(W, K, rpg, prow, panels, packed, h, m, rs_w, st);
-}
-
+// groups too large for one workgroup's registers: max-abs by slices, then panels of whole rows
 template <int BITS>
-qb_status quantize_groupwise_impl(const float *W, int64_t N, int64_t K, int groups, uint8_t *packed, float *h,
-                                  float *m, int32_t *rs_w, hipStream_t st)
+qb_status quantize_two_pass(const float *W, int64_t N, int64_t K, int groups, uint8_t *packed, float *h, float *m,
+                            int32_t *rs_w, hipStream_t st)
 {
     const int rpg = (int)(N / groups);
     const int64_t gelems = (int64_t)rpg * K;
-    if (gelems <= kMaxFusedElems) {
-        launch_panel_v<BITS, true>((int)gelems, W, (int)K, rpg, rpg, groups, packed, h, m, rs_w, st);
-        return launch_status();
-    }
-    // large groups: max-abs by slices, then panels of whole rows that divide the group
     int prow = 1;
     for (int p = rpg; p >= 1; --p)
         if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
     const int slices = (int)((gelems + 65535) / 65536);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, m, groups);
     hipLaunchKernelGGL(absmax_slices_kernel, dim3(groups * slices), dim3(256), 0, st, W, gelems, slices, m);
-    launch_panel_v<BITS, false>((int)(prow * K), W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    const int64_t pelems = (int64_t)prow * K;
+    if (pelems <= 8192) launch_panel<BITS, 256>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    else if (pelems <= 16384) launch_panel<BITS, 512>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    else launch_panel<BITS, 1024>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
     return launch_status();
 }
 
@@ -440,19 +428,25 @@ qb_status quantize_groupwise_impl(const float *W, int64_t N, int64_t K, int grou
 
 using namespace qb;
 
+extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
+
 extern "C" qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int groups, void *packed,
                                            float *h, float *m, int32_t *rs_w, void *stream)
 {
     if (!W || !packed || !h || !m || !rs_w) return QB_ERR_NULL;
     if (!bits_ok(bits)) return QB_ERR_BITS;
     if (N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0) return QB_ERR_SHAPE;
+    if ((N / groups) * K <= kMaxFusedElems) {
+        const qb_quant_job job = {W, N, K, bits, groups, packed, h, m, rs_w};
+        return qb_quantize_groupwise_batched(&job, 1, stream);
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t *p = static_cast<uint8_t *>(packed);
     switch (bits) {
-        case 2: return quantize_groupwise_impl<2>(W, N, K, groups, p, h, m, rs_w, st);
-        case 3: return quantize_groupwise_impl<3>(W, N, K, groups, p, h, m, rs_w, st);
-        case 4: return quantize_groupwise_impl<4>(W, N, K, groups, p, h, m, rs_w, st);
-        default: return quantize_groupwise_impl<8>(W, N, K, groups, p, h, m, rs_w, st);
+        case 2: return quantize_two_pass<2>(W, N, K, groups, p, h, m, rs_w, st);
+        case 3: return quantize_two_pass<3>(W, N, K, groups, p, h, m, rs_w, st);
+        case 4: return quantize_two_pass<4>(W, N, K, groups, p, h, m, rs_w, st);
+        default: return quantize_two_pass<8>(W, N, K, groups, p, h, m, rs_w, st);
     }
 }
 
@@ -477,11 +471,11 @@ extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int
     QuantBatch b;
     auto flush = [&](int max_elems, size_t lds) {
         if (b.n == 0) return;
-        const int need = (max_elems / 4 + 255) / 256;
+        // a group is held in registers, eight float4 per thread: more threads for larger groups
         const dim3 grid(b.first_wg[b.n]);
-        if (need <= 8) hipLaunchKernelGGL(quantize_batched_kernel<8>, grid, dim3(256), lds, st, b);
-        else if (need <= 16) hipLaunchKernelGGL(quantize_batched_kernel<16>, grid, dim3(256), lds, st, b);
-        else hipLaunchKernelGGL(quantize_batched_kernel<32>, grid, dim3(256), lds, st, b);
+        if (max_elems <= 8192) hipLaunchKernelGGL(quantize_batched_kernel<256>, grid, dim3(256), lds, st, b);
+        else if (max_elems <= 16384) hipLaunchKernelGGL(quantize_batched_kernel<512>, grid, dim3(512), lds, st, b);
+        else hipLaunchKernelGGL(quantize_batched_kernel<1024>, grid, dim3(1024), lds, st, b);
         b.n = 0;
     };
     b.n = 0;
@@ -503,7 +497,7 @@ extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int
         b.inv_K[k] = 1.0f / (float)j.K; b.inv_rows[k] = 1.0f / (float)rpg;
         b.first_wg[k + 1] = b.first_wg[k] + j.groups;
         if ((int)gelems > max_elems) max_elems = (int)gelems;
-        const size_t need_lds = (size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 16;
+        const size_t need_lds = (size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 64;
         if (need_lds > lds) lds = need_lds;
         if (b.n == QB_MAX_BATCH) flush(max_elems, lds);
     }
