@@ -59,32 +59,69 @@ __global__ __launch_bounds__(256) void dequant_transpose_kernel(const uint8_t *_
     }
 }
 
-// out[c][r] = conv(in[r][c]) for r < R, c < C; out has leading dimension ldo >= R, columns
-// r in [R, ldo) are zero filled.  MODE 0: bf16 copy, MODE 1: int8 x' -> bf16(2x'+1).
+// out[c][r] = conv(in[r][c]) for r < R, c < C; out has leading dimension ldo >= R (a multiple of 64),
+// columns r in [R, ldo) are zero filled.  MODE 0: bf16 copy, MODE 1: int8 x' -> bf16(2x'+1).
+// A block moves a 64x64 tile through LDS: rows are read with 16-byte (MODE 0) or 8-byte (MODE 1)
+// loads when C allows it, and every thread writes 8 consecutive r of one output row with one
+// 16-byte store.
 template <int MODE>
 __global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__ in, int R, int C, int ldo,
                                                         uint16_t *__restrict__ out)
 {
     __shared__ uint16_t tile[64][66];
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        const int r = r0 + i, c = c0 + tx;
-        uint16_t v = 0;
-        if (r < R && c < C) {
-            if (MODE == 0) {
-                v = static_cast<const uint16_t *>(in)[(size_t)r * C + c];
+    const int tid = threadIdx.x;
+    const bool vec = (C % 8 == 0);  // uniform: rows are then 16-byte (MODE 0) / 8-byte (MODE 1) aligned
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int i = (tid >> 3) + it * 32;  // row of the tile
+        const int j = (tid & 7) * 8;         // first of 8 columns
+        const int r = r0 + i, c = c0 + j;
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0;
+        if (r < R) {
+            if (vec && c + 8 <= C) {
+                if (MODE == 0) {
+                    const uint4 q = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(in) + (size_t)r * C + c);
+                    v[0] = q.x & 0xFFFF; v[1] = q.x >> 16; v[2] = q.y & 0xFFFF; v[3] = q.y >> 16;
+                    v[4] = q.z & 0xFFFF; v[5] = q.z >> 16; v[6] = q.w & 0xFFFF; v[7] = q.w >> 16;
+                } else {
+                    const uint2 q = *reinterpret_cast<const uint2 *>(static_cast<const int8_t *>(in) + (size_t)r * C + c);
+                    const uint32_t w[2] = {q.x, q.y};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int x = (int)(int8_t)((w[e >> 2] >> (8 * (e & 3))) & 0xFF);
+                        v[e] = (uint16_t)(__float_as_uint((float)(2 * x + 1)) >> 16);  // exact: 8 significant bits
+                    }
+                }
             } else {
-                const int x = static_cast<const int8_t *>(in)[(size_t)r * C + c];
-                v = (uint16_t)(__float_as_uint((float)(2 * x + 1)) >> 16);  // exact: 8 significant bits
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (c + e < C) {
+                        if (MODE == 0) {
+                            v[e] = static_cast<const uint16_t *>(in)[(size_t)r * C + c + e];
+                        } else {
+                            const int x = static_cast<const int8_t *>(in)[(size_t)r * C + c + e];
+                            v[e] = (uint16_t)(__float_as_uint((float)(2 * x + 1)) >> 16);
+                        }
+                    }
             }
         }
-        tile[i][tx] = v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[i][j + e] = v[e];
     }
     __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i, r = r0 + tx;
-        if (c < C && r < ldo) out[(size_t)c * ldo + r] = tile[tx][i];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int c = (tid >> 3) + it * 32;  // output row inside the tile
+        const int rr = (tid & 7) * 8;        // first of 8 consecutive r
+        if (c0 + c < C) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[rr + 2 * e][c] | ((uint32_t)tile[rr + 2 * e + 1][c] << 16);
+            *reinterpret_cast<uint4 *>(out + (size_t)(c0 + c) * ldo + r0 + rr) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
     }
 }
 
@@ -99,121 +136,157 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const uint16_t *__restric
     out[id] = n < N ? in[t * N + n] : (uint16_t)0;
 }
 
+// global -> LDS copy by the load unit (every lane its own global address; lane l lands at m0 + 16*l).
+// Inline assembly on purpose: the kernel states itself, with s_waitcnt vmcnt(n), which copies must have
+// landed before a barrier.
+__device__ __forceinline__ void copy16_to_lds(const void *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+
 // C[M,Nc] = sum_k A[M,k] * B[Nc,k]; A, B bf16 row-major with leading dimensions lda, ldb
 // (multiples of 8), contraction range [z*ksplit, min(Kc, (z+1)*ksplit)) for blockIdx.y = z,
 // Kc and ksplit multiples of 64.  OUT 0: bf16 C (ldc = Nc);  OUT 1: fp32 C * scale;
 // OUT 2: fp32 partial sums at part + z*M*Nc.
-template <int TM, int TN, int WM, int WN, int OUT>
+// Both operand tiles (64 bf16 = 128 bytes per row and step) are copied global -> LDS by the load
+// unit through a ring of NSTAGE stages; rows are dense with their 16-byte chunks XOR-swizzled by
+// (row/2)%8, so the 16-byte MFMA fragment reads are free of bank conflicts.  The grid is persistent
+// over the tiles of one contraction split and renumbered per XCD like the forward kernel.
+template <int TM, int TN, int WM, int WN, int NSTAGE, int OUT>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_nt_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int Nc, int Kc, int lda, int ldb,
     int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n)
 {
-    constexpr int THREADS = 64 * WM * WN;
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BKB = 128, LD = BKB + 16;  // 64 bf16 per step
-    constexpr int A_PER_THREAD = BM * 8 / THREADS, B_PER_THREAD = BN * 8 / THREADS;
-    static_assert(BM * 8 % THREADS == 0 && BN * 8 % THREADS == 0, "tiles must split evenly");
-    __shared__ __align__(16) uint8_t lds_a[2][BM * LD];
-    __shared__ __align__(16) uint8_t lds_b[2][BN * LD];
+    constexpr int NW = WM * WN;
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BKB = 128;  // 64 bf16 per step
+    constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW, PER = A_DMA + B_DMA;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tiles must split into 8-row blocks per wavefront");
+    constexpr int D = NSTAGE - 1;
+    constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB;
+    static_assert((D - 1) * PER < 64, "vmcnt has six bits");
+    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
-    const int nwg = tiles_m * tiles_n;
-    int logical;
-    {
-        const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
-        const int q = nwg >> 3, r = nwg & 7;
-        logical = xcd * q + (xcd < r ? xcd : r) + idx;
-    }
-    const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave - wm * WN;
+    const int l32 = lane & 31, hf = lane >> 5;
     const int z = blockIdx.y;
     const int k_begin = z * ksplit;
     const int k_end = (k_begin + ksplit < Kc) ? k_begin + ksplit : Kc;
     const int nsteps = (k_end - k_begin) >> 6;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave / WN, wn = wave - wm * WN;
-    const int l32 = lane & 31, hf = lane >> 5;
-
-    const uint8_t *a_src[A_PER_THREAD], *b_src[B_PER_THREAD];
-    int a_dst[A_PER_THREAD], b_dst[B_PER_THREAD];
+    // fragment reads: row r, logical chunk = sub*2 + hf, physical chunk = logical ^ ((r/2)%8)
+    const int key = (l32 >> 1) & 7;
+    int a_frag[4], b_frag[4];
 #pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i) {
-        const int c = tid + i * THREADS, row = c >> 3, kc = c & 7;
-        int r = tile_m * BM + row;
-        r = r < M ? r : M - 1;
-        a_src[i] = reinterpret_cast<const uint8_t *>(A + (size_t)r * lda + k_begin) + kc * 16;
-        a_dst[i] = row * LD + kc * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < B_PER_THREAD; ++i) {
-        const int c = tid + i * THREADS, row = c >> 3, kc = c & 7;
-        int r = tile_n * BN + row;
-        r = r < Nc ? r : Nc - 1;
-        b_src[i] = reinterpret_cast<const uint8_t *>(B + (size_t)r * ldb + k_begin) + kc * 16;
-        b_dst[i] = row * LD + kc * 16;
+    for (int sub = 0; sub < 4; ++sub) {
+        a_frag[sub] = (wm * TM * 32 + l32) * BKB + (((sub * 2 + hf) ^ key) << 4);
+        b_frag[sub] = A_BYTES + (wn * TN * 32 + l32) * BKB + (((sub * 2 + hf) ^ key) << 4);
     }
 
-    v16f acc[TM][TN];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.0f;
-
-    uint4 areg[A_PER_THREAD], breg[B_PER_THREAD];
-    auto load_global = [&](int step) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) areg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + (size_t)step * BKB);
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) breg[i] = *reinterpret_cast<const uint4 *>(b_src[i] + (size_t)step * BKB);
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) *reinterpret_cast<uint4 *>(&lds_a[buf][a_dst[i]]) = areg[i];
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i) *reinterpret_cast<uint4 *>(&lds_b[buf][b_dst[i]]) = breg[i];
-    };
-
-    if (nsteps > 0) {
-        load_global(0);
-        store_lds(0);
-    }
-    __syncthreads();
-    const int a_base = (wm * TM * 32 + l32) * LD + hf * 16;
-    const int b_base = (wn * TN * 32 + l32) * LD + hf * 16;
-    for (int s = 0; s < nsteps; ++s) {
-        if (s + 1 < nsteps) load_global(s + 1);
-        const uint8_t *pa = lds_a[s & 1], *pb = lds_b[s & 1];
-#pragma unroll
-        for (int sub = 0; sub < 4; ++sub) {
-            v8bf a[TM], b[TN];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) a[tm] = *reinterpret_cast<const v8bf *>(pa + a_base + tm * 32 * LD + sub * 32);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) b[tn] = *reinterpret_cast<const v8bf *>(pb + b_base + tn * 32 * LD + sub * 32);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    const int nwg = tiles_m * tiles_n;
+    for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
+        int logical;
+        {
+            const int xcd = work & 7, idx = work >> 3;
+            const int q = nwg >> 3, r = nwg & 7;
+            logical = xcd * q + (xcd < r ? xcd : r) + idx;
         }
-        if (s + 1 < nsteps) store_lds((s + 1) & 1);
-        __syncthreads();
-    }
+        const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+
+        const uint8_t *a_src[A_DMA], *b_src[B_DMA];
+#pragma unroll
+        for (int i = 0; i < A_DMA; ++i) {
+            int row = (i * NW + wave) * 8 + (lane >> 3);
+            const int kx = (row >> 1) & 7;
+            int r = tile_m * BM + row;
+            r = r < M ? r : M - 1;  // rows past the end re-read the last one; outputs masked
+            a_src[i] = reinterpret_cast<const uint8_t *>(A + (size_t)r * lda + k_begin) + (((lane & 7) ^ kx) * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < B_DMA; ++i) {
+            int row = (i * NW + wave) * 8 + (lane >> 3);
+            const int kx = (row >> 1) & 7;
+            int r = tile_n * BN + row;
+            r = r < Nc ? r : Nc - 1;
+            b_src[i] = reinterpret_cast<const uint8_t *>(B + (size_t)r * ldb + k_begin) + (((lane & 7) ^ kx) * 16);
+        }
+        auto fetch = [&](int step, int stage) {
+            const uint32_t st_ = lds_base + stage * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < A_DMA; ++i) copy16_to_lds(a_src[i] + (size_t)step * BKB, st_ + (i * NW + wave) * 1024);
+#pragma unroll
+            for (int i = 0; i < B_DMA; ++i)
+                copy16_to_lds(b_src[i] + (size_t)step * BKB, st_ + A_BYTES + (i * NW + wave) * 1024);
+        };
+
+        v16f acc[TM][TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.0f;
 
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
+        for (int u = 0; u < D; ++u)
+            if (u < nsteps) fetch(u, u);
+        if (nsteps >= D) wait_vmcnt<(D - 1) * PER>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+
+        int stage = 0;
+        for (int s = 0; s < nsteps; ++s) {
+            const bool more = s + D < nsteps;  // uniform
+            if (more) fetch(s + D, (stage + D) % NSTAGE);
+            const uint8_t *st_ = lds + stage * STAGE_BYTES;
+            v8bf af[4][TM], bf[4][TN];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
+            for (int sub = 0; sub < 4; ++sub) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = r0 + 8 * (i >> 2) + (i & 3);
-                if (r < M && n < Nc) {
-                    const size_t at = (size_t)r * Nc + n;
-                    if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][tn][i]);
-                    else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][tn][i] * scale;
-                    else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][tn][i];
+                for (int tm = 0; tm < TM; ++tm) af[sub][tm] = *reinterpret_cast<const v8bf *>(st_ + a_frag[sub] + tm * 32 * BKB);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) bf[sub][tn] = *reinterpret_cast<const v8bf *>(st_ + b_frag[sub] + tn * 32 * BKB);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[sub][tm], bf[sub][tn], acc[tm][tn], 0, 0, 0);
+            if (more) wait_vmcnt<(D - 1) * PER>();
+            else wait_vmcnt<0>();
+            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int r = r0 + 8 * (i >> 2) + (i & 3);
+                    if (r < M && n < Nc) {
+                        const size_t at = (size_t)r * Nc + n;
+                        if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][tn][i]);
+                        else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][tn][i] * scale;
+                        else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][tn][i];
+                    }
                 }
             }
         }
@@ -234,16 +307,12 @@ template <int OUT>
 void launch_gemm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
                  float scale, void *C, hipStream_t st)
 {
-    const long big = (long)((M + 255) / 256) * ((Nc + 127) / 128) * splits;
-    if (big >= 192) {
-        const int tm = (M + 255) / 256, tn = (Nc + 127) / 128;
-        hipLaunchKernelGGL((gemm_bf16_nt_kernel<4, 2, 2, 2, OUT>), dim3(tm * tn, splits), dim3(256), 0, st, A, B, M, Nc, Kc,
-                           lda, ldb, ksplit, scale, C, tm, tn);
-    } else {
-        const int tm = (M + 127) / 128, tn = (Nc + 127) / 128;
-        hipLaunchKernelGGL((gemm_bf16_nt_kernel<2, 2, 2, 2, OUT>), dim3(tm * tn, splits), dim3(256), 0, st, A, B, M, Nc, Kc,
-                           lda, ldb, ksplit, scale, C, tm, tn);
-    }
+    // 128x128 tiles, 3 stages of 32 KB: two workgroups per CU; persistent grid of at most 512 per split
+    const int tm = (M + 127) / 128, tn = (Nc + 127) / 128;
+    int grid = tm * tn;
+    if (grid > 512) grid = 512;
+    hipLaunchKernelGGL((gemm_bf16_nt_kernel<2, 2, 2, 2, 2, OUT>), dim3(grid, splits), dim3(256), 0, st, A, B, M, Nc, Kc, lda,
+                       ldb, ksplit, scale, C, tm, tn);
 }
 
 struct BwdPlan {
@@ -257,9 +326,9 @@ BwdPlan make_plan(int64_t T, int64_t N, int64_t K)
     BwdPlan p;
     p.Np = round_up(N, 64);
     p.Tp = round_up(T, 64);
-    // split the contraction over T so that about 512 workgroups exist, at least 256 rows each
+    // split the contraction over T so that about 256 workgroups exist, at least 256 rows each
     const int64_t tiles = ((N + 127) / 128) * ((K + 127) / 128);
-    int64_t s = (512 + tiles - 1) / tiles;
+    int64_t s = (256 + tiles - 1) / tiles;
     const int64_t max_s = (p.Tp + 255) / 256;
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
