@@ -40,23 +40,29 @@ struct Quantizer {
         fast = delta >= 1.0e-30f && delta <= 1.0e30f;
     }
     __device__ __forceinline__ float half_step() const { return (m == 0.0f) ? 0.0f : __fdiv_rn(m, Lf); }
-    __device__ __forceinline__ uint32_t code(float w) const
+    // rint((w + m)/Delta) as a float.  No clamp to [0, L] is needed: |w| <= m gives 0 <= s <= 2m(1+2^-24),
+    // so 0 <= t <= L(1+2^-23) and rint(t) is already in 0..L (callers clamp activations to [-m, m] first).
+    __device__ __forceinline__ float code_f(float w) const
     {
         const float s = __fadd_rn(w, m);
-        float r;
         if (fast) {
             const float tp = __fmul_rn(s, rinv);
-            r = rintf(tp);
+            float r = rintf(tp);
             if (!(fabsf(tp - r) <= 0.4999f)) r = rintf(__fdiv_rn(s, delta));  // rare; also catches NaN
-        } else {
-            r = rintf(__fdiv_rn(s, delta));
+            return r;
         }
-        r = fminf(fmaxf(r, 0.0f), Lf);
-        return (uint32_t)r;
+        return rintf(__fdiv_rn(s, delta));
     }
+    __device__ __forceinline__ uint32_t code(float w) const { return (uint32_t)code_f(w); }
+    // four codes, one per byte (v_cvt_pk_u8_f32 converts and inserts in one instruction; its input is
+    // an integer-valued float here, so its rounding never comes into play)
     __device__ __forceinline__ uint32_t code4(const float4 v) const
     {
-        return code(v.x) | (code(v.y) << 8) | (code(v.z) << 16) | (code(v.w) << 24);
+        uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.x), 0, 0u);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.y), 1, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.z), 2, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.w), 3, q);
+        return q;
     }
 };
 
@@ -245,43 +251,65 @@ __global__ void fill_zero_kernel(float *p, int n)
     if (i < n) p[i] = 0.0f;
 }
 
-// ---- activations: one wavefront per token row -----------------------------------------------------
+// ---- activations: a wavefront walks over token rows (row = wavefront id, + number of wavefronts, ...)
+// in chunks of 256 float4; the loads of the next chunk (possibly of the next row) are in flight while
+// the current one is quantized, so the memory pipe never drains between rows.
 __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restrict__ X, int T, int K, float clip,
                                                            int8_t *__restrict__ Xq, int32_t *__restrict__ rs_x)
 {
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int nwaves = gridDim.x * 4;
+    int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= T) return;
     Quantizer qz;
     qz.set(clip, 255.0f);
-    const float4 *src = reinterpret_cast<const float4 *>(X + (size_t)row * K);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(Xq + (size_t)row * K);
     const int k4 = K >> 2;
-    uint32_t sum = 0;
-    for (int base = 0; base < k4; base += 256) {
-        float4 v[4];
+    const int chunks = (k4 + 255) >> 8;
+
+    float4 cur[4], nxt[4];
+    auto load = [&](float4 (&v)[4], int r, int c) {
+        const float4 *src = reinterpret_cast<const float4 *>(X + (size_t)r * K);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int idx = base + u * 64 + lane;
+            const int idx = (c << 8) + u * 64 + lane;
             if (idx < k4) v[u] = src[idx];
         }
+    };
+    load(cur, row, 0);
+    uint32_t sum = 0;
+    int c = 0;
+    while (true) {
+        // where the next chunk is
+        int nrow = row, nc = c + 1;
+        if (nc == chunks) { nc = 0; nrow = row + nwaves; }
+        const bool more = nrow < T;
+        if (more) load(nxt, nrow, nc);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(Xq + (size_t)row * K);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int idx = base + u * 64 + lane;
+            const int idx = (c << 8) + u * 64 + lane;
             if (idx < k4) {
-                float4 c = v[u];
-                c.x = fminf(fmaxf(c.x, -clip), clip);
-                c.y = fminf(fmaxf(c.y, -clip), clip);
-                c.z = fminf(fmaxf(c.z, -clip), clip);
-                c.w = fminf(fmaxf(c.w, -clip), clip);
-                const uint32_t q = qz.code4(c);
+                float4 v = cur[u];
+                v.x = __builtin_amdgcn_fmed3f(v.x, -clip, clip);
+                v.y = __builtin_amdgcn_fmed3f(v.y, -clip, clip);
+                v.z = __builtin_amdgcn_fmed3f(v.z, -clip, clip);
+                v.w = __builtin_amdgcn_fmed3f(v.w, -clip, clip);
+                const uint32_t q = qz.code4(v);
                 sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
                 dst[idx] = q ^ 0x80808080u;  // u - 128 as int8
             }
         }
+        if (nc == 0) {  // row finished
+            const int total = wave_sum((int)sum);
+            if (lane == 0) rs_x[row] = total - 128 * K;
+            sum = 0;
+        }
+        if (!more) break;
+        row = nrow;
+        c = nc;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
     }
-    const int total = wave_sum((int)sum);
-    if (lane == 0) rs_x[row] = total - 128 * K;
 }
 
 // ---- test hook: slots -> row-major codes -----------------------------------------------------------
@@ -511,8 +539,11 @@ extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float
     if (!X || !Xq || !rs_x) return QB_ERR_NULL;
     if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
     if (!(clip > 0.0f) || !(clip < 3.0e38f)) return QB_ERR_CLIP;
-    hipLaunchKernelGGL(quantize_act_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), X, (int)T, (int)K, clip, Xq, rs_x);
+    // at most 8 workgroups per CU; fewer rows than that: one wavefront per row
+    unsigned blocks = (unsigned)((T + 3) / 4);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(quantize_act_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), X, (int)T,
+                       (int)K, clip, Xq, rs_x);
     return launch_status();
 }
 
