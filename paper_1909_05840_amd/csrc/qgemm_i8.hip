@@ -504,7 +504,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int a4 = 4 * acc[tm][tn][i] + E2 * rx[tm][i] + coln[tn];
-                        *reinterpret_cast<float *>(y_blk + voff[i]) = scale[tn] * (float)a4 + bv[tn];
+                        __builtin_nontemporal_store(scale[tn] * (float)a4 + bv[tn], reinterpret_cast<float *>(y_blk + voff[i]));
                     }
                 }
             }
@@ -542,84 +542,59 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     }  // persistent tile loop
 }
 
-// Epilogue shared by the role-split kernels.  acc[tm][tn][r] belongs to neuron n_base + 32*tn (n_base
-// already contains the lane's column l32) and token t_base + 32*tm + 8*(r/4) + (r%4) (t_base already
-// contains 4*hf): for one register the lanes 0..31 cover 32 consecutive neurons of one token, i.e.
-// one full 128-byte line of Y, and lanes 32..63 the line four tokens further down.
-//   A4 = 4*acc + 2e*rs_x[t] + 2*rs_w[n] + K (exact),  Y = (h_x*h_g(n)) * float(A4) + bias[n]
-// Everything the stores depend on is loaded before the first store: a load issued between two
-// stores would wait for the older store to complete (loads and stores share one in-order counter)
-// and turn the write-out into a chain of round trips.
-template <int TM, int TN>
-__device__ __forceinline__ void store_tile_fast(const v16i (&acc)[TM][TN], int e2, int t_base, int n_base, int N, int K,
-                                                int rows_per_group, float hx, const float *__restrict__ h,
-                                                const int32_t *__restrict__ rs_x, const int32_t *__restrict__ rs_w,
-                                                const float *__restrict__ bias, float *__restrict__ Y)
+// 4-byte form of the global -> LDS copy: lane l's dword lands at m0 + 4*l
+__device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_addr)
 {
-    int coln[TN];
-    float scale[TN], bv[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int n = n_base + tn * 32;
-        coln[tn] = 2 * rs_w[n] + K;
-        scale[tn] = hx * h[n / rows_per_group];
-        bv[tn] = bias ? bias[n] : 0.0f;
-    }
-    int rx[TM][16];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int4 v = *reinterpret_cast<const int4 *>(rs_x + t_base + tm * 32 + 8 * q);
-            rx[tm][4 * q + 0] = e2 * v.x;
-            rx[tm][4 * q + 1] = e2 * v.y;
-            rx[tm][4 * q + 2] = e2 * v.z;
-            rx[tm][4 * q + 3] = e2 * v.w;
-        }
-    uint32_t voff[16];  // byte offset of register r's element inside a 32x32 block
-#pragma unroll
-    for (int r = 0; r < 16; ++r) voff[r] = (uint32_t)(8 * (r >> 2) + (r & 3)) * (uint32_t)N * 4u;
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t_base + tm * 32) * N + n_base + tn * 32);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int a4 = 4 * acc[tm][tn][r] + rx[tm][r] + coln[tn];
-                *reinterpret_cast<float *>(y_blk + voff[r]) = scale[tn] * (float)a4 + bv[tn];
-            }
-        }
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
-// the same for edge tiles and the debug output: every element checked
-template <int TM, int TN>
-__device__ __forceinline__ void store_tile_checked(const v16i (&acc)[TM][TN], int e2, int t_base, int n_base, int T,
-                                                   int N, int K, int rows_per_group, float hx,
-                                                   const float *__restrict__ h, const int32_t *__restrict__ rs_x,
-                                                   const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
-                                                   float *__restrict__ Y, int32_t *__restrict__ A4out)
+// Epilogue of the role-split kernel.  Its per-token and per-neuron parameters do not come from global
+// memory but from a block in LDS that a producer wavefront filled for the tile (BM ints rs_x, then BN
+// each of rs_w, h of the neuron's group, bias; indices past the end of the matrix were clamped).  The
+// consumer wavefronts thus issue no global loads at all: their memory counter holds stores only and is
+// never waited on, so the stores of one tile need not have completed before the next tile's go out.
+// acc[tm][tn][r]: token tl + 32*tm + 8*(r/4) + (r%4) of the tile (tl contains 4*hf), neuron nl + 32*tn
+// (nl contains l32).  A4 = 4*acc + 2e*rs_x[t] + 2*rs_w[n] + K,  Y = (h_x*h_g(n)) * float(A4) + bias[n].
+template <int BM, int BN>
+__device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *pp, int e2, int tl, int nl, int t0, int n0,
+                                                int T, int N, int K, float hx, bool has_bias, bool fast,
+                                                float *__restrict__ Y, int32_t *__restrict__ A4out)
 {
+    // one 32x32 block: acc[r] is token tl + 8*(r/4) + (r%4) of the tile, neuron nl
+    const int *p_rx = reinterpret_cast<const int *>(pp);
+    const int *p_rw = p_rx + BM;
+    const float *p_h = reinterpret_cast<const float *>(p_rw + BN), *p_b = p_h + BN;
+    const int coln = 2 * p_rw[nl] + K;
+    const float scale = hx * p_h[nl];
+    const float bv = has_bias ? p_b[nl] : 0.0f;
+    int rx[16];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int n = n_base + tn * 32;
-        if (n >= N) continue;
-        const int coln = 2 * rs_w[n] + K;
-        const float scale = hx * h[n / rows_per_group];
-        const float bv = bias ? bias[n] : 0.0f;
+    for (int q = 0; q < 4; ++q) {
+        const int4 v = *reinterpret_cast<const int4 *>(p_rx + tl + 8 * q);
+        rx[4 * q + 0] = e2 * v.x + coln;
+        rx[4 * q + 1] = e2 * v.y + coln;
+        rx[4 * q + 2] = e2 * v.z + coln;
+        rx[4 * q + 3] = e2 * v.w + coln;
+    }
+    if (fast) {
+        char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+        for (int r = 0; r < 16; ++r) {
+            const int a4 = 4 * acc[r] + rx[r];
+            __builtin_nontemporal_store(scale * (float)a4 + bv,
+                                        reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
+        }
+    } else if (n0 + nl < N) {  // edge tiles and the debug output: every element checked
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int t = t_base + tm * 32 + 8 * (r >> 2) + (r & 3);
-                if (t < T) {
-                    const int a4 = 4 * acc[tm][tn][r] + e2 * rs_x[t] + coln;
-                    const size_t at = (size_t)t * N + n;
-                    Y[at] = scale * (float)a4 + bv;
-                    if (A4out) A4out[at] = a4;
-                }
+        for (int r = 0; r < 16; ++r) {
+            const int t = t0 + tl + 8 * (r >> 2) + (r & 3);
+            if (t < T) {
+                const int a4 = 4 * acc[r] + rx[r];
+                const size_t at = (size_t)t * N + n0 + nl;
+                Y[at] = scale * (float)a4 + bv;
+                if (A4out) A4out[at] = a4;
             }
+        }
     }
 }
 
@@ -659,8 +634,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int D = NSTAGE - 1;
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
     static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
+    constexpr int PARAM_BYTES = (BM + 3 * BN) * 4;  // rs_x | rs_w | h of the neuron's group | bias
+    // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
+    // barrier of the next tile; the producer rewrites the block two tiles later, after the next tile's
+    // last barrier.  Hence two blocks.
+    constexpr int NPARAM = 2;
 
-    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES];
+    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES + NPARAM * PARAM_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -673,6 +653,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     if (wave >= NC) {
         // ================================ producer ================================
         const int p = wave - NC;
+        int pb = 0;
         for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
             int logical;
             {
@@ -717,6 +698,24 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #pragma unroll
                 for (int i = 0; i < A_PER; ++i) copy16_to_lds(a_src[i] + (size_t)step * BK, st_ + a_dst[i]);
             };
+            if (p == 0) {  // the tile's epilogue parameters: older than step 0's copies, so they land before them
+                const uint32_t pbase = lds_base + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES;
+#pragma unroll
+                for (int c = 0; c < BM / 64; ++c) {
+                    int t = tile_m * BM + c * 64 + lane;
+                    t = t < T ? t : T - 1;
+                    copy4_to_lds(rs_x + t, pbase + c * 256);
+                }
+#pragma unroll
+                for (int c = 0; c < BN / 64; ++c) {
+                    int n = tile_n * BN + c * 64 + lane;
+                    n = n < N ? n : N - 1;
+                    copy4_to_lds(rs_w + n, pbase + BM * 4 + c * 256);
+                    copy4_to_lds(h + n / rows_per_group, pbase + (BM + BN) * 4 + c * 256);
+                    if (bias) copy4_to_lds(bias + n, pbase + (BM + 2 * BN) * 4 + c * 256);
+                }
+            }
+            pb ^= 1;
 #pragma unroll
             for (int u = 0; u < D; ++u)
                 if (u < nsteps) fetch(u, u);
@@ -750,6 +749,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     a_frag[2] = frag_row + ((p0 ^ 4) << 4);  // kk 1, sub 0
     a_frag[3] = frag_row + ((p0 ^ 5) << 4);  // kk 1, sub 1
     const int b_frag = A_BYTES + wn * TN * LPAIR + lane * LSLOT;  // + tn*LPAIR + kk*64*LSLOT
+    constexpr int L = (1 << BITS) - 1;
+    constexpr int E2 = (BITS == 8) ? 2 : -2 * L;  // 2*e
+    int pb = 0;
+
+    v16i acc[TM][TN];
 
     for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
         int logical;
@@ -760,7 +764,6 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
         }
         const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
 
-        v16i acc[TM][TN];
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -833,15 +836,16 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #undef QB_MMA
 #undef QB_BARRIER
 
-        // ---- epilogue
-        constexpr int L = (1 << BITS) - 1;
-        constexpr int E2 = (BITS == 8) ? 2 : -2 * L;  // 2*e
-        const int t_base = tile_m * BM + wm * TM * 32 + 4 * hf;
-        const int n_base = tile_n * BN + wn * TN * 32 + l32;
-        if ((tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N && A4out == nullptr)
-            store_tile_fast<TM, TN>(acc, E2, t_base, n_base, N, K, rows_per_group, hx, h, rs_x, rs_w, bias, Y);
-        else
-            store_tile_checked<TM, TN>(acc, E2, t_base, n_base, T, N, K, rows_per_group, hx, h, rs_x, rs_w, bias, Y, A4out);
+        // ---- write-out
+        const bool fast = (tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N && A4out == nullptr;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                store_block_lds<BM, BN>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
+                                        (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, tile_m * BM, tile_n * BN,
+                                        T, N, K, hx, bias != nullptr, fast, Y, A4out);
+        pb ^= 1;
     }
 }
 
@@ -891,15 +895,19 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
         return;
     }
-    // Tile choice (measured).  A CU pulls token tiles out of L2 / the last-level cache at a limited
+    // Tile choice (measured).  A CU pulls operand tiles out of L2 / the last-level cache at a limited
+    // rate, and on top of that copies issued next to 32x32 MFMAs run at about half their stand-alone
     // rate, so the bytes copied per MFMA decide the speed: 256x256 tiles (half the bytes of 128x128)
-    // whenever they still give every CU at least two tiles, 128x128 otherwise.  Grids are persistent
-    // (a multiple of 8 so that a workgroup stays inside its XCD's tile range).
+    // whenever they still give every CU at least two tiles, 128x128 otherwise.  With 128x128 tiles the
+    // role-split kernel (one workgroup per CU, copies run ahead across tiles) wins when a CU gets few
+    // tiles or the contraction is long; with many short tiles per CU two plain workgroups per CU win,
+    // because one's write-out overlaps the other's MFMAs.  Grids are persistent and a multiple of 8, so
+    // that a workgroup stays inside its XCD's tile range.
     const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     if (tiles256 >= 512)
         launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
-    else if (K >= 2048 && tiles128 <= 1024)  // few tiles with a long contraction: copies by dedicated wavefronts
+    else if (tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))
         launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
     else
         launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
@@ -963,6 +971,11 @@ extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_
         case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
         case 12: QB_TB(2, 2, 2, 2, 2, 4) break;
         case 14: QB_TB(2, 2, 2, 2, 2, 7) break;
+        case 11: QB_TB(2, 2, 2, 2, 2, 2) break;
+        case 13: QB_TB(2, 2, 2, 2, 2, 6) break;
+        case 15: QB_TB(2, 2, 2, 2, 2, 5) break;
+        case 16: QB_TB(2, 2, 2, 2, 3, 4) break;
+        case 17: QB_TB(2, 2, 2, 2, 3, 6) break;
         default: return -1;
     }
     return hipGetLastError() == hipSuccess ? 0 : 6;
