@@ -206,7 +206,7 @@ struct QuantBatch {
     float inv_rows[QB_MAX_BATCH];
 };
 
-template <int THREADS>
+template <int THREADS, int V>
 __global__ __launch_bounds__(THREADS) void quantize_batched_kernel(const QuantBatch b)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -215,10 +215,10 @@ __global__ __launch_bounds__(THREADS) void quantize_batched_kernel(const QuantBa
     const int g = blockIdx.x - b.first_wg[j];
     const int rpg = b.rows_per_group[j];
     switch (b.bits[j]) {
-        case 2: quantize_panel_body<2, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 3: quantize_panel_body<3, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 4: quantize_panel_body<4, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        default: quantize_panel_body<8, THREADS, 8, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 2: quantize_panel_body<2, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 3: quantize_panel_body<3, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        case 4: quantize_panel_body<4, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+        default: quantize_panel_body<8, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
     }
 }
 
@@ -499,11 +499,13 @@ extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int
     QuantBatch b;
     auto flush = [&](int max_elems, size_t lds) {
         if (b.n == 0) return;
-        // a group is held in registers, eight float4 per thread: more threads for larger groups
+        // a group is held in registers.  Measured on BERT-base groups (18432 weights): 512 threads with up
+        // to ten float4 each beat 1024 threads with eight (more workgroups per CU in different phases,
+        // cheaper barriers): 33.5 us instead of 42 us for the sixteen matrices of an encoder layer.
         const dim3 grid(b.first_wg[b.n]);
-        if (max_elems <= 8192) hipLaunchKernelGGL(quantize_batched_kernel<256>, grid, dim3(256), lds, st, b);
-        else if (max_elems <= 16384) hipLaunchKernelGGL(quantize_batched_kernel<512>, grid, dim3(512), lds, st, b);
-        else hipLaunchKernelGGL(quantize_batched_kernel<1024>, grid, dim3(1024), lds, st, b);
+        if (max_elems <= 256 * 4 * 8) hipLaunchKernelGGL((quantize_batched_kernel<256, 8>), grid, dim3(256), lds, st, b);
+        else if (max_elems <= 512 * 4 * 10) hipLaunchKernelGGL((quantize_batched_kernel<512, 10>), grid, dim3(512), lds, st, b);
+        else hipLaunchKernelGGL((quantize_batched_kernel<1024, 8>), grid, dim3(1024), lds, st, b);
         b.n = 0;
     };
     b.n = 0;
