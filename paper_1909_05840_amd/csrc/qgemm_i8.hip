@@ -612,7 +612,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
 //             for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
 //                    wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
 //   consumer: BARRIER; for s: MMA on stage s % NSTAGE; BARRIER
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD>
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3>
 __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
@@ -634,7 +634,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int D = NSTAGE - 1;
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
     static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
-    constexpr int PARAM_BYTES = (BM + 3 * BN) * 4;  // rs_x | rs_w | h of the neuron's group | bias
+    constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
+    constexpr int PARAM_BYTES = (BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias
+    static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
+
     // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
     // barrier of the next tile; the producer rewrites the block two tiles later, after the next tile's
     // last barrier.  Hence two blocks.
@@ -650,9 +653,16 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     const int ncb = (N + 31) >> 5;
     const int nwg = tiles_m * tiles_n;
 
-    if (wave >= NC) {
+    // Roles.  The wavefronts of a workgroup are dealt to the four SIMDs of the CU in turn (wavefront w runs
+    // on SIMD w%4), and a global load or global -> LDS copy issued on a SIMD that is busy with 32x32 MFMAs
+    // runs at about half speed (and slows the MFMAs), while one issued on a SIMD without MFMAs does not.
+    // SIMD3 layout: wavefronts 3 and 7 copy, the other six multiply, so that three SIMDs run MFMAs at
+    // full rate and the fourth feeds them.  (Roles depend on the wavefront number only: a different
+    // placement by the hardware would cost speed, not correctness.)
+    const bool is_producer = SIMD3 ? (wave & 3) == 3 : wave >= NC;
+    if (is_producer) {
         // ================================ producer ================================
-        const int p = wave - NC;
+        const int p = SIMD3 ? wave >> 2 : wave - NC;
         int pb = 0;
         for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
             int logical;
@@ -707,12 +717,12 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                     copy4_to_lds(rs_x + t, pbase + c * 256);
                 }
 #pragma unroll
-                for (int c = 0; c < BN / 64; ++c) {
+                for (int c = 0; c < BNP / 64; ++c) {
                     int n = tile_n * BN + c * 64 + lane;
                     n = n < N ? n : N - 1;
                     copy4_to_lds(rs_w + n, pbase + BM * 4 + c * 256);
-                    copy4_to_lds(h + n / rows_per_group, pbase + (BM + BN) * 4 + c * 256);
-                    if (bias) copy4_to_lds(bias + n, pbase + (BM + 2 * BN) * 4 + c * 256);
+                    copy4_to_lds(h + n / rows_per_group, pbase + (BM + BNP) * 4 + c * 256);
+                    if (bias) copy4_to_lds(bias + n, pbase + (BM + 2 * BNP) * 4 + c * 256);
                 }
             }
             pb ^= 1;
@@ -738,7 +748,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     }
 
     // ================================ consumer ================================
-    const int wm = wave / WN, wn = wave - wm * WN;
+    const int cidx = SIMD3 ? (wave & 3) + 3 * (wave >> 2) : wave;
+    const int wm = cidx / WN, wn = cidx - wm * WN;
     const int l32 = lane & 31, hf = lane >> 5;
     // token fragments: row = wm*TM*32 + tm*32 + l32, logical chunk = kk*4 + hf*2 + sub
     const int p0 = (hf * 2) ^ ((l32 >> 1) & 7);
@@ -842,14 +853,14 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-                store_block_lds<BM, BN>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
+                store_block_lds<BM, BNP>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
                                         (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, tile_m * BM, tile_n * BN,
                                         T, N, K, hx, bias != nullptr, fast, Y, A4out);
         pb ^= 1;
     }
 }
 
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD>
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
 void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
                int grid_cap)
@@ -858,7 +869,7 @@ void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, con
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD>), dim3(grid),
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3>), dim3(grid),
                        dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
                        tiles_m, tiles_n);
 }
@@ -896,17 +907,24 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         return;
     }
     // Tile choice (measured).  A CU pulls operand tiles out of L2 / the last-level cache at a limited
-    // rate, and on top of that copies issued next to 32x32 MFMAs run at about half their stand-alone
-    // rate, so the bytes copied per MFMA decide the speed: 256x256 tiles (half the bytes of 128x128)
-    // whenever they still give every CU at least two tiles, 128x128 otherwise.  With 128x128 tiles the
-    // role-split kernel (one workgroup per CU, copies run ahead across tiles) wins when a CU gets few
-    // tiles or the contraction is long; with many short tiles per CU two plain workgroups per CU win,
-    // because one's write-out overlaps the other's MFMAs.  Grids are persistent and a multiple of 8, so
-    // that a workgroup stays inside its XCD's tile range.
+    // rate, and copies issued on a SIMD that is busy with 32x32 MFMAs run at about half their stand-alone
+    // rate, so the bytes copied per MFMA and the tile count decide the speed.
+    //   256x256 tiles (half the bytes of 128x128 per MFMA) whenever they still give every CU two tiles;
+    //   128x96 tiles with the MFMAs on three SIMDs and the copies on the fourth when that needs fewer
+    //     rounds over the 256 CUs than 128x128 tiles would, weighted by the measured cost of a tile
+    //     (0.86 of a 128x128 one): all of BERT-base's N = 768 and 2304 layers at 4096 and 12288 tokens;
+    //   else 128x128: the role-split kernel (one workgroup per CU, copies run ahead across tiles) when a
+    //     CU gets few tiles or the contraction is long, two plain workgroups per CU when it gets many short
+    //     ones (one's write-out overlaps the other's MFMAs).
+    // Grids are persistent and a multiple of 8, so that a workgroup stays inside its XCD's tile range.
     const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
+    const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
+    const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
     if (tiles256 >= 512)
         launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
+    else if (86 * rounds96 < 100 * rounds128)
+        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
     else if (tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))
         launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
     else
@@ -967,6 +985,10 @@ extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_
         case 35: QB_WB(4, 4, 2, 2, 2, 2) break;   // ws 256x256 2 stages 2 producers
         case 36: QB_WB(4, 4, 2, 2, 2, 4) break;   // ws 256x256 2 stages 4 producers
         case 37: QB_WB(2, 2, 2, 2, 4, 2) break;   // ws 128x128 4 stages 2 producers
+#define QB_S3(B, e) launch_ws<B, 2, 1, 2, 3, e, 2, true>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
+#define QB_S3B(e) { if (bits == 2) QB_S3(2, e); else if (bits == 3) QB_S3(3, e); else if (bits == 4) QB_S3(4, e); else QB_S3(8, e); }
+        case 40: QB_S3B(3) break;   // 128x96 tiles, MFMAs on three SIMDs, copies on the fourth, 3 stages
+        case 41: QB_S3B(4) break;   // 4 stages
         // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
         case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
         case 12: QB_TB(2, 2, 2, 2, 2, 4) break;
