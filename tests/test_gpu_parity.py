@@ -236,6 +236,38 @@ def test_forward_config4_mixed_bits(qb):
         sampled_fwd_check(qb, 12288, 768, 3072, 128, b, seed=wl.config_seed(3, b), n_samples=1024)
 
 
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(4096, 768, 768), (4096, 2304, 768), (4096, 3072, 768), (4096, 768, 3072),
+                                   (4096, 1024, 1024), (32768, 1024, 1024), (2048, 768, 192), (1000, 130, 256),
+                                   (300, 96, 128), (129, 200, 384)])
+def test_forward_plain_call_matches_checked_call(qb, bits, shape):
+    """The call as bench.py makes it (no debug output: interior tiles take the straight-line streaming-store
+    path) must give bit for bit the Y of the call with the debug output (every element checked), which the
+    other tests compare with the oracle.  The shapes walk through every branch of the tile dispatch: 128x96
+    tiles on three SIMDs, role-split 128x128, two plain workgroups per CU, 256x256 tiles, the register-staged
+    kernel for K not a multiple of 128, ragged T and N, N not a multiple of 4; with and without bias."""
+    T, N, K = shape
+    G = 128 if N % 128 == 0 else (N // 2 if N % 2 == 0 else 1)
+    say("fwd plain vs checked", shape, "bits", bits)
+    W = wl.weight(N, K, seed=7 * N + K + bits).to(DEV)
+    X = wl.activation(T, K, seed=T + 3 * K + bits).to(DEV)
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W, bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+    for bias in (None, wl.activation(1, N, seed=5)[0].contiguous().to(DEV)):
+        Y_checked, A4 = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, bias=bias, want_a4=True)
+        Y_plain = torch.full((T, N), float("nan"), dtype=torch.float32, device=DEV)
+        qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, bias=bias, Y=Y_plain)
+        torch.cuda.synchronize()
+        assert torch.equal(Y_plain, Y_checked)
+    # and the integer against the oracle on sampled outputs
+    r = np.random.default_rng(T + N + K)
+    ts, ns = r.integers(0, T, 512), r.integers(0, N, 512)
+    oc, oh, _, _ = oracle.quantize_groupwise(W.cpu().numpy(), bits, G)
+    oq, _ = oracle.quantize_act(X.cpu().numpy(), CLIP)
+    Ys, A4s = oracle.qlinear_fwd_sampled(oq, CLIP, oc, oh, bits, ts, ns)
+    assert (A4.cpu().numpy()[ts, ns] == A4s).all()
+
+
 # ---- backward ----------------------------------------------------------------------------------------
 def rel_fro(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
