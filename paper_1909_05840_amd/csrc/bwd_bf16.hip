@@ -158,135 +158,161 @@ __device__ __forceinline__ void wait_vmcnt()
 // unit through a ring of NSTAGE stages; rows are dense with their 16-byte chunks XOR-swizzled by
 // (row/2)%8, so the 16-byte MFMA fragment reads are free of bank conflicts.  The grid is persistent
 // over the tiles of one contraction split and renumbered per XCD like the forward kernel.
-template <int TM, int TN, int WM, int WN, int NSTAGE, int OUT>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_nt_kernel(
+// The work is split by role and by SIMD.  The wavefronts of a workgroup are dealt to the
+// four SIMDs of the CU in turn (wavefront w on SIMD w%4), and a global -> LDS copy issued on a SIMD that is
+// busy with 32x32 MFMAs runs at about half speed (and slows the MFMAs), while one issued on a SIMD without
+// MFMAs does not.  Hence: wavefronts 3 and 7 (SIMD 3) do nothing but copy, wavefronts 0,1,2,4,5,6 multiply,
+// 64 x 32 outputs each in a 2 x 3 grid: tiles of 128 x 96.  Per step and tile, 28 KB are copied for 522
+// cycles of MFMAs on each of three SIMDs.  (Roles depend on the wavefront number only: a different
+// placement by the hardware would cost speed, not correctness.)
+// Protocol per tile (n steps, ring of NSTAGE stages, copies run D = NSTAGE-1 steps ahead); every wavefront
+// executes n+1 barriers:
+//   copy wavefronts: start copies 0..D-1; wait copy 0; BARRIER;
+//                    for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
+//                           wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
+//   MFMA wavefronts: BARRIER; for s: multiply stage s % NSTAGE; BARRIER
+template <int NSTAGE, int OUT>
+__global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int Nc, int Kc, int lda, int ldb,
     int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n)
 {
-    constexpr int NW = WM * WN;
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BKB = 128;  // 64 bf16 per step
-    constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW, PER = A_DMA + B_DMA;
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tiles must split into 8-row blocks per wavefront");
+    constexpr int TM = 2, WN = 3, NPROD = 2;
+    constexpr int BM = 128, BN = 96, BKB = 128;  // 64 bf16 per step
+    constexpr int A_TOTAL = BM / 8, B_TOTAL = BN / 8;
+    constexpr int A_PER = A_TOTAL / NPROD, B_PER = B_TOTAL / NPROD, PERP = A_PER + B_PER;
     constexpr int D = NSTAGE - 1;
     constexpr int A_BYTES = BM * BKB, STAGE_BYTES = (BM + BN) * BKB;
-    static_assert((D - 1) * PER < 64, "vmcnt has six bits");
+    static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
     __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave - wm * WN;
-    const int l32 = lane & 31, hf = lane >> 5;
     const int z = blockIdx.y;
     const int k_begin = z * ksplit;
     const int k_end = (k_begin + ksplit < Kc) ? k_begin + ksplit : Kc;
     const int nsteps = (k_end - k_begin) >> 6;
+    const int nwg = tiles_m * tiles_n;
+    auto tile_of = [&](int work, int &tile_m, int &tile_n) {
+        const int xcd = work & 7, idx = work >> 3;
+        const int q = nwg >> 3, r = nwg & 7;
+        const int logical = xcd * q + (xcd < r ? xcd : r) + idx;
+        tile_m = logical / tiles_n;
+        tile_n = logical - tile_m * tiles_n;
+    };
 
+    if ((wave & 3) == 3) {
+        // ================================ copies ================================
+        const int p = wave >> 2;
+        for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
+            int tile_m, tile_n;
+            tile_of(work, tile_m, tile_n);
+            const uint8_t *a_src[A_PER], *b_src[B_PER];
+            uint32_t a_dst[A_PER], b_dst[B_PER];
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int blk = i * NPROD + p;
+                const int row = blk * 8 + (lane >> 3);
+                const int kx = (row >> 1) & 7;
+                int r = tile_m * BM + row;
+                r = r < M ? r : M - 1;  // rows past the end re-read the last one; outputs masked
+                a_src[i] = reinterpret_cast<const uint8_t *>(A + (size_t)r * lda + k_begin) + (((lane & 7) ^ kx) * 16);
+                a_dst[i] = blk * 1024;
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int blk = i * NPROD + p;
+                const int row = blk * 8 + (lane >> 3);
+                const int kx = (row >> 1) & 7;
+                int r = tile_n * BN + row;
+                r = r < Nc ? r : Nc - 1;
+                b_src[i] = reinterpret_cast<const uint8_t *>(B + (size_t)r * ldb + k_begin) + (((lane & 7) ^ kx) * 16);
+                b_dst[i] = A_BYTES + blk * 1024;
+            }
+            auto fetch = [&](int step, int stage) {
+                const uint32_t st_ = lds_base + stage * STAGE_BYTES;
+#pragma unroll
+                for (int i = 0; i < A_PER; ++i) copy16_to_lds(a_src[i] + (size_t)step * BKB, st_ + a_dst[i]);
+#pragma unroll
+                for (int i = 0; i < B_PER; ++i) copy16_to_lds(b_src[i] + (size_t)step * BKB, st_ + b_dst[i]);
+            };
+#pragma unroll
+            for (int u = 0; u < D; ++u)
+                if (u < nsteps) fetch(u, u);
+            if (nsteps >= D) wait_vmcnt<(D - 1) * PERP>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            int stage = D % NSTAGE;  // stage of step s + D
+            for (int s = 0; s < nsteps; ++s) {
+                if (s + D < nsteps) {
+                    fetch(s + D, stage);
+                    wait_vmcnt<(D - 1) * PERP>();
+                } else {
+                    wait_vmcnt<0>();
+                }
+                stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+                __builtin_amdgcn_s_barrier();
+            }
+        }
+        return;
+    }
+
+    // ================================ MFMA ================================
+    const int cidx = (wave & 3) + 3 * (wave >> 2);
+    const int wm = cidx / WN, wn = cidx - wm * WN;
+    const int l32 = lane & 31, hf = lane >> 5;
     // fragment reads: row r, logical chunk = sub*2 + hf, physical chunk = logical ^ ((r/2)%8)
     const int key = (l32 >> 1) & 7;
     int a_frag[4], b_frag[4];
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
         a_frag[sub] = (wm * TM * 32 + l32) * BKB + (((sub * 2 + hf) ^ key) << 4);
-        b_frag[sub] = A_BYTES + (wn * TN * 32 + l32) * BKB + (((sub * 2 + hf) ^ key) << 4);
+        b_frag[sub] = A_BYTES + (wn * 32 + l32) * BKB + (((sub * 2 + hf) ^ key) << 4);
     }
-
-    const int nwg = tiles_m * tiles_n;
     for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
-        int logical;
-        {
-            const int xcd = work & 7, idx = work >> 3;
-            const int q = nwg >> 3, r = nwg & 7;
-            logical = xcd * q + (xcd < r ? xcd : r) + idx;
-        }
-        const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
-
-        const uint8_t *a_src[A_DMA], *b_src[B_DMA];
-#pragma unroll
-        for (int i = 0; i < A_DMA; ++i) {
-            int row = (i * NW + wave) * 8 + (lane >> 3);
-            const int kx = (row >> 1) & 7;
-            int r = tile_m * BM + row;
-            r = r < M ? r : M - 1;  // rows past the end re-read the last one; outputs masked
-            a_src[i] = reinterpret_cast<const uint8_t *>(A + (size_t)r * lda + k_begin) + (((lane & 7) ^ kx) * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < B_DMA; ++i) {
-            int row = (i * NW + wave) * 8 + (lane >> 3);
-            const int kx = (row >> 1) & 7;
-            int r = tile_n * BN + row;
-            r = r < Nc ? r : Nc - 1;
-            b_src[i] = reinterpret_cast<const uint8_t *>(B + (size_t)r * ldb + k_begin) + (((lane & 7) ^ kx) * 16);
-        }
-        auto fetch = [&](int step, int stage) {
-            const uint32_t st_ = lds_base + stage * STAGE_BYTES;
-#pragma unroll
-            for (int i = 0; i < A_DMA; ++i) copy16_to_lds(a_src[i] + (size_t)step * BKB, st_ + (i * NW + wave) * 1024);
-#pragma unroll
-            for (int i = 0; i < B_DMA; ++i)
-                copy16_to_lds(b_src[i] + (size_t)step * BKB, st_ + A_BYTES + (i * NW + wave) * 1024);
-        };
-
-        v16f acc[TM][TN];
+        int tile_m, tile_n;
+        tile_of(work, tile_m, tile_n);
+        v16f acc[TM];
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.0f;
-
-#pragma unroll
-        for (int u = 0; u < D; ++u)
-            if (u < nsteps) fetch(u, u);
-        if (nsteps >= D) wait_vmcnt<(D - 1) * PER>();
-        else wait_vmcnt<0>();
+            for (int i = 0; i < 16; ++i) acc[tm][i] = 0.0f;
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-
         int stage = 0;
         for (int s = 0; s < nsteps; ++s) {
-            const bool more = s + D < nsteps;  // uniform
-            if (more) fetch(s + D, (stage + D) % NSTAGE);
             const uint8_t *st_ = lds + stage * STAGE_BYTES;
-            v8bf af[4][TM], bf[4][TN];
+            v8bf af[4][TM], bf[4];
 #pragma unroll
             for (int sub = 0; sub < 4; ++sub) {
+                bf[sub] = *reinterpret_cast<const v8bf *>(st_ + b_frag[sub]);
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) af[sub][tm] = *reinterpret_cast<const v8bf *>(st_ + a_frag[sub] + tm * 32 * BKB);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) bf[sub][tn] = *reinterpret_cast<const v8bf *>(st_ + b_frag[sub] + tn * 32 * BKB);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int sub = 0; sub < 4; ++sub)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[sub][tm], bf[sub][tn], acc[tm][tn], 0, 0, 0);
-            if (more) wait_vmcnt<(D - 1) * PER>();
-            else wait_vmcnt<0>();
+                    acc[tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[sub][tm], bf[sub], acc[tm], 0, 0, 0);
             stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
-
+        const int n = tile_n * BN + wn * 32 + l32;
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const int n = tile_n * BN + (wn * TN + tn) * 32 + l32;
+        for (int tm = 0; tm < TM; ++tm) {
+            const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int r = r0 + 8 * (i >> 2) + (i & 3);
-                    if (r < M && n < Nc) {
-                        const size_t at = (size_t)r * Nc + n;
-                        if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][tn][i]);
-                        else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][tn][i] * scale;
-                        else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][tn][i];
-                    }
+            for (int i = 0; i < 16; ++i) {
+                const int r = r0 + 8 * (i >> 2) + (i & 3);
+                if (r < M && n < Nc) {
+                    const size_t at = (size_t)r * Nc + n;
+                    if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][i]);
+                    else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][i] * scale;
+                    else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][i];
                 }
             }
         }
@@ -307,12 +333,12 @@ template <int OUT>
 void launch_gemm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
                  float scale, void *C, hipStream_t st)
 {
-    // 128x128 tiles, 3 stages of 32 KB: two workgroups per CU; persistent grid of at most 512 per split
-    const int tm = (M + 127) / 128, tn = (Nc + 127) / 128;
+    // 128 x 96 tiles, 3 stages of 28 KB, one workgroup per CU; persistent grid of at most 256 per split
+    const int tm = (M + 127) / 128, tn = (Nc + 95) / 96;
     int grid = tm * tn;
-    if (grid > 512) grid = 512;
-    hipLaunchKernelGGL((gemm_bf16_nt_kernel<2, 2, 2, 2, 2, OUT>), dim3(grid, splits), dim3(256), 0, st, A, B, M, Nc, Kc, lda,
-                       ldb, ksplit, scale, C, tm, tn);
+    if (grid > 256) grid = 256;
+    hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc, lda, ldb,
+                       ksplit, scale, C, tm, tn);
 }
 
 struct BwdPlan {
@@ -326,9 +352,10 @@ BwdPlan make_plan(int64_t T, int64_t N, int64_t K)
     BwdPlan p;
     p.Np = round_up(N, 64);
     p.Tp = round_up(T, 64);
-    // split the contraction over T so that about 256 workgroups exist, at least 256 rows each
-    const int64_t tiles = ((N + 127) / 128) * ((K + 127) / 128);
-    int64_t s = (256 + tiles - 1) / tiles;
+    // split the contraction over T so that at most about 256 workgroups (one per CU) exist, at least
+    // 256 rows each
+    const int64_t tiles = ((N + 127) / 128) * ((K + 95) / 96);
+    int64_t s = 256 / tiles;
     const int64_t max_s = (p.Tp + 255) / 256;
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
