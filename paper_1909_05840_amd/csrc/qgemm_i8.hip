@@ -906,24 +906,21 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
         return;
     }
-    // Tile choice (measured).  A CU pulls operand tiles out of L2 / the last-level cache at a limited
-    // rate, and copies issued on a SIMD that is busy with 32x32 MFMAs run at about half their stand-alone
-    // rate, so the bytes copied per MFMA and the tile count decide the speed.
-    //   256x256 tiles (half the bytes of 128x128 per MFMA) whenever they still give every CU two tiles;
-    //   128x96 tiles with the MFMAs on three SIMDs and the copies on the fourth when that needs fewer
-    //     rounds over the 256 CUs than 128x128 tiles would, weighted by the measured cost of a tile
-    //     (0.86 of a 128x128 one): all of BERT-base's N = 768 and 2304 layers at 4096 and 12288 tokens;
-    //   else 128x128: the role-split kernel (one workgroup per CU, copies run ahead across tiles) when a
-    //     CU gets few tiles or the contraction is long, two plain workgroups per CU when it gets many short
-    //     ones (one's write-out overlaps the other's MFMAs).
+    // Tile choice (measured on BERT-base and BERT-large shapes).  Copies issued on a SIMD that is busy
+    // with 32x32 MFMAs run at about half their stand-alone rate, so where the tile count allows it the MFMAs
+    // go to three SIMDs and the copies to the fourth:
+    //   128x96 tiles in that layout when they need fewer rounds over the 256 CUs than 128x128 tiles would,
+    //     weighted by the measured cost of a tile (0.86 of a 128x128 one): all of BERT-base's N = 768 layers
+    //     at 4096 and 12288 tokens, and N = 2304 at 4096;
+    //   else 128x128: the role-split kernel (one workgroup per CU, copies run ahead across tiles) when a CU
+    //     gets few tiles or the contraction is long and the tiles are few, two plain workgroups per CU when
+    //     it gets many (one's write-out overlaps the other's MFMAs); this also beats 256x256 tiles on the
+    //     BERT-large shapes at 32768 tokens (2.3 against 2.07 POP/s at 2 bits).
     // Grids are persistent and a multiple of 8, so that a workgroup stays inside its XCD's tile range.
-    const long tiles256 = (long)((T + 255) / 256) * ((N + 255) / 256);
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
-    if (tiles256 >= 512)
-        launch_dma<BITS, 4, 4, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
-    else if (86 * rounds96 < 100 * rounds128)
+    if (86 * rounds96 < 100 * rounds128)
         launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
     else if (tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))
         launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
