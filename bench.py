@@ -304,7 +304,8 @@ def embedding_leg(torch, qb, wl, dev):
     sg = time_launches(torch, lambda: qb.qb_embedding_gather(codes, h, GROUPS, ids, out), iters=20)
     return {"quantize_us": round(sq * 1e6, 1), "quantize_gbs": round(V * d * 5.0 / sq / 1e9, 1),
             "gather_us": round(sg * 1e6, 1), "gather_gbs": round(n * d * 5.0 / sg / 1e9, 1),
-            "note": "algorithmic bytes: 4 read + 1 written per table element; 1 read + 4 written per gathered element"}
+            "note": "algorithmic bytes: 4 read + 1 written per table element (the kernels read the table twice: column-group "
+                    "max over all rows, then codes); 1 read + 4 written per gathered element"}
 
 
 def cpu_baseline(wl):

@@ -986,6 +986,8 @@ extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_
 #define QB_S3B(e) { if (bits == 2) QB_S3(2, e); else if (bits == 3) QB_S3(3, e); else if (bits == 4) QB_S3(4, e); else QB_S3(8, e); }
         case 40: QB_S3B(3) break;   // 128x96 tiles, MFMAs on three SIMDs, copies on the fourth, 3 stages
         case 41: QB_S3B(4) break;   // 4 stages
+#define QB_S3B(B, tm, tn) launch_ws<B, tm, tn, 2, 3, 3, 2, true>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
+        case 47: { if (bits == 2) QB_S3B(2, 2, 2); else if (bits == 3) QB_S3B(3, 2, 2); else if (bits == 4) QB_S3B(4, 2, 2); else QB_S3B(8, 2, 2); } break;  // 128x192
         // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
         case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
         case 12: QB_TB(2, 2, 2, 2, 2, 4) break;

@@ -332,71 +332,100 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const uint8_t *__rest
 }
 
 // ---- embedding table: groups are column blocks --------------------------------------------------------
-// pass 1: each thread owns four columns and walks a slice of the rows; m zero-filled before.
+// pass 1: a workgroup takes EMB_ROWS rows of up to 1024 columns; each thread owns four columns, keeps eight
+// row loads in flight, and the workgroup combines per group in LDS before it touches m (zero-filled before;
+// max-abs values are non-negative floats, which order like their bit patterns).
+constexpr int EMB_ROWS = 32;
 __global__ __launch_bounds__(256) void embedding_absmax_kernel(const float *__restrict__ E, int64_t V, int d,
-                                                               int cols_per_group, int rows_per_block,
-                                                               float *__restrict__ m)
+                                                               int cols_per_group, float *__restrict__ m)
 {
+    __shared__ unsigned int gm[1024];
     const int d4 = d >> 2;
-    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
-    const int64_t r1 = (r0 + rows_per_block < V) ? r0 + rows_per_block : V;
-    for (int c4 = blockIdx.x * 256 + threadIdx.x; c4 < d4; c4 += gridDim.x * 256) {
-        const float4 *src = reinterpret_cast<const float4 *>(E) + c4;
+    const int c4 = blockIdx.x * 256 + threadIdx.x;
+    const int col_lo = blockIdx.x * 1024;
+    const int col_hi = (col_lo + 1024 < d) ? col_lo + 1024 : d;  // exclusive
+    const int g_lo = col_lo / cols_per_group, g_n = (col_hi - 1) / cols_per_group - g_lo + 1;
+    for (int i = threadIdx.x; i < g_n; i += 256) gm[i] = 0u;
+    __syncthreads();
+    if (c4 < d4) {
+        const int64_t r0 = (int64_t)blockIdx.y * EMB_ROWS;
+        const int nr = (int)((V - r0 < EMB_ROWS) ? V - r0 : EMB_ROWS);
+        const float4 *src = reinterpret_cast<const float4 *>(E) + r0 * d4 + c4;
         float4 mx = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int64_t r = r0; r < r1; ++r) {
-            const float4 v = src[r * d4];
+        auto take = [&](const float4 v) {
             mx.x = fmaxf(mx.x, fabsf(v.x));
             mx.y = fmaxf(mx.y, fabsf(v.y));
             mx.z = fmaxf(mx.z, fabsf(v.z));
             mx.w = fmaxf(mx.w, fabsf(v.w));
+        };
+        int r = 0;
+        for (; r + 8 <= nr; r += 8) {
+            float4 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(r + i) * d4];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) take(v[i]);
         }
-        unsigned int *mb = reinterpret_cast<unsigned int *>(m);
+        for (; r < nr; ++r) take(src[(int64_t)r * d4]);
         const int c = c4 << 2;
-        const int lanes_per_group = cols_per_group >> 2;
-        if ((cols_per_group & 3) == 0 && lanes_per_group <= 64 && (lanes_per_group & (lanes_per_group - 1)) == 0 &&
-            d4 % 64 == 0) {
-            // the four columns and lanes_per_group neighbouring lanes share one group: combine first
-            float v = fmaxf(fmaxf(mx.x, mx.y), fmaxf(mx.z, mx.w));
-            for (int o = 1; o < lanes_per_group; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
-            if ((threadIdx.x & (lanes_per_group - 1)) == 0) atomicMax(mb + c / cols_per_group, __float_as_uint(v));
+        const int g0 = c / cols_per_group - g_lo, g3 = (c + 3) / cols_per_group - g_lo;
+        if (g0 == g3) {
+            atomicMax(gm + g0, __float_as_uint(fmaxf(fmaxf(mx.x, mx.y), fmaxf(mx.z, mx.w))));
         } else {
-            atomicMax(mb + (c + 0) / cols_per_group, __float_as_uint(mx.x));
-            atomicMax(mb + (c + 1) / cols_per_group, __float_as_uint(mx.y));
-            atomicMax(mb + (c + 2) / cols_per_group, __float_as_uint(mx.z));
-            atomicMax(mb + (c + 3) / cols_per_group, __float_as_uint(mx.w));
+            atomicMax(gm + g0, __float_as_uint(mx.x));
+            atomicMax(gm + (c + 1) / cols_per_group - g_lo, __float_as_uint(mx.y));
+            atomicMax(gm + (c + 2) / cols_per_group - g_lo, __float_as_uint(mx.z));
+            atomicMax(gm + g3, __float_as_uint(mx.w));
         }
     }
+    __syncthreads();
+    unsigned int *mb = reinterpret_cast<unsigned int *>(m);
+    for (int i = threadIdx.x; i < g_n; i += 256)
+        if (gm[i] != 0u) atomicMax(mb + g_lo + i, gm[i]);
 }
 
-// pass 2: codes, and h = m/255
+// pass 2: codes, and h = m/255.  Same tiling; a thread sets up the quantizers of its four columns once.
 __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__restrict__ E, int64_t V, int d,
                                                                  int cols_per_group, int groups,
                                                                  const float *__restrict__ m, float *__restrict__ h,
                                                                  uint8_t *__restrict__ codes)
 {
-    const int64_t n4 = V * (int64_t)(d >> 2);
-    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (id < groups) {
-        const float mg = m[id];
-        h[id] = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        for (int g = threadIdx.x; g < groups; g += 256) {
+            const float mg = m[g];
+            h[g] = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
+        }
     }
-    if (id >= n4) return;
-    const int c = (int)(id % (d >> 2)) << 2;
-    const float4 v = reinterpret_cast<const float4 *>(E)[id];
-    const float w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t q = 0;
-    int g_prev = -1;
-    Quantizer qz;
+    const int d4 = d >> 2;
+    const int c4 = blockIdx.x * 256 + threadIdx.x;
+    if (c4 >= d4) return;
+    const int c = c4 << 2;
+    Quantizer qz[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int g = (c + i) / cols_per_group;
-        if (g != g_prev) {
-            qz.set(m[g], 255.0f);
-            g_prev = g;
-        }
-        q |= qz.code(w[i]) << (8 * i);
+        if (i > 0 && g == (c + i - 1) / cols_per_group) qz[i] = qz[i - 1];
+        else qz[i].set(m[g], 255.0f);
     }
-    reinterpret_cast<uint32_t *>(codes)[id] = q;
+    const int64_t r0 = (int64_t)blockIdx.y * EMB_ROWS;
+    const int nr = (int)((V - r0 < EMB_ROWS) ? V - r0 : EMB_ROWS);
+    const float4 *src = reinterpret_cast<const float4 *>(E) + r0 * d4 + c4;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(codes) + r0 * d4 + c4;
+    auto code4 = [&](const float4 v) {
+        uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(qz[0].code_f(v.x), 0, 0u);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(qz[1].code_f(v.y), 1, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(qz[2].code_f(v.z), 2, q);
+        return __builtin_amdgcn_cvt_pk_u8_f32(qz[3].code_f(v.w), 3, q);
+    };
+    int r = 0;
+    for (; r + 8 <= nr; r += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(r + i) * d4];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(code4(v[i]), dst + (int64_t)(r + i) * d4);
+    }
+    for (; r < nr; ++r) dst[(int64_t)r * d4] = code4(src[(int64_t)r * d4]);
 }
 
 __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__restrict__ codes,
@@ -573,13 +602,10 @@ extern "C" qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d,
     if (V <= 0 || V > (1 << 30) || !k_ok(d) || groups <= 0 || d % groups != 0) return QB_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int cpg = (int)(d / groups);
-    const int rows_per_block = 128;
+    const dim3 grid((unsigned)((d / 4 + 255) / 256), (unsigned)((V + EMB_ROWS - 1) / EMB_ROWS));
     hipLaunchKernelGGL(fill_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, m, groups);
-    hipLaunchKernelGGL(embedding_absmax_kernel, dim3((unsigned)((d / 4 + 255) / 256), (unsigned)((V + rows_per_block - 1) / rows_per_block)),
-                       dim3(256), 0, st, E, V, (int)d, cpg, rows_per_block, m);
-    const int64_t n4 = V * (d / 4);
-    hipLaunchKernelGGL(embedding_quantize_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, E, V, (int)d, cpg,
-                       groups, m, h, codes);
+    hipLaunchKernelGGL(embedding_absmax_kernel, grid, dim3(256), 0, st, E, V, (int)d, cpg, m);
+    hipLaunchKernelGGL(embedding_quantize_kernel, grid, dim3(256), 0, st, E, V, (int)d, cpg, groups, m, h, codes);
     return launch_status();
 }
 

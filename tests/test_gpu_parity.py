@@ -322,7 +322,7 @@ def test_backward_config3_full_size(qb, lin):
 
 # ---- embedding -------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("shape", [(30522, 1024, 128, 32768), (1000, 64, 8, 100), (517, 768, 128, 1), (300, 128, 1, 50),
-                                   (64, 192, 192, 10)])
+                                   (64, 192, 192, 10), (203, 2304, 36, 20), (100, 192, 64, 5)])
 def test_embedding(qb, shape):
     V, d, G, n = shape
     say("embedding", shape)
