@@ -130,6 +130,24 @@ def qlinear_fwd(xq, clip, codes, h, bits, bias=None, openmp=False):
     return Y, A4, acc
 
 
+def qlinear_fwd_q8(xq, clip, codes, h, bits, clip_out, bias=None, act=0, openmp=False):
+    """Forward with the output quantized to 8 bits at once. Returns yq[T,N] i8 (= u - 128), rs_y[T] i32."""
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == K
+    yq = np.empty((T, N), np.int8)
+    rs_y = np.empty(T, np.int32)
+    rc = _lib(openmp).qbo_qlinear_fwd_q8(_ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(h), int(bits),
+                                         _I64(h.shape[0]), _I64(T), _I64(N), _I64(K), _ptr(bias), int(act),
+                                         ctypes.c_float(clip_out), _ptr(yq), _ptr(rs_y))
+    _check(rc, "qlinear_fwd_q8")
+    return yq, rs_y
+
+
 def qlinear_fwd_sampled(xq, clip, codes, h, bits, ts, ns, bias=None):
     xq = _c(xq, np.int8)
     codes = _c(codes, np.uint8)

@@ -30,7 +30,9 @@
  *     the stored byte is u - 128;
  *   - the straight-through estimator is the identity through both quantizers, and the
  *     weight gradient uses the de-quantized activation;
- *   - the embedding table is grouped over its columns (embedding dimension).
+ *   - the embedding table is grouped over its columns (embedding dimension);
+ *   - where a layer's output is quantized again at once (8-bit output), the value that decides
+ *     the code is the binary32 product (h_x*h_g)*float(A4) (+ bias), not the binary64 one.
  *
  * Parity pins live in tests/test_oracle_pins.py.  Unpinned: nothing in this file depends on
  * the paper's accuracy tables (those need its datasets and checkpoints).
@@ -290,6 +292,53 @@ int qbo_qlinear_fwd_sampled(const int8_t *xq, float clip, const uint8_t *codes, 
         A4[i] = (int32_t)a4;
     }
     return QBO_OK;
+}
+
+/* Forward with an 8-bit output: the layer's result goes through the activation quantizer right
+ * away (Table 1 caption: every matmul input is an 8-bit activation; App. quantizer with k = 8 and
+ * the caller's range [-c_out, +c_out]), optionally after BERT's feed-forward non-linearity
+ * GELU(y) = y/2 * (1 + erf(y/sqrt 2)).  What the next layer needs is returned: yq[T,N] = u - 128 and
+ * rs_y[t] = sum_n yq[t,n].
+ * Precision: the value that decides the code is formed in binary32, one rounding per operation,
+ *   scale = h_x * h_g;   y = scale * float(A4);   y = y + bias[n]   (if a bias is given)
+ * (int -> float conversion rounds to nearest even).  GELU is evaluated in binary64 on that y and
+ * rounded once to binary32; an implementation with a binary32 erf may differ from it by a code
+ * on inputs next to a rounding boundary.  act: 0 = none, 1 = GELU. */
+int qbo_qlinear_fwd_q8(const int8_t *xq, float clip, const uint8_t *codes, const float *h,
+                       int bits, int64_t G, int64_t T, int64_t N, int64_t K, const float *bias,
+                       int act, float clip_out, int8_t *yq, int32_t *rs_y)
+{
+    int64_t t, rows;
+    float hx, delta_out;
+    int bad = 0;
+    if (!xq || !codes || !h || !yq || !rs_y || !bits_ok(bits)) return QBO_ERR_ARG;
+    if (T <= 0 || N <= 0 || K <= 0 || G <= 0 || N % G || !(clip > 0.0f)) return QBO_ERR_ARG;
+    if (!(clip_out > 0.0f) || !isfinite(clip_out) || (act != 0 && act != 1)) return QBO_ERR_ARG;
+    hx = clip / 255.0f;
+    delta_out = 2.0f * (clip_out / 255.0f);
+    rows = N / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (t = 0; t < T; ++t) {
+        int64_t n;
+        int32_t rs = 0;
+        for (n = 0; n < N; ++n) {
+            int64_t a = 0, a4 = 0;
+            float scale, y;
+            int u;
+            if (fwd_one(xq + t * K, codes + n * K, K, bits, &a, &a4) != QBO_OK) { bad = 1; continue; }
+            scale = hx * h[n / rows];
+            y = scale * (float)(int32_t)a4;
+            if (bias) y = y + bias[n];
+            if (act == 1) y = (float)(0.5 * (double)y * (1.0 + erf((double)y / sqrt(2.0))));
+            u = quantize_one(y, clip_out, delta_out, 255);
+            yq[t * N + n] = (int8_t)(u - 128);
+            rs += u - 128;
+        }
+        rs_y[t] = rs;
+    }
+    return bad ? QBO_ERR_OVERFLOW : QBO_OK;
 }
 
 /* Straight-through backward (Sec. 3.1 last paragraph; App. last sentence): the quantizers

@@ -320,6 +320,87 @@ def test_forward_and_backward_equal_fp64_gemm(bits):
     assert abs(num - dX[3, 5]) <= 1e-9 + 1e-6 * abs(dX[3, 5])
 
 
+# ---- 8-bit output: forward followed at once by the activation quantizer ------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_q8_output_exact_when_scales_are_powers_of_two(bits):
+    """h_x = 2^-6 and h_g = 2^-e make y = h_x*h_g*A4 exact in binary32 and binary64 alike, so the fused
+    result must equal the activation quantizer applied to the separately computed Y, bit for bit."""
+    T, N, K, G = 9, 12, 64, 3
+    L = 2 ** bits - 1
+    r = rng(40 + bits)
+    xq = r.integers(-128, 128, (T, K)).astype(np.int8)
+    codes = r.integers(0, L + 1, (N, K)).astype(np.uint8)
+    h = np.array([2.0 ** -9, 2.0 ** -8, 2.0 ** -10], np.float32)
+    clip = np.float32(255 * 2.0 ** -6)
+    assert np.float32(clip) / np.float32(255) == np.float32(2.0 ** -6)
+    bias = (r.integers(-64, 64, N) * 2.0 ** -10).astype(np.float32)
+    for b in (None, bias):
+        Y, A4, _ = oracle.qlinear_fwd(xq, clip, codes, h, bits, bias=b)
+        assert np.abs(A4).max() < 2 ** 24
+        for clip_out in (0.5, 2.0, 6.0):
+            yq, rs_y = oracle.qlinear_fwd_q8(xq, clip, codes, h, bits, clip_out, bias=b)
+            ref_q, ref_rs = oracle.quantize_act(Y, clip_out)
+            assert (yq == ref_q).all() and (rs_y == ref_rs).all()
+            assert (rs_y == yq.astype(np.int64).sum(axis=1)).all()
+    # a zero output is the tie 127.5 and rounds to the even code 128, stored as 0
+    yq0, rs0 = oracle.qlinear_fwd_q8(np.zeros((2, K), np.int8), clip, np.full((N, K), 2 ** (bits - 1), np.uint8), h, bits, 6.0)
+    y0, a40, _ = oracle.qlinear_fwd(np.zeros((2, K), np.int8), clip, np.full((N, K), 2 ** (bits - 1), np.uint8), h, bits)
+    assert (yq0 == oracle.quantize_act(y0, 6.0)[0]).all()
+
+
+@pytest.mark.parametrize("bits", (3, 8))
+def test_q8_output_is_nearest_level_of_the_exact_product(bits):
+    """Generic scales: the code's level is within half a step (plus rounding slack) of the exact rational
+    h_x*h_g*A4 + bias clamped to the range, and it differs from the two-step route by at most one code."""
+    T, N, K, G = 17, 24, 128, 4
+    W = (rng(50).standard_normal((N, K)) * 0.04).astype(np.float32)
+    X = rng(51).standard_normal((T, K)).astype(np.float32)
+    bias = (rng(52).standard_normal(N) * 0.1).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    xq, rs_x = oracle.quantize_act(X, 6.0)
+    clip_out = 0.5
+    yq, rs_y = oracle.qlinear_fwd_q8(xq, 6.0, codes, h, bits, clip_out, bias=bias)
+    Y, A4, _ = oracle.qlinear_fwd(xq, 6.0, codes, h, bits, bias=bias)
+    two_step, _ = oracle.quantize_act(Y, clip_out)
+    d = np.abs(yq.astype(np.int32) - two_step.astype(np.int32))
+    assert d.max() <= 1 and (d != 0).mean() < 5e-3
+    assert (rs_y == yq.astype(np.int64).sum(axis=1)).all()
+    hx = Fraction(float(np.float32(6.0) / np.float32(255)))
+    ho = Fraction(float(np.float32(clip_out) / np.float32(255)))
+    c = Fraction(clip_out)
+    for t in range(T):
+        for n in range(N):
+            y = hx * Fraction(float(h[n // (N // G)])) * int(A4[t, n]) + Fraction(float(bias[n]))
+            y = max(-c, min(c, y))
+            level = ho * (2 * (int(yq[t, n]) + 128) - 255)
+            assert abs(level - y) <= ho * (1 + Fraction(1, 10 ** 4))
+    assert yq.min() == -128 and yq.max() == 127  # the range is hit on both sides with this clip
+
+
+def test_q8_output_gelu_matches_an_independent_erf():
+    from scipy.special import erf
+    T, N, K, G, bits = 16, 32, 64, 4, 4
+    W = (rng(60).standard_normal((N, K)) * 0.04).astype(np.float32)
+    X = rng(61).standard_normal((T, K)).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    xq, rs_x = oracle.quantize_act(X, 6.0)
+    _, A4, _ = oracle.qlinear_fwd(xq, 6.0, codes, h, bits)
+    hx = np.float32(6.0) / np.float32(255)
+    y = (hx * np.repeat(h, N // G)[None, :]).astype(np.float32) * A4.astype(np.float32)  # binary32 steps
+    assert y.dtype == np.float32
+    g = (0.5 * y.astype(np.float64) * (1.0 + erf(y.astype(np.float64) / np.sqrt(2.0)))).astype(np.float32)
+    ref_q, ref_rs = oracle.quantize_act(g, 1.0)
+    yq, rs_y = oracle.qlinear_fwd_q8(xq, 6.0, codes, h, bits, 1.0, act=1)
+    d = np.abs(yq.astype(np.int32) - ref_q.astype(np.int32))
+    assert d.max() <= 1 and (d != 0).mean() < 1e-3
+    assert (rs_y == yq.astype(np.int64).sum(axis=1)).all()
+    # GELU's shape: never below -0.17, identity-like for large positive inputs
+    lev = (np.float64(1.0) / 255) * (2 * (yq.astype(np.int64) + 128) - 255)
+    assert lev.min() >= -0.17 - 1.0 / 255
+    big = y > 0.9
+    assert big.any() and np.abs(lev[big] - np.minimum(g[big], 1.0)).max() <= 1.0 / 255 * 1.001
+
+
 # ---- P12: backward is linear in dY ---------------------------------------------------------------------------------
 def test_backward_linearity():
     T, N, K = 8, 6, 16
