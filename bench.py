@@ -42,8 +42,8 @@ BITS_SWEEP = (2, 3, 4, 8)
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
@@ -211,6 +211,7 @@ def main():
 
     if not args.no_extras:
         out["shapes"] = per_shape(torch, qb, wl, dev)
+        out["q8_output"] = q8_output_leg(torch, qb, wl, dev)
         out["backward"] = backward_leg(torch, qb, wl, dev)
         out["embedding"] = embedding_leg(torch, qb, wl, dev)
     if not args.no_cpu_baseline:
@@ -264,6 +265,37 @@ def per_shape(torch, qb, wl, dev):
                     "roofline_tops": round(roof, 1), "frac_roofline": round(ops / sec / 1e12 / roof, 4),
                     "gbs": round(byts / sec / 1e9, 1)})
         del W, X, Y, Xq
+    return res
+
+
+def q8_output_leg(torch, qb, wl, dev):
+    """The forward with 8-bit output (the next layer's input written instead of fp32 Y) on the BERT-base shapes at
+    4 bits, next to the fp32-output call on the same inputs; FFN-up also with GELU in the epilogue."""
+    res = []
+    for (name, N, K) in wl.BERT_BASE_LINEARS:
+        T, b = T_TOKENS, 4
+        W = wl.weight(N, K, seed=N + K).to(dev)
+        X = wl.activation(T, K, seed=T + K).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        Y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        Yq = torch.empty((T, N), dtype=torch.int8, device=dev)
+        rs_y = torch.empty(T, dtype=torch.int32, device=dev)
+        s32 = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        s_act = time_launches(torch, lambda: qb.qb_quantize_act(Y, CLIP, Yq, rs_y))  # what the next layer needs, two-step route
+        acts = (0, 1) if name == "ffn_up" else (0,)
+        for act in acts:
+            s8 = time_launches(torch, lambda: qb.qb_qlinear_fwd_q8(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, CLIP,
+                                                                   act=act, Yq=Yq, rs_y=rs_y))
+            ops = 2.0 * T * N * K
+            byts = T * K + N * K * b / 8.0 + 1.0 * T * N + 8 * T + 4 * N
+            roof = min(PEAK_INT8_TOPS, PEAK_HBM_GBS * 1e9 * (ops / byts) / 1e12)
+            res.append({"linear": name, "T": T, "N": N, "K": K, "bits": b, "act": "gelu" if act else "none",
+                        "us_fp32_out": round(s32 * 1e6, 2), "us_quantize_act_of_it": round(s_act * 1e6, 2),
+                        "us": round(s8 * 1e6, 2), "tops": round(ops / s8 / 1e12, 1),
+                        "frac_int8_peak": round(ops / s8 / 1e12 / PEAK_INT8_TOPS, 4),
+                        "roofline_tops": round(roof, 1), "frac_roofline": round(ops / s8 / 1e12 / roof, 4)})
+        del W, X, Y, Yq, Xq
     return res
 
 

@@ -121,6 +121,25 @@ qb_status qb_qlinear_fwd(const int8_t *Xq, const int32_t *rs_x, float clip,
                          const float *bias, float *Y, int32_t *A4_debug, void *stream);
 
 /*
+ * Forward with an 8-bit output: the layer's result goes through the activation quantizer at once
+ * (Table 1 caption: every matrix product takes 8-bit activations; App. quantizer with k = 8), so
+ * the next layer's input is written instead of the fp32 result, a quarter of its bytes.
+ *   A4 as in qb_qlinear_fwd;  y = (h_x * h_{g(n)}) * float(A4) (+ bias[n]), each step one binary32
+ *   rounding;  act = 1 applies GELU(y) = y/2 * (1 + erf(y / sqrt 2)) in binary32 (act = 0: nothing);
+ *   Yq[t,n] = code(clamp(y, -clip_out, clip_out)) - 128 with the quantizer of qb_quantize_act
+ *   for the range [-clip_out, +clip_out];  rs_y[t] = sum_n Yq[t,n].
+ * With act = 0 the codes are a function of the inputs alone (bit-exact); with act = 1 they depend
+ * on the erf implementation by at most one code next to a rounding boundary.
+ *   Yq    out  [T,N] int8        rs_y  out  [T] int32 (cleared and accumulated by this call)
+ *   K must be a multiple of 128 (QB_ERR_SHAPE otherwise); other arguments as qb_qlinear_fwd.
+ */
+qb_status qb_qlinear_fwd_q8(const int8_t *Xq, const int32_t *rs_x, float clip,
+                            const void *packed, const float *h, const int32_t *rs_w,
+                            int bits, int groups, int64_t T, int64_t N, int64_t K,
+                            const float *bias, int act, float clip_out,
+                            int8_t *Yq, int32_t *rs_y, void *stream);
+
+/*
  * Straight-through-estimator backward (Sec. 3.1, last paragraph; App., last sentence): both
  * quantizers pass the gradient through unchanged, so
  *   dX[t,j] = sum_n dY[t,n] * Q(w)[n,j]        dW[n,j] = sum_t dY[t,n] * Q(x)[t,j]

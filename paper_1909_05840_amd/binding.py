@@ -19,7 +19,7 @@ QB_K_ALIGN = 64
 QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
-           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_bwd_ste", "qb_unpack_codes",
+           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather")
 
 
@@ -59,6 +59,8 @@ def load_library():
     lib.qb_quantize_act.argtypes = [vp, i64, i64, cf, vp, vp, vp]
     lib.qb_qlinear_fwd.restype = ci
     lib.qb_qlinear_fwd.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_fwd_q8.restype = ci
+    lib.qb_qlinear_fwd_q8.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, ci, cf, vp, vp, vp]
     lib.qb_qlinear_bwd_ste.restype = ci
     lib.qb_qlinear_bwd_ste.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_unpack_codes.restype = ci
@@ -169,6 +171,21 @@ def qb_qlinear_fwd(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, bias=None, 
     _check(lib.qb_qlinear_fwd(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(h), _p(rs_w), bits, groups,
                               T, N, K, _p(bias), _p(Y), _p(A4_debug), _stream()))
     return (Y, A4_debug) if A4_debug is not None else Y
+
+
+def qb_qlinear_fwd_q8(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, clip_out, bias=None, act=0, Yq=None,
+                      rs_y=None):
+    """Forward with the output quantized to 8 bits at once. Returns Yq[T,N] int8 (= u - 128), rs_y[T] int32."""
+    lib = load_library()
+    _dev(Xq, torch.int8, "Xq")
+    T, K = Xq.shape
+    if Yq is None:
+        Yq = torch.empty((T, N), dtype=torch.int8, device=Xq.device)
+    if rs_y is None:
+        rs_y = torch.empty(T, dtype=torch.int32, device=Xq.device)
+    _check(lib.qb_qlinear_fwd_q8(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(h), _p(rs_w), bits, groups,
+                                 T, N, K, _p(bias), int(act), float(clip_out), _p(Yq), _p(rs_y), _stream()))
+    return Yq, rs_y
 
 
 def qb_qlinear_bwd_ste(dY, Xq, clip, packed, h, bits, groups, want_dx=True, want_dw=True, dX=None, dW=None,

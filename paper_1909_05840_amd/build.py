@@ -9,8 +9,9 @@ SOURCES = ("api.hip", "quantize.hip", "qgemm_i8.hip", "bwd_bf16.hip")
 # packed-fp32 instructions are switched off for every device translation unit
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-# the quantizers need one rounding per operation: no fused multiply-add contraction there
-PER_FILE = {"quantize.hip": ["-ffp-contract=off"]}
+# the quantizers (also the one in the GEMM's 8-bit-output epilogue) need one rounding per operation: no fused
+# multiply-add contraction there.  (__fmul_rn/__fadd_rn are plain operators to the compiler and would be fused.)
+PER_FILE = {"quantize.hip": ["-ffp-contract=off"], "qgemm_i8.hip": ["-ffp-contract=off"]}
 
 
 def build(verbose=False):

@@ -98,6 +98,58 @@ __device__ __forceinline__ int wave_sum(int v)
     return v;
 }
 
+// The quantizer of one range [-m, +m] (q0 = -m): code = clamp(rint(fl((w + m) / Delta)), 0, L),
+// every step one correctly rounded binary32 operation.
+//
+// The division is the expensive step (these kernels have ~20 ALU operations per element to spend
+// at HBM speed), so the common case multiplies by rinv = fl(1/Delta) instead, and falls back to
+// the true division exactly when the two could disagree:
+//   t  = fl(s/Delta)  = (s/Delta)(1+e3),           |e| <= 2^-24 each
+//   t' = fl(s*rinv)   = (s/Delta)(1+e1)(1+e2)
+//   |t' - t| <= (s/Delta) * 3.0001 * 2^-24 <= 255.0001 * 3.0001 * 2^-24 < 4.6e-5
+// (s/Delta <= L(1+2^-23) <= 255.0001).  With n = rint(t') and d = t' - n (exact by Sterbenz),
+// |d| <= 0.4999 puts t' at least 1e-4 away from every half-integer, hence t strictly on the same
+// side of it: rint(t) = n, and no tie is involved.  Otherwise the lane redoes the step with the
+// IEEE division.  `fast` is off for ranges whose reciprocal is not a normal number.
+struct Quantizer {
+    float m, delta, rinv, Lf;
+    bool fast;
+    __device__ __forceinline__ void set(float mg, float L)
+    {
+        m = mg;
+        Lf = L;
+        const float hg = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, L);
+        delta = (mg == 0.0f) ? 1.0f : 2.0f * hg;  // all-zero group: w + m = 0 gives code 0 with any Delta
+        rinv = __fdiv_rn(1.0f, delta);
+        fast = delta >= 1.0e-30f && delta <= 1.0e30f;
+    }
+    __device__ __forceinline__ float half_step() const { return (m == 0.0f) ? 0.0f : __fdiv_rn(m, Lf); }
+    // rint((w + m)/Delta) as a float.  No clamp to [0, L] is needed: |w| <= m gives 0 <= s <= 2m(1+2^-24),
+    // so 0 <= t <= L(1+2^-23) and rint(t) is already in 0..L (callers clamp activations to [-m, m] first).
+    __device__ __forceinline__ float code_f(float w) const
+    {
+        const float s = __fadd_rn(w, m);
+        if (fast) {
+            const float tp = __fmul_rn(s, rinv);
+            float r = rintf(tp);
+            if (!(fabsf(tp - r) <= 0.4999f)) r = rintf(__fdiv_rn(s, delta));  // rare; also catches NaN
+            return r;
+        }
+        return rintf(__fdiv_rn(s, delta));
+    }
+    __device__ __forceinline__ uint32_t code(float w) const { return (uint32_t)code_f(w); }
+    // four codes, one per byte (v_cvt_pk_u8_f32 converts and inserts in one instruction; its input is
+    // an integer-valued float here, so its rounding never comes into play)
+    __device__ __forceinline__ uint32_t code4(const float4 v) const
+    {
+        uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.x), 0, 0u);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.y), 1, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.z), 2, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.w), 3, q);
+        return q;
+    }
+};
+
 // ---- host-side argument checks ------------------------------------------------------------------
 inline bool bits_ok(int bits) { return bits == 2 || bits == 3 || bits == 4 || bits == 8; }
 inline bool k_ok(int64_t K) { return K > 0 && K % QB_K_ALIGN == 0 && K <= QB_MAX_K; }

@@ -21,6 +21,9 @@
 namespace qb {
 namespace {
 
+// a*b + c for |a|, |b| < 2^23 (full-rate 24-bit multiplier instead of the quarter-rate 32-bit one)
+__device__ __forceinline__ int qb_mad24(int a, int b, int c) { return __mul24(a, b) + c; }
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
-                    const int a4 = 4 * acc[tm][tn][i] + E2 * rx[i] + coln;
+                    const int a4 = 4 * acc[tm][tn][i] + qb_mad24(E2, rx[i], coln);
                     const size_t at = (size_t)t * N + n;
                     Y[at] = scale * (float)a4 + bv;
                     if (A4out) A4out[at] = a4;
@@ -503,7 +506,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
                 } else {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rx[tm][i] + coln[tn];
+                        const int a4 = 4 * acc[tm][tn][i] + qb_mad24(E2, rx[tm][i], coln[tn]);
                         __builtin_nontemporal_store(scale[tn] * (float)a4 + bv[tn], reinterpret_cast<float *>(y_blk + voff[i]));
                     }
                 }
@@ -571,10 +574,10 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int4 v = *reinterpret_cast<const int4 *>(p_rx + tl + 8 * q);
-        rx[4 * q + 0] = e2 * v.x + coln;
-        rx[4 * q + 1] = e2 * v.y + coln;
-        rx[4 * q + 2] = e2 * v.z + coln;
-        rx[4 * q + 3] = e2 * v.w + coln;
+        rx[4 * q + 0] = qb_mad24(e2, v.x, coln);  // |rs_x| <= 128*K < 2^23: the 24-bit multiply is exact and full rate
+        rx[4 * q + 1] = qb_mad24(e2, v.y, coln);
+        rx[4 * q + 2] = qb_mad24(e2, v.z, coln);
+        rx[4 * q + 3] = qb_mad24(e2, v.w, coln);
     }
     if (fast) {
         char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
@@ -598,6 +601,65 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
     }
 }
 
+// 8-bit output (the next layer's input): where to put it and how to quantize it
+struct OutQ {
+    int8_t *Yq;       // [T,N] u - 128
+    int32_t *rs_y;    // [T] row sums of Yq, accumulated with atomics (zero-filled before the launch)
+    float clip_out;   // range [-clip_out, +clip_out]
+    int act;          // 0 none, 1 GELU
+};
+
+// One 32x32 block of the 8-bit output: the value that decides the code is formed in binary32 with one
+// rounding per step, scale = h_x*h_g, y = scale*float(A4), y = y + bias; then the optional GELU, the clamp to
+// the output range and the activation quantizer.  The bytes go to the workgroup's staging tile in LDS
+// (BM rows of BN bytes), from where whole rows are written out.  Lane/register roles as in store_block_lds.
+template <int BM, int BN, int BNT>
+__device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *pp, int e2, int tl, int nl, int K,
+                                                float hx, bool has_bias, const Quantizer &qo, int act,
+                                                uint8_t *stg)
+{
+    // (this file is compiled with -ffp-contract=off: y = scale*float(A4) and y + bias are two roundings)
+    asm volatile("" : "+v"(tl));
+    const int *p_rx = reinterpret_cast<const int *>(pp);
+    const int *p_rw = p_rx + BM;
+    const float *p_h = reinterpret_cast<const float *>(p_rw + BN), *p_b = p_h + BN;
+    const int coln = 2 * p_rw[nl] + K;
+    const float scale = hx * p_h[nl];
+    const float bv = has_bias ? p_b[nl] : 0.0f;  // y + 0 = y: the code is the same as without a bias
+    const float c = qo.m;
+    float y[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int4 v = *reinterpret_cast<const int4 *>(p_rx + tl + 8 * q);
+        const int rx[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) y[4 * q + i] = scale * (float)(4 * acc[4 * q + i] + qb_mad24(e2, rx[i], coln)) + bv;  // |rs_x| < 2^23
+    }
+    if (act == 1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) y[r] = 0.5f * y[r] * (1.0f + erff(y[r] * 0.70710678118654752f));
+    }
+    // The quantizer (same steps as Quantizer::code_f) without a branch per element: the reciprocal route for
+    // all sixteen, and the true division for all sixteen if any lane's product came too close to a rounding
+    // boundary (about one block in five) or the range is too extreme for the reciprocal.
+    float s[16], rr[16];
+    bool redo = !qo.fast;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        s[r] = __builtin_amdgcn_fmed3f(y[r], -c, c) + c;
+        const float tp = s[r] * qo.rinv;
+        rr[r] = rintf(tp);
+        redo |= !(fabsf(tp - rr[r]) <= 0.4999f);
+    }
+    if (__any(redo)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rr[r] = rintf(__fdiv_rn(s[r], qo.delta));
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        stg[(tl + 8 * (r >> 2) + (r & 3)) * BNT + nl] = (uint8_t)(uint32_t)rr[r];  // the code u; u - 128 is formed on the way out
+}
+
 // ---------------------------------------------------------------------------------------------
 // Main kernel (K a multiple of 128): the same data path as above with the work split by role.
 //   consumer wavefronts (WM x WN of them): LDS fragment reads, code expansion, MFMA, epilogue
@@ -612,12 +674,15 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
 //             for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
 //                    wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
 //   consumer: BARRIER; for s: MMA on stage s % NSTAGE; BARRIER
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3>
+// OUTQ: instead of Y the tile is quantized to 8 bits (quant_block_lds) into an LDS staging tile and, after one
+// more barrier per tile (E, executed by the producers once the next tile's first copies are on their way), written
+// out in whole rows; the rows' sums are collected in LDS and added to rs_y one tile later.
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, bool OUTQ>
 __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
-    int tiles_m, int tiles_n)
+    int tiles_m, int tiles_n, OutQ oq)
 {
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
     constexpr int NC = WM * WN;
@@ -643,7 +708,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     // last barrier.  Hence two blocks.
     constexpr int NPARAM = 2;
 
-    __shared__ __align__(1024) uint8_t lds[NSTAGE * STAGE_BYTES + NPARAM * PARAM_BYTES];
+    constexpr int STG_OFF = NSTAGE * STAGE_BYTES + NPARAM * PARAM_BYTES;  // staging tile, then BM row sums
+    constexpr int STG_BYTES = OUTQ ? BM * BN + BM * 4 : 0;
+    static_assert(STG_OFF % 16 == 0 && BN % 16 == 0 && BM <= NC * 64, "staging tile: 16-byte pieces, one thread per row sum");
+    __shared__ __align__(1024) uint8_t lds[STG_OFF + STG_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t *)lds;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -729,6 +797,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #pragma unroll
             for (int u = 0; u < D; ++u)
                 if (u < nsteps) fetch(u, u);
+            if (OUTQ && work != (int)blockIdx.x) __builtin_amdgcn_s_barrier();  // barrier E of the previous tile
             if (nsteps >= D) wait_vmcnt<(D - 1) * PERP>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
@@ -744,6 +813,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                 __builtin_amdgcn_s_barrier();
             }
         }
+        if (OUTQ && (int)blockIdx.x < nwg) __builtin_amdgcn_s_barrier();  // barrier E of the last tile
         return;
     }
 
@@ -765,6 +835,25 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     int pb = 0;
 
     v16i acc[TM][TN];
+
+    // 8-bit output: staging tile, row sums, the output quantizer
+    constexpr int NCT = NC * 64;
+    const int ctid = cidx * 64 + lane;
+    uint8_t *stg = lds + STG_OFF;
+    int *rowsum = reinterpret_cast<int *>(lds + STG_OFF + BM * BN);
+    Quantizer qo;
+    int prev_t0 = -1;
+    if constexpr (OUTQ) {
+        qo.set(oq.clip_out, 255.0f);
+        if (ctid < BM) rowsum[ctid] = 0;
+    }
+    auto flush_rowsums = [&]() {  // the previous tile's row sums -> rs_y; every LDS add to them is a barrier back
+        if (ctid < BM) {
+            const int v = rowsum[ctid];
+            rowsum[ctid] = 0;
+            if (prev_t0 + ctid < T) atomicAdd(oq.rs_y + prev_t0 + ctid, v);
+        }
+    };
 
     for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
         int logical;
@@ -829,7 +918,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
         asm volatile("" ::: "memory");                                                                    \
     }
 
+        if constexpr (OUTQ) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): my LDS writes and adds are done
         QB_BARRIER()
+        if constexpr (OUTQ) {
+            if (prev_t0 >= 0) flush_rowsums();
+        }
         int s = 0;
         for (; s + NSTAGE <= nsteps; s += NSTAGE) {
 #pragma unroll
@@ -845,9 +938,54 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                 QB_BARRIER()
             }
 #undef QB_MMA
-#undef QB_BARRIER
 
         // ---- write-out
+        if constexpr (OUTQ) {
+            typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    quant_block_lds<BM, BNP, BN>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
+                                                 (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, K, hx,
+                                                 bias != nullptr, qo, oq.act, stg);
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // the staging bytes are written
+            QB_BARRIER()                         // barrier E
+            // whole rows out: 16-byte pieces, BN/16 per row
+            constexpr int PPR = BN / 16;
+            const int t0 = tile_m * BM, n0 = tile_n * BN;
+            const bool vec_ok = (N & 15) == 0 && (reinterpret_cast<uintptr_t>(oq.Yq) & 15) == 0;
+            for (int pc = ctid; pc < BM * PPR; pc += NCT) {
+                const int row = pc / PPR, cp = pc - row * PPR;
+                const int t = t0 + row, n = n0 + cp * 16;
+                if (t < T && n < N) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * BN + cp * 16);  // codes u
+                    int8_t *dst = oq.Yq + (size_t)t * N + n;
+                    int sum;
+                    if (vec_ok && n + 16 <= N) {
+                        v4u o = {v.x ^ 0x80808080u, v.y ^ 0x80808080u, v.z ^ 0x80808080u, v.w ^ 0x80808080u};  // u - 128
+                        __builtin_nontemporal_store(o, reinterpret_cast<v4u *>(dst));
+                        uint32_t su = __builtin_amdgcn_sad_u8(v.x, 0u, 0u);
+                        su = __builtin_amdgcn_sad_u8(v.y, 0u, su);
+                        su = __builtin_amdgcn_sad_u8(v.z, 0u, su);
+                        su = __builtin_amdgcn_sad_u8(v.w, 0u, su);
+                        sum = (int)su - 16 * 128;
+                    } else {
+                        const uint32_t w[4] = {v.x ^ 0x80808080u, v.y ^ 0x80808080u, v.z ^ 0x80808080u, v.w ^ 0x80808080u};
+                        sum = 0;
+#pragma unroll
+                        for (int b = 0; b < 16; ++b)
+                            if (n + b < N) {
+                                const int8_t q8 = (int8_t)((w[b >> 2] >> (8 * (b & 3))) & 255u);
+                                dst[b] = q8;
+                                sum += q8;
+                            }
+                    }
+                    atomicAdd(rowsum + row, sum);
+                }
+            }
+            prev_t0 = t0;
+        } else {
         const bool fast = (tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N && A4out == nullptr;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
@@ -856,8 +994,17 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                 store_block_lds<BM, BNP>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
                                         (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, tile_m * BM, tile_n * BN,
                                         T, N, K, hx, bias != nullptr, fast, Y, A4out);
+        }
         pb ^= 1;
     }
+    if constexpr (OUTQ) {
+        if (prev_t0 >= 0) {  // the last tile's row sums: the producers have left, the six MFMA wavefronts meet once more
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            flush_rowsums();
+        }
+    }
+#undef QB_BARRIER
 }
 
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
@@ -869,9 +1016,23 @@ void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, con
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3>), dim3(grid),
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, false>), dim3(grid),
                        dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, OutQ{nullptr, nullptr, 1.0f, 0});
+}
+
+// the same with the 8-bit output
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
+void launch_ws_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
+                  const float *bias, const OutQ &oq, int T, int N, int K, int rpg, float hx, hipStream_t st, int grid_cap)
+{
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    int grid = tiles_m * tiles_n;
+    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, true>), dim3(grid),
+                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, nullptr, nullptr, T, N, K, rpg,
+                       hx, tiles_m, tiles_n, oq);
 }
 
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
@@ -926,6 +1087,26 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
     else
         launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
+}
+
+// 8-bit output: the role-split kernels only (128x96 tiles on three SIMDs where they need fewer rounds, else 128x128)
+template <int BITS>
+void launch_bits_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
+                    const float *bias, const OutQ &oq, int T, int N, int K, int rpg, float hx, hipStream_t st)
+{
+    const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
+    const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
+    const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
+    if (86 * rounds96 < 100 * rounds128)
+        launch_ws_q8<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 256);
+    else
+        launch_ws_q8<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 256);
+}
+
+__global__ void fill_zero_i32_kernel(int32_t *p, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 #ifdef QB_TUNE
@@ -1027,6 +1208,32 @@ extern "C" qb_status qb_qlinear_fwd(const int8_t *Xq, const int32_t *rs_x, float
         case 3: launch_bits<3>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st); break;
         case 4: launch_bits<4>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st); break;
         default: launch_bits<8>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st); break;
+    }
+    return launch_status();
+}
+
+extern "C" qb_status qb_qlinear_fwd_q8(const int8_t *Xq, const int32_t *rs_x, float clip, const void *packed,
+                                       const float *h, const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N,
+                                       int64_t K, const float *bias, int act, float clip_out, int8_t *Yq, int32_t *rs_y,
+                                       void *stream)
+{
+    if (!Xq || !rs_x || !packed || !h || !rs_w || !Yq || !rs_y) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K) || K % 128 != 0 || groups <= 0 || N % groups != 0 ||
+        (act != 0 && act != 1))
+        return QB_ERR_SHAPE;
+    if (!(clip > 0.0f) || !(clip < 3.0e38f) || !(clip_out > 0.0f) || !(clip_out < 3.0e38f)) return QB_ERR_CLIP;
+    const float hx = clip / 255.0f;
+    const int rpg = (int)(N / groups);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    const OutQ oq{Yq, rs_y, clip_out, act};
+    hipLaunchKernelGGL(fill_zero_i32_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, rs_y, (int)T);
+    switch (bits) {
+        case 2: launch_bits_q8<2>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
+        case 3: launch_bits_q8<3>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
+        case 4: launch_bits_q8<4>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
+        default: launch_bits_q8<8>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
     }
     return launch_status();
 }

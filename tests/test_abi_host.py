@@ -76,6 +76,12 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_qlinear_fwd(P, P, f(6.0), P, P, P, 7, 128, 16, 768, 768, NULL, P, NULL, NULL) == 2
     assert lib.qb_qlinear_fwd(P, P, f(6.0), P, P, P, 4, 128, 16, 770, 768, NULL, P, NULL, NULL) == 3
     assert lib.qb_qlinear_fwd(P, P, f(-1.0), P, P, P, 4, 128, 16, 768, 768, NULL, P, NULL, NULL) == 4
+    # qlinear_fwd_q8(Xq,rs_x,clip,packed,h,rs_w,bits,groups,T,N,K,bias,act,clip_out,Yq,rs_y,stream)
+    assert lib.qb_qlinear_fwd_q8(P, P, f(6.0), P, P, P, 4, 128, 16, 768, 768, NULL, 0, f(6.0), NULL, P, NULL) == 1
+    assert lib.qb_qlinear_fwd_q8(P, P, f(6.0), P, P, P, 5, 128, 16, 768, 768, NULL, 0, f(6.0), P, P, NULL) == 2
+    assert lib.qb_qlinear_fwd_q8(P, P, f(6.0), P, P, P, 4, 128, 16, 768, 192, NULL, 0, f(6.0), P, P, NULL) == 3  # K % 128
+    assert lib.qb_qlinear_fwd_q8(P, P, f(6.0), P, P, P, 4, 128, 16, 768, 768, NULL, 2, f(6.0), P, P, NULL) == 3  # act
+    assert lib.qb_qlinear_fwd_q8(P, P, f(6.0), P, P, P, 4, 128, 16, 768, 768, NULL, 0, f(0.0), P, P, NULL) == 4
     # qlinear_bwd_ste(dY,Xq,clip,packed,h,bits,groups,T,N,K,dX,dW,workspace,stream)
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, NULL, NULL) == 5
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, ctypes.c_void_p(0x1010), NULL) == 5

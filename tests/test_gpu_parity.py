@@ -269,6 +269,71 @@ def test_forward_plain_call_matches_checked_call(qb, bits, shape):
 
 
 # ---- backward ----------------------------------------------------------------------------------------
+# ---- forward with 8-bit output --------------------------------------------------------------------------
+def run_fwd_q8(qb, W, X, bits, G, clip_out, bias=None, act=0):
+    N, K = W.shape
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    Yq, rs_y = qb.qb_qlinear_fwd_q8(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, clip_out,
+                                    bias=None if bias is None else bias.to(DEV), act=act)
+    torch.cuda.synchronize()
+    oc, oh, _, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    oq, _ = oracle.quantize_act(X.numpy(), CLIP)
+    return Yq.cpu().numpy(), rs_y.cpu().numpy(), oq, oc, oh
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(300, 384, 256, 128), (1000, 256, 384, 64), (517, 768, 768, 128), (70, 200, 128, 8),
+                                   (1, 32, 128, 1), (2048, 1024, 128, 128)])
+def test_forward_q8_output(qb, bits, shape):
+    """Both tile layouts, ragged tails in T and N (N = 200: rows that are not a multiple of 16 bytes), with and
+    without bias: codes and row sums equal the oracle's bit for bit."""
+    T, N, K, G = shape
+    say("fwd q8", shape, "bits", bits)
+    W = wl.weight_uniform(N, K, seed=13 * N + K + bits, lo=-0.1, hi=0.1)
+    X = wl.activation(T, K, seed=T + K + bits + 5)
+    bias = (0.3 * wl.activation(1, N, seed=9)[0]).contiguous()
+    for b, clip_out in ((None, 2.0), (bias, 0.75)):
+        Yq, rs_y, oq, oc, oh = run_fwd_q8(qb, W, X, bits, G, clip_out, bias=b)
+        yo, ro = oracle.qlinear_fwd_q8(oq, CLIP, oc, oh, bits, clip_out, bias=None if b is None else b.numpy(), openmp=True)
+        assert (Yq == yo).all(), int((Yq != yo).sum())
+        assert (rs_y == ro).all()
+    assert Yq.min() == -128 and Yq.max() == 127 or T == 1
+
+
+@pytest.mark.parametrize("bits", (3, 8))
+def test_forward_q8_output_gelu(qb, bits):
+    """GELU in front of the output quantizer: the binary32 erf may move a value across a rounding boundary, so
+    codes may differ from the oracle's (binary64 erf) by one, rarely; row sums must fit the GPU's own codes."""
+    T, N, K, G = 700, 768, 256, 128
+    W = wl.weight_uniform(N, K, seed=77 + bits, lo=-0.1, hi=0.1)
+    X = wl.activation(T, K, seed=78 + bits)
+    bias = (0.3 * wl.activation(1, N, seed=9)[0]).contiguous()
+    Yq, rs_y, oq, oc, oh = run_fwd_q8(qb, W, X, bits, G, 1.5, bias=bias, act=1)
+    yo, ro = oracle.qlinear_fwd_q8(oq, CLIP, oc, oh, bits, 1.5, bias=bias.numpy(), act=1, openmp=True)
+    d = np.abs(Yq.astype(np.int32) - yo.astype(np.int32))
+    assert d.max() <= 1 and (d != 0).mean() < 1e-3, (int(d.max()), float((d != 0).mean()))
+    assert (rs_y == Yq.astype(np.int64).sum(axis=1)).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
+def test_forward_q8_config2_full_size(qb, bits, lin):
+    """Configuration 2 shapes at T = 4096 as bench.py launches them: sampled token rows against the oracle (rows
+    are independent), row sums of every row against the GPU's own codes."""
+    name, N, K = lin
+    T, G = 4096, 128
+    say("fwd q8 full size", lin, "bits", bits)
+    W = wl.weight(N, K, seed=wl.config_seed(1, N + K + bits))
+    X = wl.activation(T, K, seed=wl.config_seed(1, N + K + bits) + 1)
+    Yq, rs_y, oq, oc, oh = run_fwd_q8(qb, W, X, bits, G, 3.0)
+    rows = np.concatenate([np.random.default_rng(N + K + bits).integers(0, T, 30), [0, T - 1]])
+    yo, ro = oracle.qlinear_fwd_q8(oq[rows], CLIP, oc, oh, bits, 3.0, openmp=True)
+    assert (Yq[rows] == yo).all()
+    assert (rs_y[rows] == ro).all()
+    assert (rs_y == Yq.astype(np.int64).sum(axis=1)).all()
+
+
 def rel_fro(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
 
