@@ -230,7 +230,7 @@ def measured_traffic(kernel):
         return None
 
 
-def time_launches(torch, fn, iters=50, warm=5):
+def time_launches(torch, fn, iters=100, warm=30):
     for _ in range(warm):
         fn()
     torch.cuda.synchronize()
@@ -250,6 +250,7 @@ def per_shape(torch, qb, wl, dev):
     res = []
     cases = [(T_TOKENS, N, K, 4) for (_, N, K) in wl.BERT_BASE_LINEARS] + [(T_TOKENS, 768, 3072, b) for b in (2, 3, 8)]
     cases += [(32768, 1024, 4096, 2), (32768, 4096, 1024, 3)]
+    cases += [(1024, 768, 768, 4), (128, 768, 3072, 4)]  # configs[0]; a 128-token inference batch (launch-bound)
     for (T, N, K, b) in cases:
         W = wl.weight(N, K, seed=N + K).to(dev)
         X = wl.activation(T, K, seed=T + K).to(dev)

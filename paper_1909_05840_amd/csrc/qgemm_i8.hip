@@ -1063,6 +1063,17 @@ template <int BITS>
 void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                  const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st)
 {
+    const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
+    if (tiles128 <= 160) {
+        // Few tiles (small token counts, the inference regime): the persistent kernels below leave most CUs idle
+        // and pay ~6.5 us at least; 32x64 tiles of the register-staged kernel spread the work over the chip
+        // (measured 4.4-5 us against 8 at T <= 1024, N = 768; 6.8 against 8.4 at 1024 x 2304 x 768; equal
+        // at about 190 tiles).  Long contractions take 256 features per step.
+        if (K % 256 == 0 && K >= 2048) launch_cfg<BITS, 1, 1, 1, 2, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+        else if (K % 128 == 0) launch_cfg<BITS, 1, 1, 1, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+        else launch_cfg<BITS, 1, 1, 1, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+        return;
+    }
     if (K % 128 != 0) {  // odd number of 64-feature units: register-staged kernel, one unit per step
         launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
         return;
@@ -1078,7 +1089,6 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
     //     it gets many (one's write-out overlaps the other's MFMAs); this also beats 256x256 tiles on the
     //     BERT-large shapes at 32768 tokens (2.3 against 2.07 POP/s at 2 bits).
     // Grids are persistent and a multiple of 8, so that a workgroup stays inside its XCD's tile range.
-    const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
     if (86 * rounds96 < 100 * rounds128)
@@ -1169,6 +1179,13 @@ extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_
         case 41: QB_S3B(4) break;   // 4 stages
 #define QB_S3B(B, tm, tn) launch_ws<B, tm, tn, 2, 3, 3, 2, true>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
         case 47: { if (bits == 2) QB_S3B(2, 2, 2); else if (bits == 3) QB_S3B(3, 2, 2); else if (bits == 4) QB_S3B(4, 2, 2); else QB_S3B(8, 2, 2); } break;  // 128x192
+#define QB_SM(tm, tn, wm, wn, ku) launch_cfg<4, tm, tn, wm, wn, ku>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st)
+        case 70: QB_SM(1, 1, 2, 2, 2); break;  // 64x64
+        case 71: QB_SM(1, 1, 1, 2, 2); break;  // 32x64
+        case 72: QB_SM(1, 1, 1, 1, 2); break;  // 32x32, one wavefront
+        case 73: QB_SM(1, 1, 1, 4, 2); break;  // 32x128
+        case 74: QB_SM(1, 1, 1, 2, 4); break;  // 32x64, 256 features per step
+        case 75: QB_SM(1, 1, 1, 1, 4); break;  // 32x32
         // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
         case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
         case 12: QB_TB(2, 2, 2, 2, 2, 4) break;

@@ -159,7 +159,7 @@ def assert_rel(Y, Yo, tol=1e-6):
 
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("shape", [(300, 160, 192, 8), (257, 96, 64, 96), (1, 32, 64, 1), (129, 130, 320, 10),
-                                   (513, 768, 768, 128), (64, 6, 128, 6)])
+                                   (513, 768, 768, 128), (64, 6, 128, 6), (100, 96, 2048, 96), (1700, 1536, 192, 128)])
 def test_forward_full_compare(qb, bits, shape):
     """Several tiles and ragged tails in T, N; full element-by-element comparison."""
     T, N, K, G = shape
@@ -239,13 +239,14 @@ def test_forward_config4_mixed_bits(qb):
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("shape", [(4096, 768, 768), (4096, 2304, 768), (4096, 3072, 768), (4096, 768, 3072),
                                    (4096, 1024, 1024), (32768, 1024, 1024), (2048, 768, 192), (1000, 130, 256),
-                                   (300, 96, 128), (129, 200, 384)])
+                                   (300, 96, 128), (129, 200, 384), (4096, 768, 192), (512, 768, 2048)])
 def test_forward_plain_call_matches_checked_call(qb, bits, shape):
     """The call as bench.py makes it (no debug output: interior tiles take the straight-line streaming-store
     path) must give bit for bit the Y of the call with the debug output (every element checked), which the
     other tests compare with the oracle.  The shapes walk through every branch of the tile dispatch: 128x96
-    tiles on three SIMDs, role-split 128x128, two plain workgroups per CU, 256x256 tiles, the register-staged
-    kernel for K not a multiple of 128, ragged T and N, N not a multiple of 4; with and without bias."""
+    tiles on three SIMDs, role-split 128x128, two plain workgroups per CU, the register-staged kernel with
+    128x128 tiles for K not a multiple of 128 and with 32x64 tiles (64, 128 and 256 features per step) for
+    problems of few tiles, ragged T and N, N not a multiple of 4; with and without bias."""
     T, N, K = shape
     G = 128 if N % 128 == 0 else (N // 2 if N % 2 == 0 else 1)
     say("fwd plain vs checked", shape, "bits", bits)
