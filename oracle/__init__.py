@@ -213,23 +213,24 @@ def bwd_dw_sampled(dY_bf16, xq, clip, ns, js):
     return out
 
 
-def embedding_quantize(E, groups):
+def embedding_quantize(E, groups, bits=8):
+    """Codes u8 [V,d] (0..2^bits-1), h[G], m[G]; bits is 8 or 4."""
     E = _c(E, np.float32)
     V, d = E.shape
     codes = np.empty((V, d), np.uint8)
     h = np.empty(groups, np.float32)
     m = np.empty(groups, np.float32)
-    _check(_lib().qbo_embedding_quantize(_ptr(E), _I64(V), _I64(d), _I64(groups), _ptr(codes), _ptr(h), _ptr(m)),
-           "embedding_quantize")
+    _check(_lib().qbo_embedding_quantize_bits(_ptr(E), _I64(V), _I64(d), int(bits), _I64(groups), _ptr(codes),
+                                              _ptr(h), _ptr(m)), "embedding_quantize")
     return codes, h, m
 
 
-def embedding_gather(codes, h, ids):
+def embedding_gather(codes, h, ids, bits=8):
     codes = _c(codes, np.uint8)
     h = _c(h, np.float32)
     ids = _c(ids, np.int64)
     V, d = codes.shape
     out = np.empty((ids.shape[0], d), np.float64)
-    _check(_lib().qbo_embedding_gather(_ptr(codes), _ptr(h), _I64(V), _I64(d), _I64(h.shape[0]),
-                                       _ptr(ids), _I64(ids.shape[0]), _ptr(out)), "embedding_gather")
+    _check(_lib().qbo_embedding_gather_bits(_ptr(codes), _ptr(h), _I64(V), _I64(d), int(bits), _I64(h.shape[0]),
+                                            _ptr(ids), _I64(ids.shape[0]), _ptr(out)), "embedding_gather")
     return out

@@ -432,13 +432,17 @@ int qbo_bwd_dw_sampled(const uint16_t *dY, const int8_t *xq, float clip,
 }
 
 /* Embedding table (App. "Mixed Precision Quantization for Embedding": the output neurons,
- * i.e. the embedding dimension, are bucketed into groups).  E[V,d] fp32, 8-bit codes,
- * group g = columns [g*d/G, (g+1)*d/G) over all V rows. */
-int qbo_embedding_quantize(const float *E, int64_t V, int64_t d, int64_t G,
-                           uint8_t *codes, float *h, float *m)
+ * i.e. the embedding dimension, are bucketed into groups; 4-bit word embeddings next to 8-bit
+ * position embeddings).  E[V,d] fp32, k-bit codes (k = 4 or 8) with the same quantizer as the
+ * weights, group g = columns [g*d/G, (g+1)*d/G) over all V rows. */
+int qbo_embedding_quantize_bits(const float *E, int64_t V, int64_t d, int bits, int64_t G,
+                                uint8_t *codes, float *h, float *m)
 {
     int64_t g, cols;
+    int L;
     if (!E || !codes || !h || !m || V <= 0 || d <= 0 || G <= 0 || d % G) return QBO_ERR_ARG;
+    if (bits != 4 && bits != 8) return QBO_ERR_ARG;
+    L = (1 << bits) - 1;
     cols = d / G;
     for (g = 0; g < G; ++g) {
         float mg = 0.0f, hg, delta;
@@ -449,32 +453,47 @@ int qbo_embedding_quantize(const float *E, int64_t V, int64_t d, int64_t G,
                 if (!isfinite(a)) return QBO_ERR_NONFINITE;
                 if (a > mg) mg = a;
             }
-        hg = (mg == 0.0f) ? 0.0f : mg / 255.0f;
+        hg = (mg == 0.0f) ? 0.0f : mg / (float)L;
         delta = 2.0f * hg;
         m[g] = mg;
         h[g] = hg;
         for (v = 0; v < V; ++v)
             for (c = 0; c < cols; ++c) {
                 int64_t at = v * d + g * cols + c;
-                codes[at] = (uint8_t)quantize_one(E[at], mg, delta, 255);
+                codes[at] = (uint8_t)quantize_one(E[at], mg, delta, L);
             }
     }
     return QBO_OK;
 }
 
-/* Lookup with de-quantization: out[i,j] = h[g(j)] * (2*u[ids[i], j] - 255), binary64. */
-int qbo_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int64_t G,
-                         const int64_t *ids, int64_t n_ids, double *out)
+int qbo_embedding_quantize(const float *E, int64_t V, int64_t d, int64_t G,
+                           uint8_t *codes, float *h, float *m)
+{
+    return qbo_embedding_quantize_bits(E, V, d, 8, G, codes, h, m);
+}
+
+/* Lookup with de-quantization: out[i,j] = h[g(j)] * (2*u[ids[i], j] - L), L = 2^k - 1, binary64. */
+int qbo_embedding_gather_bits(const uint8_t *codes, const float *h, int64_t V, int64_t d, int bits, int64_t G,
+                              const int64_t *ids, int64_t n_ids, double *out)
 {
     int64_t i, j, cols;
+    int L;
     if (!codes || !h || !ids || !out || V <= 0 || d <= 0 || G <= 0 || d % G || n_ids < 0) return QBO_ERR_ARG;
+    if (bits != 4 && bits != 8) return QBO_ERR_ARG;
+    L = (1 << bits) - 1;
     cols = d / G;
     for (i = 0; i < n_ids; ++i) {
         if (ids[i] < 0 || ids[i] >= V) return QBO_ERR_ARG;
         for (j = 0; j < d; ++j)
-            out[i * d + j] = (double)h[j / cols] * (double)(2 * (int)codes[ids[i] * d + j] - 255);
+            out[i * d + j] = (double)h[j / cols] * (double)(2 * (int)codes[ids[i] * d + j] - L);
     }
     return QBO_OK;
+}
+
+int qbo_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int64_t G,
+                         const int64_t *ids, int64_t n_ids, double *out)
+{
+    return qbo_embedding_gather_bits(codes, h, V, d, 8, G, ids, n_ids, out);
 }
 
 int qbo_num_threads(void)

@@ -422,20 +422,36 @@ def test_backward_linearity():
 
 
 # ---- P13: embedding = weight quantizer on the transposed table; gather = row select -----------------------------------
-def test_embedding_is_weight_grouping_on_transpose():
+@pytest.mark.parametrize("bits", (4, 8))
+def test_embedding_is_weight_grouping_on_transpose(bits):
     V, d, G = 50, 32, 8
     E = (rng(40).standard_normal((V, d)) * 0.02).astype(np.float32)
-    codes, h, m = oracle.embedding_quantize(E, G)
-    cT, hT, mT, _ = oracle.quantize_groupwise(np.ascontiguousarray(E.T), 8, G)
+    codes, h, m = oracle.embedding_quantize(E, G, bits)
+    cT, hT, mT, _ = oracle.quantize_groupwise(np.ascontiguousarray(E.T), bits, G)
     assert (codes == cT.T).all() and (h == hT).all() and (m == mT).all()
     cols = d // G
     for g in range(G):
         assert m[g] == np.abs(E[:, g * cols:(g + 1) * cols]).max()
     ids = np.array([3, 3, 49, 0, 17], np.int64)
-    out = oracle.embedding_gather(codes, h, ids)
-    full = oracle.dequantize_groupwise(cT, hT, 8).T
+    out = oracle.embedding_gather(codes, h, ids, bits)
+    full = oracle.dequantize_groupwise(cT, hT, bits).T
     assert (out == full[ids]).all()
     assert np.abs(out - E[ids]).max() <= h.max() * (1 + 1e-6)
+    assert codes.max() == 2 ** bits - 1 and codes.min() == 0
+
+
+def test_mixed_precision_embedding_size_matches_the_paper():
+    """App. "Mixed Precision Quantization for Embedding": 4-bit word and 8-bit position embeddings bring the
+    embedding table to 11.6 MB (about 8x smaller than the 91 MB of fp32); sizes from the packed row lengths."""
+    d = 768
+    word, pos, typ = 30522 * d, 512 * d, 2 * d
+    mib = 2.0 ** 20
+    fp32 = (word + pos + typ) * 4 / mib
+    assert abs(fp32 - 91.0) < 0.5                                   # Sec. 3: 91 MB for the embedding
+    mixed = (30522 * oracle.packed_row_bytes(d, 4) + 512 * oracle.packed_row_bytes(d, 8) + 2 * oracle.packed_row_bytes(d, 8)) / mib
+    assert abs(mixed - 11.6) < 0.06
+    assert 7.5 < fp32 / mixed < 8.1
+    assert abs((word + pos + typ) / mib - fp32 / 4) < 1e-9           # all 8 bits: the 4x of the abstract
 
 
 def test_argument_errors():
