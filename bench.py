@@ -335,7 +335,16 @@ def embedding_leg(torch, qb, wl, dev):
     out = torch.empty((n, d), dtype=torch.float32, device=dev)
     sq = time_launches(torch, lambda: qb.qb_embedding_quantize(E, GROUPS, codes, h, m), iters=20)
     sg = time_launches(torch, lambda: qb.qb_embedding_gather(codes, h, GROUPS, ids, out), iters=20)
-    return {"quantize_us": round(sq * 1e6, 1), "quantize_gbs": round(V * d * 5.0 / sq / 1e9, 1),
+    # the paper's mixed-precision embedding: BERT-base word embeddings (30522 x 768) at 4 bits
+    V4, d4 = 30522, 768
+    E4 = wl.embedding_table(V4, d4, seed=wl.config_seed(4, 2)).to(dev)
+    c4 = torch.empty((V4, d4 // 2), dtype=torch.uint8, device=dev)
+    out4 = torch.empty((n, d4), dtype=torch.float32, device=dev)
+    sq4 = time_launches(torch, lambda: qb.qb_embedding_quantize_bits(E4, 4, GROUPS, c4, h, m), iters=20)
+    sg4 = time_launches(torch, lambda: qb.qb_embedding_gather_bits(c4, h, 4, GROUPS, ids, out4), iters=20)
+    four = {"table": "30522 x 768, 4-bit", "quantize_us": round(sq4 * 1e6, 1), "quantize_gbs": round(V4 * d4 * 4.5 / sq4 / 1e9, 1),
+            "gather_us": round(sg4 * 1e6, 1), "gather_gbs": round(n * d4 * 4.5 / sg4 / 1e9, 1)}
+    return {"quantize_us": round(sq * 1e6, 1), "quantize_gbs": round(V * d * 5.0 / sq / 1e9, 1), "four_bit": four,
             "gather_us": round(sg * 1e6, 1), "gather_gbs": round(n * d * 5.0 / sg / 1e9, 1),
             "note": "algorithmic bytes: 4 read + 1 written per table element (the kernels read the table twice: column-group "
                     "max over all rows, then codes); 1 read + 4 written per gathered element"}

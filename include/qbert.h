@@ -177,6 +177,19 @@ qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups
 qb_status qb_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int groups,
                               const int64_t *ids, int64_t n_ids, float *out, void *stream);
 
+/*
+ * The same two calls for k = 4 or 8 bits (App. "Mixed Precision Quantization for Embedding":
+ * 4-bit word embeddings next to 8-bit position embeddings, 128 groups).  bits = 8 is exactly
+ * the pair above.  bits = 4: codes is [V, d/2] bytes, column 2i in the low and column 2i+1 in
+ * the high nibble of byte i of the row; out[i,j] = h[g(j)] * (2u - 15).  Other bit-widths:
+ * QB_ERR_BITS.
+ */
+qb_status qb_embedding_quantize_bits(const float *E, int64_t V, int64_t d, int bits, int groups,
+                                     uint8_t *codes, float *h, float *m, void *stream);
+qb_status qb_embedding_gather_bits(const uint8_t *codes, const float *h, int64_t V, int64_t d, int bits,
+                                   int groups, const int64_t *ids, int64_t n_ids, float *out,
+                                   void *stream);
+
 #ifdef __cplusplus
 }
 #endif

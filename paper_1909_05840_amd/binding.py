@@ -20,7 +20,7 @@ QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
-           "qb_embedding_quantize", "qb_embedding_gather")
+           "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits")
 
 
 class _QuantJob(ctypes.Structure):
@@ -69,6 +69,10 @@ def load_library():
     lib.qb_embedding_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
     lib.qb_embedding_gather.restype = ci
     lib.qb_embedding_gather.argtypes = [vp, vp, i64, i64, ci, vp, i64, vp, vp]
+    lib.qb_embedding_quantize_bits.restype = ci
+    lib.qb_embedding_quantize_bits.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp]
+    lib.qb_embedding_gather_bits.restype = ci
+    lib.qb_embedding_gather_bits.argtypes = [vp, vp, i64, i64, ci, ci, vp, i64, vp, vp]
     _lib = lib
     return lib
 
@@ -239,4 +243,32 @@ def qb_embedding_gather(codes, h, groups, ids, out=None):
     if out is None:
         out = torch.empty((n, d), dtype=torch.float32, device=codes.device)
     _check(lib.qb_embedding_gather(_p(codes), _p(h), V, d, groups, _p(ids), n, _p(out), _stream()))
+    return out
+
+
+def qb_embedding_quantize_bits(E, bits, groups, codes=None, h=None, m=None):
+    """bits = 8: codes [V,d] uint8; bits = 4: codes [V,d/2], two codes per byte (even column in the low nibble)."""
+    lib = load_library()
+    _dev(E, torch.float32, "E")
+    V, d = E.shape
+    if codes is None:
+        codes = torch.empty((V, d * bits // 8), dtype=torch.uint8, device=E.device)
+    if h is None:
+        h = torch.empty(max(groups, 1), dtype=torch.float32, device=E.device)
+    if m is None:
+        m = torch.empty(max(groups, 1), dtype=torch.float32, device=E.device)
+    _check(lib.qb_embedding_quantize_bits(_p(E), V, d, bits, groups, _p(codes), _p(h), _p(m), _stream()))
+    return codes, h, m
+
+
+def qb_embedding_gather_bits(codes, h, bits, groups, ids, out=None):
+    lib = load_library()
+    _dev(codes, torch.uint8, "codes")
+    _dev(ids, torch.int64, "ids")
+    V = codes.shape[0]
+    d = codes.shape[1] * 8 // bits
+    n = ids.shape[0]
+    if out is None:
+        out = torch.empty((n, d), dtype=torch.float32, device=codes.device)
+    _check(lib.qb_embedding_gather_bits(_p(codes), _p(h), V, d, bits, groups, _p(ids), n, _p(out), _stream()))
     return out

@@ -332,16 +332,20 @@ __global__ __launch_bounds__(256) void embedding_absmax_kernel(const float *__re
         if (gm[i] != 0u) atomicMax(mb + g_lo + i, gm[i]);
 }
 
-// pass 2: codes, and h = m/255.  Same tiling; a thread sets up the quantizers of its four columns once.
+// pass 2: codes, and h = m/L.  Same tiling; a thread sets up the quantizers of its four columns once.
+// BITS = 8: one code per byte.  BITS = 4: two per byte, column 2i in the low nibble of byte i (a row is the
+// little-endian bit stream of its codes).
+template <int BITS>
 __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__restrict__ E, int64_t V, int d,
                                                                  int cols_per_group, int groups,
                                                                  const float *__restrict__ m, float *__restrict__ h,
                                                                  uint8_t *__restrict__ codes)
 {
+    constexpr float Lf = (float)((1 << BITS) - 1);
     if (blockIdx.x == 0 && blockIdx.y == 0) {
         for (int g = threadIdx.x; g < groups; g += 256) {
             const float mg = m[g];
-            h[g] = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, 255.0f);
+            h[g] = (mg == 0.0f) ? 0.0f : __fdiv_rn(mg, Lf);
         }
     }
     const int d4 = d >> 2;
@@ -353,34 +357,54 @@ __global__ __launch_bounds__(256) void embedding_quantize_kernel(const float *__
     for (int i = 0; i < 4; ++i) {
         const int g = (c + i) / cols_per_group;
         if (i > 0 && g == (c + i - 1) / cols_per_group) qz[i] = qz[i - 1];
-        else qz[i].set(m[g], 255.0f);
+        else qz[i].set(m[g], Lf);
     }
     const int64_t r0 = (int64_t)blockIdx.y * EMB_ROWS;
     const int nr = (int)((V - r0 < EMB_ROWS) ? V - r0 : EMB_ROWS);
     const float4 *src = reinterpret_cast<const float4 *>(E) + r0 * d4 + c4;
-    uint32_t *dst = reinterpret_cast<uint32_t *>(codes) + r0 * d4 + c4;
     auto code4 = [&](const float4 v) {
         uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(qz[0].code_f(v.x), 0, 0u);
         q = __builtin_amdgcn_cvt_pk_u8_f32(qz[1].code_f(v.y), 1, q);
         q = __builtin_amdgcn_cvt_pk_u8_f32(qz[2].code_f(v.z), 2, q);
         return __builtin_amdgcn_cvt_pk_u8_f32(qz[3].code_f(v.w), 3, q);
     };
-    int r = 0;
-    for (; r + 8 <= nr; r += 8) {
-        float4 v[8];
+    if constexpr (BITS == 8) {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(codes) + r0 * d4 + c4;
+        int r = 0;
+        for (; r + 8 <= nr; r += 8) {
+            float4 v[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(r + i) * d4];
+            for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(r + i) * d4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(code4(v[i]), dst + (int64_t)(r + i) * d4);
+            for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(code4(v[i]), dst + (int64_t)(r + i) * d4);
+        }
+        for (; r < nr; ++r) dst[(int64_t)r * d4] = code4(src[(int64_t)r * d4]);
+    } else {
+        // four codes (one per byte of q) -> two bytes: low nibbles from bytes 0 and 2, high from bytes 1 and 3
+        auto nib4 = [&](const float4 v) {
+            const uint32_t q = code4(v);
+            return (uint16_t)((q & 0xFu) | ((q >> 4) & 0xF0u) | ((q >> 8) & 0xF00u) | ((q >> 12) & 0xF000u));
+        };
+        uint16_t *dst = reinterpret_cast<uint16_t *>(codes) + r0 * d4 + c4;
+        int r = 0;
+        for (; r + 8 <= nr; r += 8) {
+            float4 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = src[(int64_t)(r + i) * d4];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dst[(int64_t)(r + i) * d4] = nib4(v[i]);
+        }
+        for (; r < nr; ++r) dst[(int64_t)r * d4] = nib4(src[(int64_t)r * d4]);
     }
-    for (; r < nr; ++r) dst[(int64_t)r * d4] = code4(src[(int64_t)r * d4]);
 }
 
+template <int BITS>
 __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__restrict__ codes,
                                                                const float *__restrict__ h, int64_t V, int d,
                                                                int cols_per_group, const int64_t *__restrict__ ids,
                                                                int64_t n_ids, float *__restrict__ out)
 {
+    constexpr int L = (1 << BITS) - 1;
     const int d4 = d >> 2;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= n_ids * d4) return;
@@ -389,11 +413,18 @@ __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__
     const int64_t tok = ids[i];
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     if (tok >= 0 && tok < V) {
-        const uint32_t q = *reinterpret_cast<const uint32_t *>(codes + tok * d + c);
-        o.x = h[(c + 0) / cols_per_group] * (float)(2 * (int)(q & 255u) - 255);
-        o.y = h[(c + 1) / cols_per_group] * (float)(2 * (int)((q >> 8) & 255u) - 255);
-        o.z = h[(c + 2) / cols_per_group] * (float)(2 * (int)((q >> 16) & 255u) - 255);
-        o.w = h[(c + 3) / cols_per_group] * (float)(2 * (int)(q >> 24) - 255);
+        int u0, u1, u2, u3;
+        if constexpr (BITS == 8) {
+            const uint32_t q = *reinterpret_cast<const uint32_t *>(codes + tok * d + c);
+            u0 = q & 255u; u1 = (q >> 8) & 255u; u2 = (q >> 16) & 255u; u3 = q >> 24;
+        } else {
+            const uint32_t q = *reinterpret_cast<const uint16_t *>(codes + ((tok * d + c) >> 1));
+            u0 = q & 15u; u1 = (q >> 4) & 15u; u2 = (q >> 8) & 15u; u3 = (q >> 12) & 15u;
+        }
+        o.x = h[(c + 0) / cols_per_group] * (float)(2 * u0 - L);
+        o.y = h[(c + 1) / cols_per_group] * (float)(2 * u1 - L);
+        o.z = h[(c + 2) / cols_per_group] * (float)(2 * u2 - L);
+        o.w = h[(c + 3) / cols_per_group] * (float)(2 * u3 - L);
     }
     reinterpret_cast<float4 *>(out)[id] = o;
 }
@@ -543,28 +574,50 @@ extern "C" qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, i
     return launch_status();
 }
 
-extern "C" qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups, uint8_t *codes, float *h,
-                                           float *m, void *stream)
+extern "C" qb_status qb_embedding_quantize_bits(const float *E, int64_t V, int64_t d, int bits, int groups, uint8_t *codes,
+                                                float *h, float *m, void *stream)
 {
     if (!E || !codes || !h || !m) return QB_ERR_NULL;
+    if (bits != 4 && bits != 8) return QB_ERR_BITS;
     if (V <= 0 || V > (1 << 30) || !k_ok(d) || groups <= 0 || d % groups != 0) return QB_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int cpg = (int)(d / groups);
     const dim3 grid((unsigned)((d / 4 + 255) / 256), (unsigned)((V + EMB_ROWS - 1) / EMB_ROWS));
     hipLaunchKernelGGL(fill_zero_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, m, groups);
     hipLaunchKernelGGL(embedding_absmax_kernel, grid, dim3(256), 0, st, E, V, (int)d, cpg, m);
-    hipLaunchKernelGGL(embedding_quantize_kernel, grid, dim3(256), 0, st, E, V, (int)d, cpg, groups, m, h, codes);
+    if (bits == 8)
+        hipLaunchKernelGGL(embedding_quantize_kernel<8>, grid, dim3(256), 0, st, E, V, (int)d, cpg, groups, m, h, codes);
+    else
+        hipLaunchKernelGGL(embedding_quantize_kernel<4>, grid, dim3(256), 0, st, E, V, (int)d, cpg, groups, m, h, codes);
+    return launch_status();
+}
+
+extern "C" qb_status qb_embedding_quantize(const float *E, int64_t V, int64_t d, int groups, uint8_t *codes, float *h,
+                                           float *m, void *stream)
+{
+    return qb_embedding_quantize_bits(E, V, d, 8, groups, codes, h, m, stream);
+}
+
+extern "C" qb_status qb_embedding_gather_bits(const uint8_t *codes, const float *h, int64_t V, int64_t d, int bits,
+                                              int groups, const int64_t *ids, int64_t n_ids, float *out, void *stream)
+{
+    if (!codes || !h || (n_ids > 0 && (!ids || !out))) return QB_ERR_NULL;
+    if (bits != 4 && bits != 8) return QB_ERR_BITS;
+    if (V <= 0 || !k_ok(d) || groups <= 0 || d % groups != 0 || n_ids < 0 || n_ids > (1 << 30)) return QB_ERR_SHAPE;
+    if (n_ids == 0) return QB_OK;
+    const int64_t n4 = n_ids * (d / 4);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bits == 8)
+        hipLaunchKernelGGL(embedding_gather_kernel<8>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, codes, h, V,
+                           (int)d, (int)(d / groups), ids, n_ids, out);
+    else
+        hipLaunchKernelGGL(embedding_gather_kernel<4>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, codes, h, V,
+                           (int)d, (int)(d / groups), ids, n_ids, out);
     return launch_status();
 }
 
 extern "C" qb_status qb_embedding_gather(const uint8_t *codes, const float *h, int64_t V, int64_t d, int groups,
                                          const int64_t *ids, int64_t n_ids, float *out, void *stream)
 {
-    if (!codes || !h || (n_ids > 0 && (!ids || !out))) return QB_ERR_NULL;
-    if (V <= 0 || !k_ok(d) || groups <= 0 || d % groups != 0 || n_ids < 0 || n_ids > (1 << 30)) return QB_ERR_SHAPE;
-    if (n_ids == 0) return QB_OK;
-    const int64_t n4 = n_ids * (d / 4);
-    hipLaunchKernelGGL(embedding_gather_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), codes, h, V, (int)d, (int)(d / groups), ids, n_ids, out);
-    return launch_status();
+    return qb_embedding_gather_bits(codes, h, V, d, 8, groups, ids, n_ids, out, stream);
 }

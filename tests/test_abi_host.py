@@ -104,6 +104,12 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_embedding_quantize(P, 100, 1024, 100, P, P, P, NULL) == 3   # 1024 % 100
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, 0, P, NULL) == 0  # empty lookup
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, -1, P, NULL) == 3
+    # embedding_quantize_bits(E,V,d,bits,groups,codes,h,m,stream), embedding_gather_bits(codes,h,V,d,bits,groups,ids,n,out,stream)
+    assert lib.qb_embedding_quantize_bits(P, 100, 1024, 3, 128, P, P, P, NULL) == 2
+    assert lib.qb_embedding_quantize_bits(P, 100, 1024, 4, 128, NULL, P, P, NULL) == 1
+    assert lib.qb_embedding_quantize_bits(P, 100, 1000, 4, 125, P, P, P, NULL) == 3
+    assert lib.qb_embedding_gather_bits(P, P, 100, 1024, 2, 128, P, 4, P, NULL) == 2
+    assert lib.qb_embedding_gather_bits(P, P, 100, 1024, 4, 128, P, 0, P, NULL) == 0
 
 
 def test_package_never_imports_the_oracle():

@@ -412,6 +412,34 @@ def test_embedding(qb, shape):
     assert (ob[:2] == 0).all() and (ob[2].numpy() == oracle.embedding_gather(oc, oh, np.array([0]))[0].astype(np.float32)).all()
 
 
+@pytest.mark.parametrize("shape", [(30522, 768, 128, 4096), (1000, 64, 8, 100), (517, 768, 128, 1), (300, 128, 1, 50),
+                                   (64, 192, 192, 10), (203, 2304, 36, 20), (100, 192, 64, 5)])
+def test_embedding_4bit(qb, shape):
+    """4-bit table (the paper's mixed-precision embedding): packed bytes equal the oracle's codes packed as a
+    little-endian bit stream, scales bit for bit, the gather within 1e-6; the 8-bit call through the same entry
+    point equals the dedicated one."""
+    V, d, G, n = shape
+    say("embedding 4-bit", shape)
+    E = wl.embedding_table(V, d, seed=wl.config_seed(4, V + d + 4))
+    ids = wl.token_ids(n, V, seed=wl.config_seed(4, 2))
+    codes, h, m = qb.qb_embedding_quantize_bits(E.to(DEV), 4, G)
+    out = qb.qb_embedding_gather_bits(codes, h, 4, G, ids.to(DEV))
+    torch.cuda.synchronize()
+    oc, oh, om = oracle.embedding_quantize(E.numpy(), G, bits=4)
+    assert codes.shape == (V, d // 2)
+    assert (codes.cpu().numpy() == oracle.pack(oc, 4)).all()
+    assert (h.cpu().numpy().view(np.uint32) == oh.view(np.uint32)).all()
+    assert (m.cpu().numpy().view(np.uint32) == om.view(np.uint32)).all()
+    oo = oracle.embedding_gather(oc, oh, ids.numpy(), bits=4)
+    assert_rel(out.cpu().numpy(), oo.astype(np.float32), tol=1e-6)
+    bad = torch.tensor([V, -1, 0], dtype=torch.int64)
+    ob = qb.qb_embedding_gather_bits(codes, h, 4, G, bad.to(DEV)).cpu()
+    assert (ob[:2] == 0).all() and (ob[2].numpy() == oracle.embedding_gather(oc, oh, np.array([0]), bits=4)[0].astype(np.float32)).all()
+    c8, h8, m8 = qb.qb_embedding_quantize_bits(E.to(DEV), 8, G)
+    c8b, h8b, m8b = qb.qb_embedding_quantize(E.to(DEV), G)
+    assert torch.equal(c8, c8b) and torch.equal(h8, h8b) and torch.equal(m8, m8b)
+
+
 def test_runs_are_deterministic(qb):
     """Integer accumulation is order independent and dW partial sums are added in a fixed order."""
     T, N, K, G, bits = 2048, 768, 768, 128, 3
