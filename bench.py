@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-streams", type=int, default=1, help="streams the step's independent GEMMs are spread over")
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference dispatch for HBM byte counters)")
@@ -88,12 +89,30 @@ def main():
         for i in range(len(linears)):
             qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
 
-    def stage_gemm():
-        for b in BITS_SWEEP:
-            for i, (_, N, K) in enumerate(linears):
-                o = q[(b, i)]
-                qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
-                                  Y=Ys[i])
+    side_all = [torch.cuda.Stream(device=dev) for _ in range(3)]   # default priority
+
+    def stage_gemm(nstreams=None):
+        side = side_all[:max(0, (args.gemm_streams if nstreams is None else nstreams) - 1)]
+        if not side:
+            for b in BITS_SWEEP:
+                for i, (_, N, K) in enumerate(linears):
+                    o = q[(b, i)]
+                    qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
+                                      Y=Ys[i])
+            return
+        # the GEMMs of different linears are independent: linear i goes to stream i % n (fork / join on events)
+        cur = torch.cuda.current_stream()
+        lanes = [cur] + side
+        for s_ in side:
+            s_.wait_stream(cur)
+        for i, (_, N, K) in enumerate(linears):
+            with torch.cuda.stream(lanes[i % len(lanes)]):
+                for b in BITS_SWEEP:
+                    o = q[(b, i)]
+                    qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
+                                      Y=Ys[i])
+        for s_ in side:
+            cur.wait_stream(s_)
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
@@ -131,6 +150,27 @@ def main():
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+
+        # ---- the same step with the GEMMs of different linears on two streams (they are independent of each
+        # other; in a network they would belong to two micro-batches): reported beside `value`, not as `value`
+        overlapped = None
+        if use_graph and not args.no_extras and args.gemm_streams == 1:
+            def step2():
+                stage_quantize()
+                stage_act()
+                stage_gemm(2)
+            step2()
+            stream.synchronize()
+            run2 = capture(step2)
+            for _ in range(args.warmup):
+                run2()
+            stream.synchronize()
+            t2 = time.perf_counter()
+            for k in range(args.steps):
+                run2()
+            stream.synchronize()
+            torch.cuda.synchronize()
+            overlapped = (time.perf_counter() - t2) * 1e3 / args.steps
 
         # ---- per-kernel pass: each stage on its own, 16 kernels per graph, ten replays between two events.
         # The quantize/pack stage is one kernel reading 113 MB of weights that would stay in the 256 MB
@@ -190,7 +230,8 @@ def main():
         "config": {"workload": "configs[1]: BERT-base encoder layer, 4 linears (QKV 768->2304, out 768->768, "
                                "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
                                "step = 16 quantize/pack + 4 act-quant + 16 int8 GEMM+epilogue",
-                   "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph},
+                   "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph,
+                   "gemm_streams": args.gemm_streams},
         "roofline": {"kernel": "qgemm_i8_ws_kernel / qgemm_i8_dma_kernel (int8 MFMA GEMM + scale epilogue), "
                                "16 launches per step",
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
@@ -209,6 +250,10 @@ def main():
         },
     }
 
+    if overlapped is not None:
+        out["overlapped"] = {"gemm_streams": 2, "ms_per_step": round(overlapped, 4),
+                             "value": round(gemm_ops / (overlapped * 1e-3) / 1e12, 3),
+                             "note": "same step, the GEMMs of different linears on two streams inside the graph"}
     if not args.no_extras:
         out["shapes"] = per_shape(torch, qb, wl, dev)
         out["q8_output"] = q8_output_leg(torch, qb, wl, dev)
@@ -231,16 +276,28 @@ def measured_traffic(kernel):
 
 
 def time_launches(torch, fn, iters=100, warm=30):
-    for _ in range(warm):
-        fn()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e-3 / iters
+    """Seconds per call of fn: ten calls captured in a HIP graph (the Python binding costs more per call than a
+    small kernel runs), the graph replayed between two events on its stream."""
+    s = torch.cuda.Stream()   # default priority
+    per = 10
+    with torch.cuda.stream(s):
+        for _ in range(warm):
+            fn()
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            for _ in range(per):
+                fn()
+        g.replay()
+        s.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(1, iters // per)
+        e0.record(s)
+        for _ in range(reps):
+            g.replay()
+        e1.record(s)
+        s.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / (reps * per)
 
 
 def per_shape(torch, qb, wl, dev):
