@@ -102,9 +102,11 @@ def test_hip_graph_replays_match_eager(qb):
     packed, h, m, rs_w = qb.qb_quantize_groupwise(W, bits, G)
     Xq, rs_x = qb.qb_quantize_act(X, CLIP)
     Y_eager = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N).clone()
+    Yq_eager, rsy_eager = [t.clone() for t in qb.qb_qlinear_fwd_q8(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, 2.0)]
     p_eager = packed.clone()
     torch.cuda.synchronize()
     Y = torch.empty_like(Y_eager)
+    Yq, rs_y = torch.empty_like(Yq_eager), torch.empty_like(rsy_eager)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         g = torch.cuda.CUDAGraph()
@@ -113,13 +115,17 @@ def test_hip_graph_replays_match_eager(qb):
                                                "rs_w": rs_w}])
             qb.qb_quantize_act(X, CLIP, Xq, rs_x)
             qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, Y=Y)
+            qb.qb_qlinear_fwd_q8(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, 2.0, Yq=Yq, rs_y=rs_y)
         for rep in range(4):
             Y.zero_()
             packed.zero_()
+            Yq.zero_()
+            rs_y.fill_(12345)   # the call clears the row sums itself, on every replay
             stream.synchronize()
             g.replay()
             stream.synchronize()
             assert torch.equal(Y, Y_eager) and torch.equal(packed, p_eager), rep
+            assert torch.equal(Yq, Yq_eager) and torch.equal(rs_y, rsy_eager), rep
             # eager work of the program between replays
             Y2 = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N)
             stream.synchronize()
@@ -320,10 +326,11 @@ def test_forward_q8_output_gelu(qb, bits):
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
 def test_forward_q8_config2_full_size(qb, bits, lin):
-    """Configuration 2 shapes at T = 4096 as bench.py launches them: sampled token rows against the oracle (rows
-    are independent), row sums of every row against the GPU's own codes."""
+    """Configuration 2 shapes at T = 4096 as bench.py launches them (QKV also at 12288 tokens: nine tiles per
+    workgroup): sampled token rows against the oracle (rows are independent), row sums of every row against the
+    GPU's own codes."""
     name, N, K = lin
-    T, G = 4096, 128
+    T, G = (12288 if name == "qkv" and bits == 3 else 4096), 128
     say("fwd q8 full size", lin, "bits", bits)
     W = wl.weight(N, K, seed=wl.config_seed(1, N + K + bits))
     X = wl.activation(T, K, seed=wl.config_seed(1, N + K + bits) + 1)
