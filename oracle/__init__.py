@@ -130,6 +130,34 @@ def qlinear_fwd(xq, clip, codes, h, bits, bias=None, openmp=False):
     return Y, A4, acc
 
 
+def quantize_act_dyn(X):
+    """Per-token max-abs range. Returns xq[T,K] i8, rs_x[T] i32, hx[T] f32."""
+    X = _c(X, np.float32)
+    T, K = X.shape
+    xq = np.empty((T, K), np.int8)
+    rs = np.empty(T, np.int32)
+    hx = np.empty(T, np.float32)
+    _check(_lib().qbo_quantize_act_dyn(_ptr(X), _I64(T), _I64(K), _ptr(xq), _ptr(rs), _ptr(hx)), "quantize_act_dyn")
+    return xq, rs, hx
+
+
+def qlinear_fwd_dyn(xq, hx, codes, h, bits, bias=None, openmp=False):
+    """Forward with one activation scale per token. Returns Y[T,N] f32, A4[T,N] i32."""
+    xq = _c(xq, np.int8)
+    hx = _c(hx, np.float32)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    Y = np.empty((T, N), np.float32)
+    A4 = np.empty((T, N), np.int32)
+    rc = _lib(openmp).qbo_qlinear_fwd_dyn(_ptr(xq), _ptr(hx), _ptr(codes), _ptr(h), int(bits), _I64(h.shape[0]),
+                                          _I64(T), _I64(N), _I64(K), _ptr(bias), _ptr(Y), _ptr(A4))
+    _check(rc, "qlinear_fwd_dyn")
+    return Y, A4
+
+
 def qlinear_fwd_q8(xq, clip, codes, h, bits, clip_out, bias=None, act=0, openmp=False):
     """Forward with the output quantized to 8 bits at once. Returns yq[T,N] i8 (= u - 128), rs_y[T] i32."""
     xq = _c(xq, np.int8)

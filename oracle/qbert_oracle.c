@@ -27,7 +27,7 @@
  *   - Delta is formed as 2*(m/L);
  *   - groups are G equal blocks of N/G consecutive rows (output neurons) of W[N,K];
  *   - activations use the same quantizer with k = 8 and a caller-given range [-c, +c];
- *     the stored byte is u - 128;
+ *     the stored byte is u - 128; the dynamic variant takes c per token as the row's max-abs;
  *   - the straight-through estimator is the identity through both quantizers, and the
  *     weight gradient uses the de-quantized activation;
  *   - the embedding table is grouped over its columns (embedding dimension);
@@ -201,6 +201,35 @@ int qbo_quantize_act(const float *X, int64_t T, int64_t K, float clip, int8_t *x
     return QBO_OK;
 }
 
+/* The same quantizer with a range per token (row): [-c_t, +c_t], c_t = max_j |X[t,j]| (the appendix
+ * allows any range [q0, q_255]; the paper fixes none for activations).  A dynamic range needs no
+ * calibration and never clips.  out: xq[T,K] = u - 128, rs_x[t], hx[t] = c_t/255 (0 for a zero row,
+ * whose codes are 0 like those of an all-zero weight group). */
+int qbo_quantize_act_dyn(const float *X, int64_t T, int64_t K, int8_t *xq, int32_t *rs_x, float *hx)
+{
+    int64_t t, j;
+    if (!X || !xq || !rs_x || !hx || T <= 0 || K <= 0) return QBO_ERR_ARG;
+    for (t = 0; t < T; ++t) {
+        float c = 0.0f, h, delta;
+        int32_t acc = 0;
+        for (j = 0; j < K; ++j) {
+            float a = fabsf(X[t * K + j]);
+            if (!isfinite(a)) return QBO_ERR_NONFINITE;
+            if (a > c) c = a;
+        }
+        h = (c == 0.0f) ? 0.0f : c / 255.0f;
+        delta = 2.0f * h;
+        hx[t] = h;
+        for (j = 0; j < K; ++j) {
+            int u = quantize_one(X[t * K + j], c, delta, 255);
+            xq[t * K + j] = (int8_t)(u - 128);
+            acc += u - 128;
+        }
+        rs_x[t] = acc;
+    }
+    return QBO_OK;
+}
+
 /* De-quantized activation: h_x*(2u - 255) = h_x*(2*xq + 1). */
 int qbo_dequantize_act(const int8_t *xq, int64_t T, int64_t K, float clip, double *Xhat)
 {
@@ -264,6 +293,34 @@ int qbo_qlinear_fwd(const int8_t *xq, float clip, const uint8_t *codes, const fl
             Y[t * N + n] = (float)y;
             if (A4) A4[t * N + n] = (int32_t)a4;
             if (acc) acc[t * N + n] = (int32_t)a;
+        }
+    }
+    return bad ? QBO_ERR_OVERFLOW : QBO_OK;
+}
+
+/* Forward with one activation scale per token: Y[t,n] = float(hx[t]*h_g*A4 (+bias)). */
+int qbo_qlinear_fwd_dyn(const int8_t *xq, const float *hx, const uint8_t *codes, const float *h,
+                        int bits, int64_t G, int64_t T, int64_t N, int64_t K, const float *bias,
+                        float *Y, int32_t *A4)
+{
+    int64_t t, rows;
+    int bad = 0;
+    if (!xq || !hx || !codes || !h || !Y || !bits_ok(bits)) return QBO_ERR_ARG;
+    if (T <= 0 || N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    rows = N / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (t = 0; t < T; ++t) {
+        int64_t n;
+        for (n = 0; n < N; ++n) {
+            int64_t a = 0, a4 = 0;
+            double y;
+            if (fwd_one(xq + t * K, codes + n * K, K, bits, &a, &a4) != QBO_OK) { bad = 1; continue; }
+            y = (double)hx[t] * (double)h[n / rows] * (double)a4;
+            if (bias) y += (double)bias[n];
+            Y[t * N + n] = (float)y;
+            if (A4) A4[t * N + n] = (int32_t)a4;
         }
     }
     return bad ? QBO_ERR_OVERFLOW : QBO_OK;

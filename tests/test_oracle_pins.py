@@ -401,6 +401,47 @@ def test_q8_output_gelu_matches_an_independent_erf():
     assert big.any() and np.abs(lev[big] - np.minimum(g[big], 1.0)).max() <= 1.0 / 255 * 1.001
 
 
+# ---- dynamic (per-token max-abs) activation range ---------------------------------------------------------------
+def test_dynamic_activation_range_equals_static_quantizer_row_by_row():
+    """Each row is the static quantizer with clip = that row's max-abs; the row's extreme hits code 0 or 255; the
+    forward with per-token scales equals the fp64 GEMM of the de-quantized operands."""
+    T, K, N, G, bits = 13, 64, 12, 3, 4
+    X = rng(70).standard_normal((T, K)).astype(np.float32)
+    X[3] *= 100.0
+    X[5] = 0.0
+    X[7] = 2.0 ** -20 * X[7]
+    xq, rs, hx = oracle.quantize_act_dyn(X)
+    for t in range(T):
+        c = float(np.abs(X[t]).max())
+        if c == 0.0:
+            assert hx[t] == 0 and (xq[t] == -128).all() and rs[t] == -128 * K   # code 0 everywhere, like a zero group
+            continue
+        q1, r1 = oracle.quantize_act(X[t:t + 1], c)
+        assert (xq[t] == q1[0]).all() and rs[t] == r1[0]
+        assert hx[t] == np.float32(c) / np.float32(255)
+        assert xq[t].max() == 127 or xq[t].min() == -128
+        # nearest level of the exact quotient
+        lev = float(hx[t]) * (2 * (xq[t].astype(np.int64) + 128) - 255)
+        assert np.abs(lev - X[t].astype(np.float64)).max() <= float(hx[t]) * (1 + 1e-5)
+    W = (rng(71).standard_normal((N, K)) * 0.04).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    bias = rng(72).standard_normal(N).astype(np.float32)
+    Y, A4 = oracle.qlinear_fwd_dyn(xq, hx, codes, h, bits)
+    What = oracle.dequantize_groupwise(codes, h, bits)
+    Xhat = hx.astype(np.float64)[:, None] * (2 * xq.astype(np.float64) + 1)
+    ref = Xhat @ What.T
+    assert np.allclose(Y, ref, rtol=1e-6, atol=1e-30)
+    assert (Y[5] == 0).all() and (A4[5] != 0).any()      # zero row: zero scale times a non-zero integer
+    Yb, _ = oracle.qlinear_fwd_dyn(xq, hx, codes, h, bits, bias=bias)
+    assert np.allclose(Yb, ref + bias[None, :], rtol=1e-6, atol=1e-7)
+    # a constant per-token scale reproduces the static forward bit for bit
+    xs, rss = oracle.quantize_act(X, 6.0)
+    Ys, A4s, _ = oracle.qlinear_fwd(xs, 6.0, codes, h, bits)
+    hconst = np.full(T, np.float32(6.0) / np.float32(255), np.float32)
+    Yd, A4d = oracle.qlinear_fwd_dyn(xs, hconst, codes, h, bits)
+    assert (Yd == Ys).all() and (A4d == A4s).all()
+
+
 # ---- P12: backward is linear in dY ---------------------------------------------------------------------------------
 def test_backward_linearity():
     T, N, K = 8, 6, 16
