@@ -257,6 +257,7 @@ def main():
     if not args.no_extras:
         out["shapes"] = per_shape(torch, qb, wl, dev)
         out["q8_output"] = q8_output_leg(torch, qb, wl, dev)
+        out["dynamic_range"] = dynamic_range_leg(torch, qb, wl, dev)
         out["backward"] = backward_leg(torch, qb, wl, dev)
         out["embedding"] = embedding_leg(torch, qb, wl, dev)
     if not args.no_cpu_baseline:
@@ -354,6 +355,28 @@ def q8_output_leg(torch, qb, wl, dev):
                         "frac_int8_peak": round(ops / s8 / 1e12 / PEAK_INT8_TOPS, 4),
                         "roofline_tops": round(roof, 1), "frac_roofline": round(ops / s8 / 1e12 / roof, 4)})
         del W, X, Y, Yq, Xq
+    return res
+
+
+def dynamic_range_leg(torch, qb, wl, dev):
+    """Per-token dynamic activation range: the quantizer and the forward that takes per-token scales, next to the
+    static-clip calls on the same shapes (4 bits, T = 4096)."""
+    res = []
+    for (name, N, K) in wl.BERT_BASE_LINEARS:
+        T, b = T_TOKENS, 4
+        W = wl.weight(N, K, seed=N + K).to(dev)
+        X = wl.activation(T, K, seed=T + K).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        hx = torch.empty(T, dtype=torch.float32, device=dev)
+        Y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        sa = time_launches(torch, lambda: qb.qb_quantize_act(X, CLIP, Xq, rs_x))
+        sad = time_launches(torch, lambda: qb.qb_quantize_act_dyn(X, Xq, rs_x, hx))
+        sf = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        sfd = time_launches(torch, lambda: qb.qb_qlinear_fwd_dyn(Xq, rs_x, hx, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        res.append({"linear": name, "act_quant_us": round(sa * 1e6, 2), "act_quant_dyn_us": round(sad * 1e6, 2),
+                    "fwd_us": round(sf * 1e6, 2), "fwd_dyn_us": round(sfd * 1e6, 2)})
+        del W, X, Y, Xq
     return res
 
 

@@ -140,6 +140,21 @@ qb_status qb_qlinear_fwd_q8(const int8_t *Xq, const int32_t *rs_x, float clip,
                             int8_t *Yq, int32_t *rs_y, void *stream);
 
 /*
+ * Activation quantization with a range per token (the appendix's quantizer takes any range
+ * [q0, q_255]; the paper fixes none for activations): c_t = max_j |X[t,j]|, otherwise as
+ * qb_quantize_act.  Needs no calibrated clip and never clips.
+ *   hx_rows  out  [T] fp32, c_t / 255 (0 for an all-zero row, whose codes are 0)
+ * and the forward that takes those scales: Y[t,n] = (hx_rows[t] * h_{g(n)}) * float(A4[t,n]) (+ bias[n]);
+ * other arguments as qb_qlinear_fwd.
+ */
+qb_status qb_quantize_act_dyn(const float *X, int64_t T, int64_t K,
+                              int8_t *Xq, int32_t *rs_x, float *hx_rows, void *stream);
+qb_status qb_qlinear_fwd_dyn(const int8_t *Xq, const int32_t *rs_x, const float *hx_rows,
+                             const void *packed, const float *h, const int32_t *rs_w,
+                             int bits, int groups, int64_t T, int64_t N, int64_t K,
+                             const float *bias, float *Y, int32_t *A4_debug, void *stream);
+
+/*
  * Straight-through-estimator backward (Sec. 3.1, last paragraph; App., last sentence): both
  * quantizers pass the gradient through unchanged, so
  *   dX[t,j] = sum_n dY[t,n] * Q(w)[n,j]        dW[n,j] = sum_t dY[t,n] * Q(x)[t,j]

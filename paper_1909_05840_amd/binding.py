@@ -20,7 +20,8 @@ QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
-           "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits")
+           "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
+           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn")
 
 
 class _QuantJob(ctypes.Structure):
@@ -69,6 +70,10 @@ def load_library():
     lib.qb_embedding_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
     lib.qb_embedding_gather.restype = ci
     lib.qb_embedding_gather.argtypes = [vp, vp, i64, i64, ci, vp, i64, vp, vp]
+    lib.qb_quantize_act_dyn.restype = ci
+    lib.qb_quantize_act_dyn.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_fwd_dyn.restype = ci
+    lib.qb_qlinear_fwd_dyn.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_embedding_quantize_bits.restype = ci
     lib.qb_embedding_quantize_bits.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp]
     lib.qb_embedding_gather_bits.restype = ci
@@ -272,3 +277,32 @@ def qb_embedding_gather_bits(codes, h, bits, groups, ids, out=None):
         out = torch.empty((n, d), dtype=torch.float32, device=codes.device)
     _check(lib.qb_embedding_gather_bits(_p(codes), _p(h), V, d, bits, groups, _p(ids), n, _p(out), _stream()))
     return out
+
+
+def qb_quantize_act_dyn(X, Xq=None, rs_x=None, hx_rows=None):
+    """Per-token max-abs range: X[T,K] fp32 -> (Xq[T,K] int8, rs_x[T] int32, hx_rows[T] fp32)."""
+    lib = load_library()
+    _dev(X, torch.float32, "X")
+    T, K = X.shape
+    if Xq is None:
+        Xq = torch.empty((T, K), dtype=torch.int8, device=X.device)
+    if rs_x is None:
+        rs_x = torch.empty(T, dtype=torch.int32, device=X.device)
+    if hx_rows is None:
+        hx_rows = torch.empty(T, dtype=torch.float32, device=X.device)
+    _check(lib.qb_quantize_act_dyn(_p(X), T, K, _p(Xq), _p(rs_x), _p(hx_rows), _stream()))
+    return Xq, rs_x, hx_rows
+
+
+def qb_qlinear_fwd_dyn(Xq, rs_x, hx_rows, packed, h, rs_w, bits, groups, N, bias=None, Y=None, want_a4=False):
+    """Forward with one activation scale per token. Returns Y[T,N] fp32 (and A4[T,N] int32 if asked)."""
+    lib = load_library()
+    _dev(Xq, torch.int8, "Xq")
+    _dev(hx_rows, torch.float32, "hx_rows")
+    T, K = Xq.shape
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=Xq.device)
+    A4 = torch.empty((T, N), dtype=torch.int32, device=Xq.device) if want_a4 else None
+    _check(lib.qb_qlinear_fwd_dyn(_p(Xq), _p(rs_x), _p(hx_rows), _p(packed), _p(h), _p(rs_w), bits, groups,
+                                  T, N, K, _p(bias), _p(Y), _p(A4), _stream()))
+    return (Y, A4) if want_a4 else Y

@@ -33,8 +33,9 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
-    int tiles_m, int tiles_n)
+    int tiles_m, int tiles_n, const float *__restrict__ hx_rows)
 {
+    // hx_rows: one activation scale per token (dynamic range) instead of hx, or null
     constexpr int THREADS = 64 * WM * WN;
     constexpr bool QB_SKIP_STORES = false;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64 * KU, LDA = BK + 16;
@@ -176,7 +177,8 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
         const bool n_ok = n < N;
         const int nn = n_ok ? n : N - 1;
         const int coln = 2 * rs_w[nn] + K;
-        const float scale = hx * h[nn / rows_per_group];
+        const float hg = h[nn / rows_per_group];
+        const float scale = hx * hg;
         const float bv = bias ? bias[nn] : 0.0f;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
@@ -186,6 +188,17 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
                 if (sum == 0x12345678) Y[0] = 1.0f;
+            } else if (hx_rows) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int t = t0 + 8 * (i >> 2) + (i & 3);
+                    if (t < T && n_ok) {
+                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                        const size_t at = (size_t)t * N + n;
+                        Y[at] = (hx_rows[t] * hg) * (float)a4 + bv;
+                        if (A4out) A4out[at] = a4;
+                    }
+                }
             } else if (interior) {
                 int rx[16];
 #pragma unroll
@@ -561,7 +574,7 @@ __device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_addr)
 template <int BM, int BN>
 __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *pp, int e2, int tl, int nl, int t0, int n0,
                                                 int T, int N, int K, float hx, bool has_bias, bool fast,
-                                                float *__restrict__ Y, int32_t *__restrict__ A4out)
+                                                float *__restrict__ Y, int32_t *__restrict__ A4out, bool dyn = false)
 {
     // one 32x32 block: acc[r] is token tl + 8*(r/4) + (r%4) of the tile, neuron nl
     const int *p_rx = reinterpret_cast<const int *>(pp);
@@ -570,6 +583,24 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
     const int coln = 2 * p_rw[nl] + K;
     const float scale = hx * p_h[nl];
     const float bv = has_bias ? p_b[nl] : 0.0f;
+    // per row: the scale.  dyn: one activation scale per token, the tile's BM of them follow the bias in the
+    // parameter block; otherwise the one scale of the call.
+    float sc[16];
+    if (dyn) {
+        const float *p_hx = p_b + BN;
+        const float hg = p_h[nl];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = *reinterpret_cast<const float4 *>(p_hx + tl + 8 * q);
+            sc[4 * q + 0] = v.x * hg;
+            sc[4 * q + 1] = v.y * hg;
+            sc[4 * q + 2] = v.z * hg;
+            sc[4 * q + 3] = v.w * hg;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[r] = scale;
+    }
     int rx[16];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -584,7 +615,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int a4 = 4 * acc[r] + rx[r];
-            __builtin_nontemporal_store(scale * (float)a4 + bv,
+            __builtin_nontemporal_store(sc[r] * (float)a4 + bv,
                                         reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
         }
     } else if (n0 + nl < N) {  // edge tiles and the debug output: every element checked
@@ -594,7 +625,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
             if (t < T) {
                 const int a4 = 4 * acc[r] + rx[r];
                 const size_t at = (size_t)t * N + n0 + nl;
-                Y[at] = scale * (float)a4 + bv;
+                Y[at] = sc[r] * (float)a4 + bv;
                 if (A4out) A4out[at] = a4;
             }
         }
@@ -607,6 +638,7 @@ struct OutQ {
     int32_t *rs_y;    // [T] row sums of Yq, accumulated with atomics (zero-filled before the launch)
     float clip_out;   // range [-clip_out, +clip_out]
     int act;          // 0 none, 1 GELU
+    const float *hx_rows;  // fp32 output only: one activation scale per token (dynamic range) instead of hx, or null
 };
 
 // One 32x32 block of the 8-bit output: the value that decides the code is formed in binary32 with one
@@ -700,7 +732,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
     static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
     constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
-    constexpr int PARAM_BYTES = (BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias
+    constexpr int PARAM_BYTES = (2 * BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias | per-token scales
     static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
 
     // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
@@ -783,6 +815,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                     int t = tile_m * BM + c * 64 + lane;
                     t = t < T ? t : T - 1;
                     copy4_to_lds(rs_x + t, pbase + c * 256);
+                    if (oq.hx_rows) copy4_to_lds(oq.hx_rows + t, pbase + (BM + 3 * BNP) * 4 + c * 256);
                 }
 #pragma unroll
                 for (int c = 0; c < BNP / 64; ++c) {
@@ -993,7 +1026,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
             for (int tn = 0; tn < TN; ++tn)
                 store_block_lds<BM, BNP>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
                                         (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, tile_m * BM, tile_n * BN,
-                                        T, N, K, hx, bias != nullptr, fast, Y, A4out);
+                                        T, N, K, hx, bias != nullptr, fast, Y, A4out, oq.hx_rows != nullptr);
         }
         pb ^= 1;
     }
@@ -1010,7 +1043,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
 void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
-               int grid_cap)
+               int grid_cap, const float *hx_rows = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -1018,7 +1051,7 @@ void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, con
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
     hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, false>), dim3(grid),
                        dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                       tiles_m, tiles_n, OutQ{nullptr, nullptr, 1.0f, 0});
+                       tiles_m, tiles_n, OutQ{nullptr, nullptr, 1.0f, 0, hx_rows});
 }
 
 // the same with the 8-bit output
@@ -1037,12 +1070,13 @@ void launch_ws_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, 
 
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
 void launch_cfg(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
-                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st)
+                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
+                const float *hx_rows = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     hipLaunchKernelGGL((qgemm_i8_kernel<BITS, TM, TN, WM, WN, KU>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), 0, st,
-                       Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n);
+                       Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n, hx_rows);
 }
 
 // grid_cap: upper bound of workgroups (a multiple of 8); 0 = one workgroup per tile
@@ -1061,7 +1095,8 @@ void launch_dma(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, co
 
 template <int BITS>
 void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
-                 const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st)
+                 const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
+                 const float *hx_rows = nullptr)
 {
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     if (tiles128 <= 160) {
@@ -1069,13 +1104,13 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         // and pay ~6.5 us at least; 32x64 tiles of the register-staged kernel spread the work over the chip
         // (measured 4.4-5 us against 8 at T <= 1024, N = 768; 6.8 against 8.4 at 1024 x 2304 x 768; equal
         // at about 190 tiles).  Long contractions take 256 features per step.
-        if (K % 256 == 0 && K >= 2048) launch_cfg<BITS, 1, 1, 1, 2, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
-        else if (K % 128 == 0) launch_cfg<BITS, 1, 1, 1, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
-        else launch_cfg<BITS, 1, 1, 1, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+        if (K % 256 == 0 && K >= 2048) launch_cfg<BITS, 1, 1, 1, 2, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
+        else if (K % 128 == 0) launch_cfg<BITS, 1, 1, 1, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
+        else launch_cfg<BITS, 1, 1, 1, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
         return;
     }
     if (K % 128 != 0) {  // odd number of 64-feature units: register-staged kernel, one unit per step
-        launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st);
+        launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
         return;
     }
     // Tile choice (measured on BERT-base and BERT-large shapes).  Copies issued on a SIMD that is busy
@@ -1092,9 +1127,9 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
     if (86 * rounds96 < 100 * rounds128)
-        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
-    else if (tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))
-        launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256);
+        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows);
+    else if (hx_rows || tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))  // (per-token scales: role-split kernels only)
+        launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows);
     else
         launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
 }
@@ -1244,13 +1279,33 @@ extern "C" qb_status qb_qlinear_fwd_q8(const int8_t *Xq, const int32_t *rs_x, fl
     const int rpg = (int)(N / groups);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t *p = static_cast<const uint8_t *>(packed);
-    const OutQ oq{Yq, rs_y, clip_out, act};
+    const OutQ oq{Yq, rs_y, clip_out, act, nullptr};
     hipLaunchKernelGGL(fill_zero_i32_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, rs_y, (int)T);
     switch (bits) {
         case 2: launch_bits_q8<2>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
         case 3: launch_bits_q8<3>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
         case 4: launch_bits_q8<4>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
         default: launch_bits_q8<8>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
+    }
+    return launch_status();
+}
+
+extern "C" qb_status qb_qlinear_fwd_dyn(const int8_t *Xq, const int32_t *rs_x, const float *hx_rows, const void *packed,
+                                        const float *h, const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N,
+                                        int64_t K, const float *bias, float *Y, int32_t *A4_debug, void *stream)
+{
+    if (!Xq || !rs_x || !hx_rows || !packed || !h || !rs_w || !Y) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0)
+        return QB_ERR_SHAPE;
+    const int rpg = (int)(N / groups);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    switch (bits) {
+        case 2: launch_bits<2>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
+        case 3: launch_bits<3>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
+        case 4: launch_bits<4>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
+        default: launch_bits<8>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
     }
     return launch_status();
 }

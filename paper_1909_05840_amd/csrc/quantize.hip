@@ -260,6 +260,54 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
     }
 }
 
+// ---- activations with a range per token: c_t = max_j |X[t,j]|.  One wavefront per row; the row's first
+// 64*V float4 stay in registers between the max and the quantization, the rest (K > 256*V) is read again.
+template <int V>
+__global__ __launch_bounds__(256) void quantize_act_dyn_kernel(const float *__restrict__ X, int T, int K,
+                                                               int8_t *__restrict__ Xq, int32_t *__restrict__ rs_x,
+                                                               float *__restrict__ hx)
+{
+    const int lane = threadIdx.x & 63;
+    const int nwaves = gridDim.x * 4;
+    const int k4 = K >> 2;
+    for (int row = blockIdx.x * 4 + (threadIdx.x >> 6); row < T; row += nwaves) {
+        const float4 *src = reinterpret_cast<const float4 *>(X + (size_t)row * K);
+        float4 v[V];
+        float mx = 0.0f;
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int idx = u * 64 + lane;
+            if (idx < k4) {
+                v[u] = src[idx];
+                mx = absmax4(v[u], mx);
+            }
+        }
+        for (int idx = V * 64 + lane; idx < k4; idx += 64) mx = absmax4(src[idx], mx);
+        const float c = wave_max(mx);
+        Quantizer qz;
+        qz.set(c, 255.0f);
+        if (lane == 0) hx[row] = qz.half_step();
+        uint32_t *dst = reinterpret_cast<uint32_t *>(Xq + (size_t)row * K);
+        uint32_t sum = 0;
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const int idx = u * 64 + lane;
+            if (idx < k4) {
+                const uint32_t q = qz.code4(v[u]);
+                sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
+                dst[idx] = q ^ 0x80808080u;  // u - 128 as int8
+            }
+        }
+        for (int idx = V * 64 + lane; idx < k4; idx += 64) {
+            const uint32_t q = qz.code4(src[idx]);
+            sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
+            dst[idx] = q ^ 0x80808080u;
+        }
+        const int total = wave_sum((int)sum);
+        if (lane == 0) rs_x[row] = total - 128 * K;
+    }
+}
+
 // ---- test hook: slots -> row-major codes -----------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(256) void unpack_codes_kernel(const uint8_t *__restrict__ packed, int N, int K,
@@ -554,6 +602,19 @@ extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(quantize_act_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), X, (int)T,
                        (int)K, clip, Xq, rs_x);
+    return launch_status();
+}
+
+extern "C" qb_status qb_quantize_act_dyn(const float *X, int64_t T, int64_t K, int8_t *Xq, int32_t *rs_x, float *hx_rows,
+                                         void *stream)
+{
+    if (!X || !Xq || !rs_x || !hx_rows) return QB_ERR_NULL;
+    if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
+    unsigned blocks = (unsigned)((T + 3) / 4);
+    if (blocks > 2048) blocks = 2048;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (K <= 1024) hipLaunchKernelGGL(quantize_act_dyn_kernel<4>, dim3(blocks), dim3(256), 0, st, X, (int)T, (int)K, Xq, rs_x, hx_rows);
+    else hipLaunchKernelGGL(quantize_act_dyn_kernel<16>, dim3(blocks), dim3(256), 0, st, X, (int)T, (int)K, Xq, rs_x, hx_rows);
     return launch_status();
 }
 

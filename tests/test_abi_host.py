@@ -104,6 +104,12 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_embedding_quantize(P, 100, 1024, 100, P, P, P, NULL) == 3   # 1024 % 100
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, 0, P, NULL) == 0  # empty lookup
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, -1, P, NULL) == 3
+    # quantize_act_dyn(X,T,K,Xq,rs_x,hx,stream), qlinear_fwd_dyn(Xq,rs_x,hx,packed,h,rs_w,bits,groups,T,N,K,bias,Y,A4,stream)
+    assert lib.qb_quantize_act_dyn(P, 16, 64, P, P, NULL, NULL) == 1
+    assert lib.qb_quantize_act_dyn(P, 16, 65, P, P, P, NULL) == 3
+    assert lib.qb_qlinear_fwd_dyn(P, P, NULL, P, P, P, 4, 128, 16, 768, 768, NULL, P, NULL, NULL) == 1
+    assert lib.qb_qlinear_fwd_dyn(P, P, P, P, P, P, 6, 128, 16, 768, 768, NULL, P, NULL, NULL) == 2
+    assert lib.qb_qlinear_fwd_dyn(P, P, P, P, P, P, 4, 128, 16, 770, 768, NULL, P, NULL, NULL) == 3
     # embedding_quantize_bits(E,V,d,bits,groups,codes,h,m,stream), embedding_gather_bits(codes,h,V,d,bits,groups,ids,n,out,stream)
     assert lib.qb_embedding_quantize_bits(P, 100, 1024, 3, 128, P, P, P, NULL) == 2
     assert lib.qb_embedding_quantize_bits(P, 100, 1024, 4, 128, NULL, P, P, NULL) == 1

@@ -342,6 +342,55 @@ def test_forward_q8_config2_full_size(qb, bits, lin):
     assert (rs_y == Yq.astype(np.int64).sum(axis=1)).all()
 
 
+# ---- dynamic (per-token) activation range ---------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(1024, 768), (4096, 3072), (1, 64), (1023, 768), (7, 1024), (130, 4096), (33, 8192)])
+def test_quantize_act_dynamic(qb, shape):
+    T, K = shape
+    say("act quant dynamic", shape)
+    X = wl.activation(T, K, seed=T + K + 1)
+    X[T // 2] *= 37.0
+    if T > 4:
+        X[3] = 0.0
+    Xq, rs_x, hx = qb.qb_quantize_act_dyn(X.to(DEV))
+    torch.cuda.synchronize()
+    oq, ors, ohx = oracle.quantize_act_dyn(X.numpy())
+    assert (Xq.cpu().numpy() == oq).all()
+    assert (rs_x.cpu().numpy() == ors).all()
+    assert (hx.cpu().numpy().view(np.uint32) == ohx.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(300, 384, 256, 128), (1000, 256, 192, 64), (517, 768, 768, 128), (70, 200, 128, 8),
+                                   (2048, 1024, 128, 128), (2304, 1536, 128, 128), (4096, 768, 128, 128),
+                                   (4096, 768, 192, 128)])
+def test_forward_dynamic_scales(qb, bits, shape):
+    """Per-token scales through every kernel that takes them (32x64 register-staged tiles, the 128x128 one for K not a
+    multiple of 128, both role-split layouts), ragged T and N, with and without bias."""
+    T, N, K, G = shape
+    say("fwd dynamic", shape, "bits", bits)
+    W = wl.weight_uniform(N, K, seed=17 * N + K + bits, lo=-0.1, hi=0.1)
+    X = wl.activation(T, K, seed=T + K + bits + 9)
+    X[T // 3] *= 11.0
+    bias = (0.3 * wl.activation(1, N, seed=9)[0]).contiguous()
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, G)
+    Xq, rs_x, hx = qb.qb_quantize_act_dyn(X.to(DEV))
+    oc, oh, _, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    oq, _, ohx = oracle.quantize_act_dyn(X.numpy())
+    for b in (None, bias):
+        Y, A4 = qb.qb_qlinear_fwd_dyn(Xq, rs_x, hx, packed, h, rs_w, bits, G, N, bias=None if b is None else b.to(DEV),
+                                      want_a4=True)
+        torch.cuda.synchronize()
+        Yo, A4o = oracle.qlinear_fwd_dyn(oq, ohx, oc, oh, bits, bias=None if b is None else b.numpy(), openmp=True)
+        assert (A4.cpu().numpy() == A4o).all()
+        if b is None:
+            assert_rel(Y.cpu().numpy(), Yo)
+        else:
+            assert np.abs(Y.cpu().numpy() - Yo).max() <= 1e-6 * max(np.abs(Yo).max(), np.abs(b.numpy()).max())
+        Y2 = qb.qb_qlinear_fwd_dyn(Xq, rs_x, hx, packed, h, rs_w, bits, G, N, bias=None if b is None else b.to(DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, Y)   # the call without the debug output
+
+
 def rel_fro(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
 
