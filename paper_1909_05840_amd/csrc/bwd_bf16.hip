@@ -31,12 +31,12 @@ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 // packed slots -> WT[j][n] = bf16(h_g * (2u - L)); one thread per (n, 32-code run); n < Np
 template <int BITS>
-__global__ __launch_bounds__(256) void dequant_transpose_kernel(const uint8_t *__restrict__ packed,
-                                                                const float *__restrict__ h, int N, int Np, int K,
-                                                                int rows_per_group, uint16_t *__restrict__ WT)
+__device__ __forceinline__ void dequant_transpose_body(int bx, const uint8_t *__restrict__ packed,
+                                                       const float *__restrict__ h, int N, int Np, int K,
+                                                       int rows_per_group, uint16_t *__restrict__ WT)
 {
     const int runs = K >> 5;
-    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t id = (int64_t)bx * 256 + threadIdx.x;
     if (id >= (int64_t)Np * runs) return;
     const int rc = (int)(id / Np), n = (int)(id % Np);  // consecutive threads: consecutive n
     uint16_t *dst = WT + (size_t)(rc * 32) * Np + n;
@@ -65,11 +65,10 @@ __global__ __launch_bounds__(256) void dequant_transpose_kernel(const uint8_t *_
 // loads when C allows it, and every thread writes 8 consecutive r of one output row with one
 // 16-byte store.
 template <int MODE>
-__global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__ in, int R, int C, int ldo,
-                                                        uint16_t *__restrict__ out)
+__device__ __forceinline__ void transpose_body(int bx, int by, uint16_t (*tile)[66], const void *__restrict__ in, int R,
+                                               int C, int ldo, uint16_t *__restrict__ out)
 {
-    __shared__ uint16_t tile[64][66];
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int r0 = bx * 64, c0 = by * 64;
     const int tid = threadIdx.x;
     const bool vec = (C % 8 == 0);  // uniform: rows are then 16-byte (MODE 0) / 8-byte (MODE 1) aligned
 #pragma unroll
@@ -123,6 +122,34 @@ __global__ __launch_bounds__(256) void transpose_kernel(const void *__restrict__
             *reinterpret_cast<uint4 *>(out + (size_t)(c0 + c) * ldo + r0 + rr) = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
+}
+
+// The operands of both backward GEMMs staged by one launch: blocks [0, nb_w) de-quantize and transpose the weights
+// (for dX), the next nb_y blocks transpose dY and the last nb_x blocks transpose-and-convert the activation codes
+// (for dW).  A section with zero blocks is skipped.
+struct StageArgs {
+    const uint8_t *packed; const float *h; int N, Np, K, rows_per_group; uint16_t *WT; int nb_w;
+    const uint16_t *dY; int T, Tp; uint16_t *dYT; int nb_y;
+    const int8_t *Xq; uint16_t *XT; int nb_x;
+};
+
+template <int BITS>
+__global__ __launch_bounds__(256) void stage_operands_kernel(const StageArgs a)
+{
+    __shared__ uint16_t tile[64][66];
+    int b = blockIdx.x;
+    if (b < a.nb_w) {
+        dequant_transpose_body<BITS>(b, a.packed, a.h, a.N, a.Np, a.K, a.rows_per_group, a.WT);
+        return;
+    }
+    b -= a.nb_w;
+    const int tb = a.Tp / 64;  // tiles along T
+    if (b < a.nb_y) {
+        transpose_body<0>(b % tb, b / tb, tile, a.dY, a.T, a.N, a.Tp, a.dYT);
+        return;
+    }
+    b -= a.nb_y;
+    transpose_body<1>(b % tb, b / tb, tile, a.Xq, a.T, a.K, a.Tp, a.XT);
 }
 
 // dYp[t][n] = dY[t][n] for n < N, 0 for N <= n < Np
@@ -400,16 +427,24 @@ extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, fl
     const int rpg = (int)(N / groups);
     const int Np = (int)p.Np, Tp = (int)p.Tp;
 
-    if (dX) {
-        uint16_t *WT = reinterpret_cast<uint16_t *>(ws + p.off_wt);
-        const uint8_t *pk = static_cast<const uint8_t *>(packed);
-        const unsigned blocks = (unsigned)(((int64_t)Np * (K / 32) + 255) / 256);
+    uint16_t *WT = reinterpret_cast<uint16_t *>(ws + p.off_wt);
+    uint16_t *dYT = reinterpret_cast<uint16_t *>(ws + p.off_dyt);
+    uint16_t *XT = reinterpret_cast<uint16_t *>(ws + p.off_xt);
+    {
+        StageArgs a;
+        a.packed = static_cast<const uint8_t *>(packed); a.h = h; a.N = (int)N; a.Np = Np; a.K = (int)K; a.rows_per_group = rpg;
+        a.WT = WT; a.nb_w = dX ? (int)(((int64_t)Np * (K / 32) + 255) / 256) : 0;
+        a.dY = dY; a.T = (int)T; a.Tp = Tp; a.dYT = dYT; a.nb_y = dW ? (Tp / 64) * (int)((N + 63) / 64) : 0;
+        a.Xq = Xq; a.XT = XT; a.nb_x = dW ? (Tp / 64) * (int)((K + 63) / 64) : 0;
+        const dim3 grid((unsigned)(a.nb_w + a.nb_y + a.nb_x));
         switch (bits) {
-            case 2: hipLaunchKernelGGL(dequant_transpose_kernel<2>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
-            case 3: hipLaunchKernelGGL(dequant_transpose_kernel<3>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
-            case 4: hipLaunchKernelGGL(dequant_transpose_kernel<4>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
-            default: hipLaunchKernelGGL(dequant_transpose_kernel<8>, dim3(blocks), dim3(256), 0, st, pk, h, (int)N, Np, (int)K, rpg, WT); break;
+            case 2: hipLaunchKernelGGL(stage_operands_kernel<2>, grid, dim3(256), 0, st, a); break;
+            case 3: hipLaunchKernelGGL(stage_operands_kernel<3>, grid, dim3(256), 0, st, a); break;
+            case 4: hipLaunchKernelGGL(stage_operands_kernel<4>, grid, dim3(256), 0, st, a); break;
+            default: hipLaunchKernelGGL(stage_operands_kernel<8>, grid, dim3(256), 0, st, a); break;
         }
+    }
+    if (dX) {
         const uint16_t *Aop = dY;
         if (N % 64) {
             uint16_t *dYp = reinterpret_cast<uint16_t *>(ws + p.off_dyp);
@@ -419,12 +454,6 @@ extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, fl
         launch_gemm<0>(Aop, WT, (int)T, (int)K, Np, Np, Np, 1, Np, 1.0f, dX, st);
     }
     if (dW) {
-        uint16_t *dYT = reinterpret_cast<uint16_t *>(ws + p.off_dyt);
-        uint16_t *XT = reinterpret_cast<uint16_t *>(ws + p.off_xt);
-        hipLaunchKernelGGL(transpose_kernel<0>, dim3((unsigned)(Tp / 64), (unsigned)((N + 63) / 64)), dim3(256), 0, st,
-                           static_cast<const void *>(dY), (int)T, (int)N, Tp, dYT);
-        hipLaunchKernelGGL(transpose_kernel<1>, dim3((unsigned)(Tp / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, st,
-                           static_cast<const void *>(Xq), (int)T, (int)K, Tp, XT);
         const float hx = clip / 255.0f;
         if (p.splits > 1) {
             float *part = reinterpret_cast<float *>(ws + p.off_part);
