@@ -179,6 +179,61 @@ def test_forward_full_compare(qb, bits, shape):
     assert (Y[A4o == 0] == 0).all()
 
 
+@pytest.mark.parametrize("bits", BITS)
+def test_forward_maximum_K_and_extreme_codes(qb, bits):
+    """The longest contraction the ABI accepts (K = 32768) with every operand at an end of its range: |A4| reaches
+    255 * L * K (2.13e9 at 8 bits, just inside int32, where the kernel's intermediate 4*acc touches 2^31)."""
+    T, N, K, G = 96, 64, 32768, 32
+    say("fwd max K", (T, N, K), "bits", bits)
+    W = torch.full((N, K), 0.1)
+    W[1::2] = -0.1                      # groups of two rows: codes L and 0
+    W[5, ::3] = 0.02
+    X = torch.full((T, K), 6.0)
+    X[1::3] = -6.0                      # x' = 127 and -128
+    X[2::3] = wl.activation(T, K, seed=5)[2::3]
+    Y, A4, oq, oc, oh = run_fwd(qb, W, X, bits, G)
+    Yo, A4o, _ = oracle.qlinear_fwd(oq, CLIP, oc, oh, bits, openmp=True)
+    assert int(np.abs(A4o.astype(np.int64)).max()) == 255 * (2 ** bits - 1) * K   # 2.13e9 at 8 bits
+    assert (A4 == A4o).all()
+    assert_rel(Y, Yo)
+
+
+@pytest.mark.parametrize("bits", (3, 8))
+def test_forward_maximum_K_role_split_kernels(qb, bits):
+    """The same extremes through the 128x96 role-split kernel (4096 x 768 outputs): sampled positions against the
+    oracle, and every output whose token row and neuron row are constant against the closed form
+    A4 = K * (2x'+1) * (2c'+1)."""
+    T, N, K, G = 4096, 768, 32768, 128
+    say("fwd max K role-split", (T, N, K), "bits", bits)
+    L = 2 ** bits - 1
+    W = torch.full((N, K), 0.1)
+    W[1::2] = -0.1
+    W[4::6, ::5] = 0.03                 # some rows with mixed codes
+    X = torch.full((T, K), 6.0)
+    X[1::3] = -6.0
+    X[2::3, ::2] = 0.7
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    Y, A4 = qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, bits, G, N, want_a4=True)
+    torch.cuda.synchronize()
+    A4 = A4.cpu().numpy()
+    oc, oh, _, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    oq, _ = oracle.quantize_act(X.numpy(), CLIP)
+    assert (qb.qb_unpack_codes(packed, N, K, bits).cpu().numpy() == oc).all() and (Xq.cpu().numpy() == oq).all()
+    r = np.random.default_rng(bits)
+    ts, ns = r.integers(0, T, 600), r.integers(0, N, 600)
+    Ys, A4s = oracle.qlinear_fwd_sampled(oq, CLIP, oc, oh, bits, ts, ns)
+    assert (A4[ts, ns] == A4s).all()
+    assert_rel(Y.cpu().numpy()[ts, ns], Ys)
+    xrow = np.where((oq == oq[:, :1]).all(axis=1))[0]          # constant token rows
+    wrow = np.where((oc == oc[:, :1]).all(axis=1))[0]          # constant neuron rows
+    assert len(xrow) > T // 2 and len(wrow) > N // 2
+    fx = 2 * oq[xrow, 0].astype(np.int64) + 1
+    fw = 2 * oc[wrow, 0].astype(np.int64) - L
+    assert (A4[np.ix_(xrow, wrow)] == K * fx[:, None] * fw[None, :]).all()
+    assert int(np.abs(A4.astype(np.int64)).max()) == 255 * L * K
+
+
 def test_forward_config1_and_bias(qb):
     """Configuration 1: one BERT-base Q projection, 4-bit, 128 groups, T = 1024, seed 0."""
     W = wl.weight(768, 768, seed=wl.config_seed(0, 0))
