@@ -239,6 +239,15 @@ __device__ __forceinline__ void copy12_to_lds(const void *g, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
+// the same with a wavefront-uniform base address (in SGPRs) and a 32-bit byte offset per lane
+__device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(off), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void copy12_to_lds(const void *base, uint32_t off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %1, %0" ::"s"(base), "v"(off), "s"(lds_addr) : "memory", "m0");
+}
 
 template <int BITS> struct SlotRead;  // one lane's slot (32 codes) out of LDS
 template <> struct SlotRead<2> {
@@ -776,37 +785,41 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
             // chunk holds logical chunk (l%8) ^ ((row/2)%8): the swizzle that makes 16 consecutive
             // rows of one logical chunk land in 16 different 16-byte bank groups
             const int last_row = T - 1 - tile_m * BM;  // rows past the end re-read the last one; outputs masked
-            const int8_t *a_src[A_PER];
-            uint32_t a_dst[A_PER];
+            // addresses: a wavefront-uniform base per tile and step, a 32-bit byte offset per lane and copy
+            const int8_t *a_base = Xq + (size_t)tile_m * BM * K;
+            uint32_t a_off[A_PER], a_dst[A_PER];
 #pragma unroll
             for (int i = 0; i < A_PER; ++i) {
                 const int blk = (i * NPROD + p) % A_TOTAL;  // surplus copies repeat one: same bytes, same place
                 int row = blk * 8 + (lane >> 3);
                 const int key = (row >> 1) & 7;
                 row = row < last_row ? row : last_row;
-                a_src[i] = Xq + ((size_t)tile_m * BM + row) * K + (((lane & 7) ^ key) * 16);
+                a_off[i] = (uint32_t)row * (uint32_t)K + (((lane & 7) ^ key) * 16);
                 a_dst[i] = blk * 1024;
             }
-            const uint8_t *b_src[B_PER];
-            uint32_t b_dst[B_PER];
+            const int cb0 = tile_n * (BN / 32);
+            const uint8_t *b_base = packed + (size_t)cb0 * kunits * 64 * SLOT;
+            uint32_t b_off[B_PER], b_dst[B_PER];
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
                 const int j = (i * NPROD + p) % B_TOTAL;
                 const int pair = j / PARTS, part = j - pair * PARTS;
-                int cb = tile_n * (BN / 32) + pair;
+                int cb = cb0 + pair;
                 cb = cb < ncb ? cb : ncb - 1;  // blocks past the end re-read the last one; outputs masked
-                b_src[i] = packed + (size_t)cb * kunits * 64 * SLOT + part * 64 * CH + lane * CH;
+                b_off[i] = (uint32_t)(cb - cb0) * (uint32_t)(kunits * 64 * SLOT) + part * 64 * CH + lane * CH;
                 b_dst[i] = A_BYTES + pair * LPAIR + part * 1024;
             }
             auto fetch = [&](int step, int stage) {
                 const uint32_t st_ = lds_base + stage * STAGE_BYTES;
+                const uint8_t *bs = b_base + (size_t)step * PAIR;
+                const int8_t *as = a_base + (size_t)step * BK;
 #pragma unroll
                 for (int i = 0; i < B_PER; ++i) {
-                    if constexpr (BITS == 3) copy12_to_lds(b_src[i] + (size_t)step * PAIR, st_ + b_dst[i]);
-                    else copy16_to_lds(b_src[i] + (size_t)step * PAIR, st_ + b_dst[i]);
+                    if constexpr (BITS == 3) copy12_to_lds(bs, b_off[i], st_ + b_dst[i]);
+                    else copy16_to_lds(bs, b_off[i], st_ + b_dst[i]);
                 }
 #pragma unroll
-                for (int i = 0; i < A_PER; ++i) copy16_to_lds(a_src[i] + (size_t)step * BK, st_ + a_dst[i]);
+                for (int i = 0; i < A_PER; ++i) copy16_to_lds(as, a_off[i], st_ + a_dst[i]);
             };
             if (p == 0) {  // the tile's epilogue parameters: older than step 0's copies, so they land before them
                 const uint32_t pbase = lds_base + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES;
