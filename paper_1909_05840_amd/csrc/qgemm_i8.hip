@@ -362,15 +362,18 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     // ones repeat an earlier copy, writing the same bytes to the same place.
     const int kunits = K >> 6;
     const int ncb = (N + 31) >> 5;
-    const uint8_t *b_gsrc[B_DMA];
+    // (addresses: a wavefront-uniform base per tile and step, a 32-bit byte offset per lane and copy)
+    const int cb0 = tile_n * (BN / 32);
+    const uint8_t *b_base = packed + (size_t)cb0 * kunits * 64 * SLOT;
+    uint32_t b_off[B_DMA];
     int b_ldst[B_DMA];
 #pragma unroll
     for (int i = 0; i < B_DMA; ++i) {
         const int j = (i * NW + wave) % B_TOTAL;
         const int pair = j / PARTS, part = j - pair * PARTS;
-        int cb = tile_n * (BN / 32) + pair;
+        int cb = cb0 + pair;
         cb = cb < ncb ? cb : ncb - 1;  // blocks past the end re-read the last one; outputs masked
-        b_gsrc[i] = packed + (size_t)cb * kunits * 64 * SLOT + part * 64 * CH + lane * CH;
+        b_off[i] = (uint32_t)(cb - cb0) * (uint32_t)(kunits * 64 * SLOT) + part * 64 * CH + lane * CH;
         b_ldst[i] = pair * LPAIR + part * 1024;
     }
     // ---- fragment reads.  tokens: row = wm*TM*32 + tm*32 + l32, logical chunk = kk*4 + hf*2 + sub
@@ -395,11 +398,11 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     if constexpr (!(SKIP & 1)) {                                                                          \
         const uint32_t st_ = lds_base + (stage) * STAGE_BYTES;                                            \
         _Pragma("unroll") for (int i = 0; i < B_DMA; ++i) {                                               \
-            if constexpr (BITS == 3) copy12_to_lds(b_gsrc[i] + (size_t)(step) * PAIR, st_ + A_BYTES + b_ldst[i]); \
-            else copy16_to_lds(b_gsrc[i] + (size_t)(step) * PAIR, st_ + A_BYTES + b_ldst[i]);             \
+            if constexpr (BITS == 3) copy12_to_lds(b_base + (size_t)(step) * PAIR, b_off[i], st_ + A_BYTES + b_ldst[i]); \
+            else copy16_to_lds(b_base + (size_t)(step) * PAIR, b_off[i], st_ + A_BYTES + b_ldst[i]);      \
         }                                                                                                 \
         _Pragma("unroll") for (int i = 0; i < A_DMA; ++i)                                                 \
-            copy16_to_lds(a_base + a_off[i] + (size_t)(step) * BK, st_ + (i * NW + wave) * 1024);         \
+            copy16_to_lds(a_base + (size_t)(step) * BK, a_off[i], st_ + (i * NW + wave) * 1024);          \
     }
 #define QB_MMA(stage)                                                                                     \
     {                                                                                                     \
