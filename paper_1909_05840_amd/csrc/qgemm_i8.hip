@@ -8,13 +8,20 @@
 // u - 128 for 8 bits (e = +1); either way A4 equals sum_j (2x'+1)(2u-L), the integer the
 // paper's "integer matmul followed by de-quantization" has to produce.
 //
-// Data movement.  The token tile of X' is copied global -> LDS by the load unit itself
-// (global_load_lds_dwordx4, no registers involved), double buffered, into a dense 128-byte-row
-// layout whose 16-byte chunks are XOR-swizzled by the row number so that the MFMA fragment
-// reads are free of bank conflicts.  The packed weights never touch LDS: the packed
-// layout stores, per 32-neuron block and 64-feature unit, one slot per lane, so a wavefront
-// fetches its B operand with one coalesced load and expands the k-bit codes to int8 with a few
-// byte-parallel shifts and masks in registers, right in front of the MFMA that consumes them.
+// Three kernels, chosen by shape (launch_bits):
+//   qgemm_i8_kernel     register-staged: the token tile goes global -> registers -> LDS, the packed weights never
+//                       touch LDS (the packed layout stores, per 32-neuron block and 64-feature unit, one slot per
+//                       lane, so a wavefront fetches its B operand with one coalesced load).  Small tiles for
+//                       problems of few tiles, and any K that is a multiple of 64.
+//   qgemm_i8_dma_kernel both operands copied global -> LDS by the load unit itself (global_load_lds_dwordx4, no
+//                       registers involved) through a ring of stages; every wavefront copies and multiplies; two
+//                       workgroups per CU.
+//   qgemm_i8_ws_kernel  the same data path with the work split by role (copy wavefronts / MFMA wavefronts), one
+//                       persistent workgroup per CU, epilogue parameters staged in LDS; optionally with the copy
+//                       wavefronts on a SIMD of their own (128x96 tiles), an 8-bit output, per-token scales.
+// In all of them the token tile sits in LDS as dense 128-byte rows whose 16-byte chunks are XOR-swizzled by the
+// row number, so that the MFMA fragment reads are free of bank conflicts, and the k-bit codes are expanded to
+// int8 with a few byte-parallel shifts and masks in registers, right in front of the MFMA that consumes them.
 // Workgroups are renumbered so that the ones sharing a token panel run on the same XCD (same L2).
 #include "qb_common.hpp"
 

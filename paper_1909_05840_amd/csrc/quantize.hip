@@ -1,5 +1,5 @@
-// Quantize / pack kernels for gfx950: group-wise k-bit weights, 8-bit activations, the
-// unpack test hook and the 8-bit column-grouped embedding table.
+// Quantize / pack kernels for gfx950: group-wise k-bit weights, 8-bit activations (static clip or a
+// max-abs range per token), the unpack test hook and the 4/8-bit column-grouped embedding table.
 //
 // All of them are bound by HBM traffic.  The weight kernel therefore reads each fp32 weight
 // from memory exactly once: one workgroup owns one group (a contiguous block of N/G rows),
