@@ -61,6 +61,20 @@ def quantize_groupwise(W, bits, groups):
     return codes, h, m, rs
 
 
+def quantize_groupwise_clip(W, bits, m_in):
+    """Group ranges [-m_in[g], +m_in[g]] given by the caller. Returns codes[N,K] u8, h[G] f32, rs_w[N] i32."""
+    W = _c(W, np.float32)
+    m_in = _c(m_in, np.float32)
+    N, K = W.shape
+    G = m_in.shape[0]
+    codes = np.empty((N, K), np.uint8)
+    h = np.empty(G, np.float32)
+    rs = np.empty(N, np.int32)
+    _check(_lib().qbo_quantize_groupwise_clip(_ptr(W), _I64(N), _I64(K), int(bits), _I64(G), _ptr(m_in), _ptr(codes),
+                                              _ptr(h), _ptr(rs)), "quantize_groupwise_clip")
+    return codes, h, rs
+
+
 def dequantize_groupwise(codes, h, bits):
     codes = _c(codes, np.uint8)
     h = _c(h, np.float32)

@@ -120,6 +120,43 @@ int qbo_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int64
     return QBO_OK;
 }
 
+/* The same with the range of every group given by the caller instead of taken as the max-abs:
+ * [-m_g, +m_g] may be a clipped sub-interval of the weights' range (App.: the range is
+ * [q0, q_{2^k-1}], "X' = Clamp(X, q0, q_{2^k-1})"), e.g. a percentile; weights outside are clamped and
+ * get the end codes 0 or L.  m_in[G] >= 0 finite. */
+int qbo_quantize_groupwise_clip(const float *W, int64_t N, int64_t K, int bits, int64_t G, const float *m_in,
+                                uint8_t *codes, float *h, int32_t *rs_w)
+{
+    int64_t g, rows;
+    int L, half;
+    if (!W || !m_in || !codes || !h || !rs_w || !bits_ok(bits)) return QBO_ERR_ARG;
+    if (N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    L = (1 << bits) - 1;
+    half = 1 << (bits - 1);
+    rows = N / G;
+    for (g = 0; g < G; ++g) {
+        float mg = m_in[g], hg, delta;
+        int64_t r, j;
+        if (!(mg >= 0.0f) || !isfinite(mg)) return QBO_ERR_ARG;
+        hg = (mg == 0.0f) ? 0.0f : mg / (float)L;
+        delta = 2.0f * hg;
+        h[g] = hg;
+        for (r = g * rows; r < (g + 1) * rows; ++r) {
+            int32_t acc = 0;
+            for (j = 0; j < K; ++j) {
+                float w = W[r * K + j];
+                int u;
+                if (isnan(w)) return QBO_ERR_NONFINITE;
+                u = quantize_one(w, mg, delta, L);
+                codes[r * K + j] = (uint8_t)u;
+                acc += u - half;
+            }
+            rs_w[r] = acc;
+        }
+    }
+    return QBO_OK;
+}
+
 /* Q(w) = Delta*u + q0, written as h*(2u - L): the same real number, one rounding. */
 int qbo_dequantize_groupwise(const uint8_t *codes, const float *h, int64_t N, int64_t K,
                              int bits, int64_t G, double *Wq)

@@ -401,6 +401,42 @@ def test_q8_output_gelu_matches_an_independent_erf():
     assert big.any() and np.abs(lev[big] - np.minimum(g[big], 1.0)).max() <= 1.0 / 255 * 1.001
 
 
+# ---- clipped weight ranges ------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_clipped_group_range(bits):
+    """A given range equal to the max-abs reproduces the plain quantizer; a smaller one clamps: weights outside get
+    the end codes, weights inside get the nearest level of the exact quotient; the end codes de-quantize to -+m."""
+    N, K, G = 12, 64, 4
+    L = 2 ** bits - 1
+    W = (rng(80 + bits).standard_normal((N, K)) * 0.04).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    c2, h2, rs2 = oracle.quantize_groupwise_clip(W, bits, m)
+    assert (c2 == codes).all() and (h2 == h).all() and (rs2 == rs_w).all()
+    mc = (0.5 * m).astype(np.float32)
+    c3, h3, rs3 = oracle.quantize_groupwise_clip(W, bits, mc)
+    assert (rs3 == (c3.astype(np.int64) - 2 ** (bits - 1)).sum(axis=1)).all()
+    rows = N // G
+    clipped = 0
+    for n in range(N):
+        mg, hg = Fraction(float(mc[n // rows])), Fraction(float(h3[n // rows]))
+        assert hg == Fraction(float(np.float32(mc[n // rows]) / np.float32(L)))
+        for j in range(K):
+            w = Fraction(float(W[n, j]))
+            u = int(c3[n, j])
+            if w >= mg:
+                assert u == L
+                clipped += 1
+            elif w <= -mg:
+                assert u == 0
+                clipped += 1
+            else:
+                assert abs(hg * (2 * u - L) - w) <= hg * (1 + Fraction(1, 10 ** 5))
+    assert clipped > 0
+    # m = 0: everything is code 0, h = 0
+    c4, h4, _ = oracle.quantize_groupwise_clip(W, bits, np.zeros(G, np.float32))
+    assert (c4 == 0).all() and (h4 == 0).all()
+
+
 # ---- dynamic (per-token max-abs) activation range ---------------------------------------------------------------
 def test_dynamic_activation_range_equals_static_quantizer_row_by_row():
     """Each row is the static quantizer with clip = that row's max-abs; the row's extreme hits code 0 or 255; the
