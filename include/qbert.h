@@ -92,6 +92,19 @@ typedef struct {
 qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
 
 /*
+ * qb_quantize_groupwise with the range of every group given by the caller instead of taken as
+ * the max-abs (App.: the range [q0, q_{2^k-1}] may be a sub-interval of the tensor's range,
+ * X' = Clamp(X, q0, q_{2^k-1})): [-m_in[g], +m_in[g]], e.g. a percentile; weights outside are
+ * clamped and get the end codes.  m_in = the max-abs gives the codes of qb_quantize_groupwise.
+ *   m_in  in  [G] fp32, >= 0 and finite (not checked on the device)
+ * The packed result feeds qb_qlinear_fwd and qb_qlinear_bwd_ste unchanged (the backward passes the
+ * gradient through the clamp as well: plain straight-through).
+ */
+qb_status qb_quantize_groupwise_clip(const float *W, int64_t N, int64_t K, int bits, int groups,
+                                     const float *m_in, void *packed, float *h, int32_t *rs_w,
+                                     void *stream);
+
+/*
  * 8-bit activation quantization (Table 1 caption: all models use 8-bit activations; same
  * appendix formulas with k = 8 and the caller-given range [-clip, +clip]).
  *   X     in   [T,K] fp32

@@ -21,7 +21,7 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
-           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn")
+           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip")
 
 
 class _QuantJob(ctypes.Structure):
@@ -70,6 +70,8 @@ def load_library():
     lib.qb_embedding_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
     lib.qb_embedding_gather.restype = ci
     lib.qb_embedding_gather.argtypes = [vp, vp, i64, i64, ci, vp, i64, vp, vp]
+    lib.qb_quantize_groupwise_clip.restype = ci
+    lib.qb_quantize_groupwise_clip.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
     lib.qb_quantize_act_dyn.restype = ci
     lib.qb_quantize_act_dyn.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_dyn.restype = ci
@@ -306,3 +308,20 @@ def qb_qlinear_fwd_dyn(Xq, rs_x, hx_rows, packed, h, rs_w, bits, groups, N, bias
     _check(lib.qb_qlinear_fwd_dyn(_p(Xq), _p(rs_x), _p(hx_rows), _p(packed), _p(h), _p(rs_w), bits, groups,
                                   T, N, K, _p(bias), _p(Y), _p(A4), _stream()))
     return (Y, A4) if want_a4 else Y
+
+
+def qb_quantize_groupwise_clip(W, bits, m_in, packed=None, h=None, rs_w=None):
+    """Group ranges [-m_in[g], +m_in[g]] given by the caller (device fp32 [G]). Returns (packed, h, rs_w)."""
+    lib = load_library()
+    _dev(W, torch.float32, "W")
+    _dev(m_in, torch.float32, "m_in")
+    N, K = W.shape
+    G = m_in.shape[0]
+    if packed is None:
+        packed = torch.empty(max(qb_packed_nbytes(N, K, bits), 1), dtype=torch.uint8, device=W.device)
+    if h is None:
+        h = torch.empty(G, dtype=torch.float32, device=W.device)
+    if rs_w is None:
+        rs_w = torch.empty(N, dtype=torch.int32, device=W.device)
+    _check(lib.qb_quantize_groupwise_clip(_p(W), N, K, bits, G, _p(m_in), _p(packed), _p(h), _p(rs_w), _stream()))
+    return packed, h, rs_w

@@ -79,6 +79,15 @@ __device__ __forceinline__ void quantize_panel_body(
         h[g] = qz.half_step();
         if (FUSED) m[g] = mg;
     }
+    if (!FUSED) {  // the range was given: it may be smaller than the group's max-abs (clipped range)
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            v[i].x = __builtin_amdgcn_fmed3f(v[i].x, -mg, mg);
+            v[i].y = __builtin_amdgcn_fmed3f(v[i].y, -mg, mg);
+            v[i].z = __builtin_amdgcn_fmed3f(v[i].z, -mg, mg);
+            v[i].w = __builtin_amdgcn_fmed3f(v[i].w, -mg, mg);
+        }
+    }
 
     // codes, four per dword, into the LDS image of the panel
 #pragma unroll
@@ -507,12 +516,45 @@ qb_status quantize_two_pass(const float *W, int64_t N, int64_t K, int groups, ui
     return launch_status();
 }
 
+// ranges given by the caller: the second pass alone
+template <int BITS>
+qb_status quantize_given_range(const float *W, int64_t N, int64_t K, int groups, const float *m_in, uint8_t *packed,
+                               float *h, int32_t *rs_w, hipStream_t st)
+{
+    const int rpg = (int)(N / groups);
+    int prow = 1;
+    for (int p = rpg; p >= 1; --p)
+        if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
+    float *m = const_cast<float *>(m_in);  // read only on this path
+    const int64_t pelems = (int64_t)prow * K;
+    if (pelems <= 8192) launch_panel<BITS, 256>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    else if (pelems <= 16384) launch_panel<BITS, 512>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    else launch_panel<BITS, 1024>(W, (int)K, rpg, prow, (int)(N / prow), packed, h, m, rs_w, st);
+    return launch_status();
+}
+
 }  // namespace
 }  // namespace qb
 
 using namespace qb;
 
 extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
+
+extern "C" qb_status qb_quantize_groupwise_clip(const float *W, int64_t N, int64_t K, int bits, int groups, const float *m_in,
+                                                void *packed, float *h, int32_t *rs_w, void *stream)
+{
+    if (!W || !m_in || !packed || !h || !rs_w) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *p = static_cast<uint8_t *>(packed);
+    switch (bits) {
+        case 2: return quantize_given_range<2>(W, N, K, groups, m_in, p, h, rs_w, st);
+        case 3: return quantize_given_range<3>(W, N, K, groups, m_in, p, h, rs_w, st);
+        case 4: return quantize_given_range<4>(W, N, K, groups, m_in, p, h, rs_w, st);
+        default: return quantize_given_range<8>(W, N, K, groups, m_in, p, h, rs_w, st);
+    }
+}
 
 extern "C" qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, int groups, void *packed,
                                            float *h, float *m, int32_t *rs_w, void *stream)

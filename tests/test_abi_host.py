@@ -104,6 +104,10 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_embedding_quantize(P, 100, 1024, 100, P, P, P, NULL) == 3   # 1024 % 100
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, 0, P, NULL) == 0  # empty lookup
     assert lib.qb_embedding_gather(P, P, 100, 1024, 128, P, -1, P, NULL) == 3
+    # quantize_groupwise_clip(W,N,K,bits,groups,m_in,packed,h,rs_w,stream)
+    assert lib.qb_quantize_groupwise_clip(P, 768, 768, 4, 128, NULL, P, P, P, NULL) == 1
+    assert lib.qb_quantize_groupwise_clip(P, 768, 768, 5, 128, P, P, P, P, NULL) == 2
+    assert lib.qb_quantize_groupwise_clip(P, 770, 768, 4, 128, P, P, P, P, NULL) == 3
     # quantize_act_dyn(X,T,K,Xq,rs_x,hx,stream), qlinear_fwd_dyn(Xq,rs_x,hx,packed,h,rs_w,bits,groups,T,N,K,bias,Y,A4,stream)
     assert lib.qb_quantize_act_dyn(P, 16, 64, P, P, NULL, NULL) == 1
     assert lib.qb_quantize_act_dyn(P, 16, 65, P, P, P, NULL) == 3

@@ -69,6 +69,29 @@ def test_quantize_zero_group_ties_and_extremes(qb):
         check_quantize(qb, Wt, bits, 8)
 
 
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(768, 768, 128), (2304, 768, 128), (768, 3072, 128), (96, 64, 96), (6, 64, 1), (768, 768, 1)])
+def test_quantize_given_clipped_range(qb, bits, shape):
+    """Ranges given by the caller: half of each group's max-abs (about the outer weights are clamped), then the
+    max-abs itself (must reproduce the plain call), then zero."""
+    N, K, G = shape
+    say("quantize clip", shape, "bits", bits)
+    W = wl.weight_uniform(N, K, seed=3 * N + K + bits, lo=-0.1, hi=0.1)
+    _, _, om, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    for scale in (0.5, 1.0, 0.0):
+        m_in = (om * np.float32(scale)).astype(np.float32)
+        packed, h, rs = qb.qb_quantize_groupwise_clip(W.to(DEV), bits, torch.from_numpy(m_in).to(DEV))
+        codes = qb.qb_unpack_codes(packed, N, K, bits)
+        torch.cuda.synchronize()
+        oc, oh, ors = oracle.quantize_groupwise_clip(W.numpy(), bits, m_in)
+        assert (codes.cpu().numpy() == oc).all()
+        assert (h.cpu().numpy().view(np.uint32) == oh.view(np.uint32)).all()
+        assert (rs.cpu().numpy() == ors).all()
+        if scale == 0.5:
+            L = 2 ** bits - 1
+            assert (oc == 0).any() and (oc == L).any()
+
+
 def test_quantize_batched_matches_single_calls(qb):
     """Configuration 4 style: 12 layers x 4 linears, each layer at its own bit-width, in batched launches
     (more jobs than one launch holds, mixed bits, one job with groups too large for the fused path)."""
