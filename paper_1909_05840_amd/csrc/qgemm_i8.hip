@@ -749,7 +749,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int PERP = A_PER + B_PER;             // per producer and step
     constexpr int D = NSTAGE - 1;
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
-    static_assert((D - 1) * PERP < 64, "vmcnt has six bits");
+    static_assert((D - 1) * PERP + 2 * (BM / 64) + 3 * ((BN + 63) / 64) < 64, "vmcnt has six bits");
     constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
     constexpr int PARAM_BYTES = (2 * BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias | per-token scales
     static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
@@ -831,7 +831,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #pragma unroll
                 for (int i = 0; i < A_PER; ++i) copy16_to_lds(as, a_off[i], st_ + a_dst[i]);
             };
-            if (p == 0) {  // the tile's epilogue parameters: older than step 0's copies, so they land before them
+            if (0 < nsteps) fetch(0, 0);  // the first step's copies go first: the K-loop waits for nothing else
+            if (p == 0) {  // the tile's epilogue parameters: needed after the K-loop only
                 const uint32_t pbase = lds_base + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES;
 #pragma unroll
                 for (int c = 0; c < BM / 64; ++c) {
@@ -851,11 +852,19 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
             }
             pb ^= 1;
 #pragma unroll
-            for (int u = 0; u < D; ++u)
+            for (int u = 1; u < D; ++u)
                 if (u < nsteps) fetch(u, u);
             if (OUTQ && work != (int)blockIdx.x) __builtin_amdgcn_s_barrier();  // barrier E of the previous tile
-            if (nsteps >= D) wait_vmcnt<(D - 1) * PERP>();
-            else wait_vmcnt<0>();
+            // step 0 has landed when only younger copies are outstanding: steps 1..D-1 and, in the wavefront
+            // that issued them, the parameter copies (their number depends on bias and per-token scales)
+            if (nsteps >= D) {
+                constexpr int W0 = (D - 1) * PERP, PM = BM / 64, PN = BNP / 64;
+                if (p != 0) wait_vmcnt<W0>();
+                else if (oq.hx_rows) { if (bias) wait_vmcnt<W0 + 2 * PM + 3 * PN>(); else wait_vmcnt<W0 + 2 * PM + 2 * PN>(); }
+                else { if (bias) wait_vmcnt<W0 + PM + 3 * PN>(); else wait_vmcnt<W0 + PM + 2 * PN>(); }
+            } else {
+                wait_vmcnt<0>();
+            }
             __builtin_amdgcn_s_barrier();
             int stage = D % NSTAGE;  // stage of step s + D
             for (int s = 0; s < nsteps; ++s) {
