@@ -155,6 +155,18 @@ def quantize_act_dyn(X):
     return xq, rs, hx
 
 
+def quantize_act_dyn_tensor(X):
+    """One max-abs range for the whole tensor. Returns xq[T,K] i8, rs_x[T] i32, hx f32 (a scalar: c/255)."""
+    X = _c(X, np.float32)
+    T, K = X.shape
+    xq = np.empty((T, K), np.int8)
+    rs = np.empty(T, np.int32)
+    hx = np.empty(1, np.float32)
+    _check(_lib().qbo_quantize_act_dyn_tensor(_ptr(X), _I64(T), _I64(K), _ptr(xq), _ptr(rs), _ptr(hx)),
+           "quantize_act_dyn_tensor")
+    return xq, rs, hx[0]
+
+
 def qlinear_fwd_dyn(xq, hx, codes, h, bits, bias=None, openmp=False):
     """Forward with one activation scale per token. Returns Y[T,N] f32, A4[T,N] i32."""
     xq = _c(xq, np.int8)

@@ -267,6 +267,35 @@ int qbo_quantize_act_dyn(const float *X, int64_t T, int64_t K, int8_t *xq, int32
     return QBO_OK;
 }
 
+/* The same quantizer with one range for the whole tensor taken from the data: [-c, +c], c = max |X|
+ * (the appendix allows any range [q0, q_255]).  Like a calibrated clip it is one scale per matmul, but
+ * it needs no calibration and never clips.  out: xq[T,K] = u - 128, rs_x[t], hx[0] = c/255 (0 for an
+ * all-zero tensor, whose codes are 0). */
+int qbo_quantize_act_dyn_tensor(const float *X, int64_t T, int64_t K, int8_t *xq, int32_t *rs_x, float *hx)
+{
+    int64_t t, j;
+    float c = 0.0f, h, delta;
+    if (!X || !xq || !rs_x || !hx || T <= 0 || K <= 0) return QBO_ERR_ARG;
+    for (t = 0; t < T * K; ++t) {
+        float a = fabsf(X[t]);
+        if (!isfinite(a)) return QBO_ERR_NONFINITE;
+        if (a > c) c = a;
+    }
+    h = (c == 0.0f) ? 0.0f : c / 255.0f;
+    delta = 2.0f * h;
+    hx[0] = h;
+    for (t = 0; t < T; ++t) {
+        int32_t acc = 0;
+        for (j = 0; j < K; ++j) {
+            int u = quantize_one(X[t * K + j], c, delta, 255);
+            xq[t * K + j] = (int8_t)(u - 128);
+            acc += u - 128;
+        }
+        rs_x[t] = acc;
+    }
+    return QBO_OK;
+}
+
 /* De-quantized activation: h_x*(2u - 255) = h_x*(2*xq + 1). */
 int qbo_dequantize_act(const int8_t *xq, int64_t T, int64_t K, float clip, double *Xhat)
 {

@@ -542,3 +542,45 @@ def test_argument_errors():
         oracle.quantize_groupwise(W, 4, 2)
     with pytest.raises(oracle.OracleError):
         oracle.quantize_act(np.zeros((2, 2), np.float32), -1.0)
+
+
+def test_dynamic_tensor_range_worked_example_and_special_cases():
+    """One range for the whole tensor, c = max|X| (App. A: any range [q0, q_255]).  A case worked by hand with
+    c = 31.875, h = 1/8, Delta = 1/4 (every quotient exact); the static quantizer at clip = c; the nearest-level
+    bound; a zero tensor; the forward against the fp64 product of the de-quantized operands."""
+    X = np.array([[-31.875, 0.125, 10.125, -0.125], [31.875, -0.125, 0.125, -31.625]], np.float32)
+    xq, rs, hx = oracle.quantize_act_dyn_tensor(X)
+    assert hx == np.float32(0.125)
+    assert xq.tolist() == [[-128, 0, 40, -1], [127, -1, 0, -127]]
+    assert rs.tolist() == [-89, -1]
+
+    T, K, N, G, bits = 9, 64, 8, 2, 3
+    X = rng(90).standard_normal((T, K)).astype(np.float32)
+    X[2] *= 50.0          # the tensor's maximum sits in row 2: the other rows use few of the 256 levels
+    c = float(np.abs(X).max())
+    xq, rs, hx = oracle.quantize_act_dyn_tensor(X)
+    q1, r1 = oracle.quantize_act(X, c)
+    assert (xq == q1).all() and (rs == r1).all() and hx == np.float32(c) / np.float32(255)
+    assert xq.max() == 127 or xq.min() == -128
+    lev = float(hx) * (2 * (xq.astype(np.int64) + 128) - 255)
+    assert np.abs(lev - X.astype(np.float64)).max() <= float(hx) * (1 + 1e-5)
+    others = np.delete(np.arange(T), 2)
+    assert np.unique(xq[others]).size < 40                     # coarse for the small rows ...
+    xq_t, _, hx_t = oracle.quantize_act_dyn(X)
+    assert np.unique(xq_t[others]).size > 150                  # ... unlike a range per token
+    assert (xq_t[2] == xq[2]).all() and hx_t[2] == hx
+
+    W = (rng(91).standard_normal((N, K)) * 0.04).astype(np.float32)
+    codes, h, m, rs_w = oracle.quantize_groupwise(W, bits, G)
+    Y, A4 = oracle.qlinear_fwd_dyn(xq, np.full(T, hx, np.float32), codes, h, bits)
+    Y1, A41, _ = oracle.qlinear_fwd(xq, c, codes, h, bits)
+    assert (A4 == A41).all() and (Y == Y1).all()
+    ref = (float(hx) * (2 * xq.astype(np.float64) + 1)) @ oracle.dequantize_groupwise(codes, h, bits).T
+    assert np.allclose(Y, ref, rtol=1e-6, atol=1e-30)
+
+    Z = np.zeros((3, 32), np.float32)
+    xq, rs, hx = oracle.quantize_act_dyn_tensor(Z)
+    assert hx == 0 and (xq == -128).all() and (rs == -128 * 32).all()
+    Z[1, 5] = np.inf
+    with pytest.raises(Exception):
+        oracle.quantize_act_dyn_tensor(Z)
