@@ -359,8 +359,8 @@ def q8_output_leg(torch, qb, wl, dev):
 
 
 def dynamic_range_leg(torch, qb, wl, dev):
-    """Per-token dynamic activation range: the quantizer and the forward that takes per-token scales, next to the
-    static-clip calls on the same shapes (4 bits, T = 4096)."""
+    """Dynamic activation range, per token and per tensor: the quantizers and the forward that takes per-token
+    scales, next to the static-clip calls on the same shapes (4 bits, T = 4096)."""
     res = []
     for (name, N, K) in wl.BERT_BASE_LINEARS:
         T, b = T_TOKENS, 4
@@ -372,9 +372,12 @@ def dynamic_range_leg(torch, qb, wl, dev):
         Y = torch.empty((T, N), dtype=torch.float32, device=dev)
         sa = time_launches(torch, lambda: qb.qb_quantize_act(X, CLIP, Xq, rs_x))
         sad = time_launches(torch, lambda: qb.qb_quantize_act_dyn(X, Xq, rs_x, hx))
+        c = torch.empty(1, dtype=torch.float32, device=dev)
+        sat = time_launches(torch, lambda: qb.qb_quantize_act_dyn_tensor(X, Xq, rs_x, hx, c))  # reads X twice
         sf = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
         sfd = time_launches(torch, lambda: qb.qb_qlinear_fwd_dyn(Xq, rs_x, hx, packed, h, rs_w, b, GROUPS, N, Y=Y))
         res.append({"linear": name, "act_quant_us": round(sa * 1e6, 2), "act_quant_dyn_us": round(sad * 1e6, 2),
+                    "act_quant_dyn_tensor_us": round(sat * 1e6, 2),
                     "fwd_us": round(sf * 1e6, 2), "fwd_dyn_us": round(sfd * 1e6, 2)})
         del W, X, Y, Xq
     return res

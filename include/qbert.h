@@ -168,6 +168,19 @@ qb_status qb_qlinear_fwd_dyn(const int8_t *Xq, const int32_t *rs_x, const float 
                              const float *bias, float *Y, int32_t *A4_debug, void *stream);
 
 /*
+ * Activation quantization with one range for the whole tensor, taken from the data (the appendix's
+ * quantizer takes any range [q0, q_255]): c = max |X|, otherwise as qb_quantize_act with clip = c.  One scale
+ * per matmul like a calibrated clip, but nothing is clipped and no calibration is needed.
+ *   c_out    out  [1] fp32 device, c (also the reduction's scratch: the call zero-fills it first)
+ *   hx_rows  out  [T] fp32, c / 255 in every entry (0 for an all-zero tensor, whose codes are 0), the form
+ *                 qb_qlinear_fwd_dyn takes; its Y equals qb_qlinear_fwd's with clip = c
+ * Three launches on `stream` (fill, reduce, quantize); no host synchronisation.  Errors as qb_quantize_act.
+ */
+qb_status qb_quantize_act_dyn_tensor(const float *X, int64_t T, int64_t K,
+                                     int8_t *Xq, int32_t *rs_x, float *hx_rows, float *c_out,
+                                     void *stream);
+
+/*
  * Straight-through-estimator backward (Sec. 3.1, last paragraph; App., last sentence): both
  * quantizers pass the gradient through unchanged, so
  *   dX[t,j] = sum_n dY[t,n] * Q(w)[n,j]        dW[n,j] = sum_t dY[t,n] * Q(x)[t,j]

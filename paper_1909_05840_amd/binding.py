@@ -21,7 +21,7 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
-           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip")
+           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor")
 
 
 class _QuantJob(ctypes.Structure):
@@ -74,6 +74,8 @@ def load_library():
     lib.qb_quantize_groupwise_clip.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
     lib.qb_quantize_act_dyn.restype = ci
     lib.qb_quantize_act_dyn.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    lib.qb_quantize_act_dyn_tensor.restype = ci
+    lib.qb_quantize_act_dyn_tensor.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_dyn.restype = ci
     lib.qb_qlinear_fwd_dyn.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_embedding_quantize_bits.restype = ci
@@ -294,6 +296,24 @@ def qb_quantize_act_dyn(X, Xq=None, rs_x=None, hx_rows=None):
         hx_rows = torch.empty(T, dtype=torch.float32, device=X.device)
     _check(lib.qb_quantize_act_dyn(_p(X), T, K, _p(Xq), _p(rs_x), _p(hx_rows), _stream()))
     return Xq, rs_x, hx_rows
+
+
+def qb_quantize_act_dyn_tensor(X, Xq=None, rs_x=None, hx_rows=None, c=None):
+    """One max-abs range for the whole tensor: X[T,K] fp32 -> (Xq[T,K] int8, rs_x[T] int32, hx_rows[T] fp32 (all
+    equal c/255), c[1] fp32 = max|X|)."""
+    lib = load_library()
+    _dev(X, torch.float32, "X")
+    T, K = X.shape
+    if Xq is None:
+        Xq = torch.empty((T, K), dtype=torch.int8, device=X.device)
+    if rs_x is None:
+        rs_x = torch.empty(T, dtype=torch.int32, device=X.device)
+    if hx_rows is None:
+        hx_rows = torch.empty(T, dtype=torch.float32, device=X.device)
+    if c is None:
+        c = torch.empty(1, dtype=torch.float32, device=X.device)
+    _check(lib.qb_quantize_act_dyn_tensor(_p(X), T, K, _p(Xq), _p(rs_x), _p(hx_rows), _p(c), _stream()))
+    return Xq, rs_x, hx_rows, c
 
 
 def qb_qlinear_fwd_dyn(Xq, rs_x, hx_rows, packed, h, rs_w, bits, groups, N, bias=None, Y=None, want_a4=False):

@@ -211,9 +211,13 @@ __global__ void fill_zero_kernel(float *p, int n)
 // ---- activations: a wavefront walks over token rows (row = wavefront id, + number of wavefronts, ...)
 // in chunks of 256 float4; the loads of the next chunk (possibly of the next row) are in flight while
 // the current one is quantized, so the memory pipe never drains between rows.
+template <bool DEVCLIP>
 __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restrict__ X, int T, int K, float clip,
-                                                           int8_t *__restrict__ Xq, int32_t *__restrict__ rs_x)
+                                                           const float *__restrict__ clip_dev,
+                                                           int8_t *__restrict__ Xq, int32_t *__restrict__ rs_x,
+                                                           float *__restrict__ hx_rows)
 {
+    if constexpr (DEVCLIP) clip = *clip_dev;  // the range found by tensor_absmax_kernel
     const int lane = threadIdx.x & 63;
     const int nwaves = gridDim.x * 4;
     int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -258,7 +262,10 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
         }
         if (nc == 0) {  // row finished
             const int total = wave_sum((int)sum);
-            if (lane == 0) rs_x[row] = total - 128 * K;
+            if (lane == 0) {
+                rs_x[row] = total - 128 * K;
+                if constexpr (DEVCLIP) hx_rows[row] = qz.half_step();
+            }
             sum = 0;
         }
         if (!more) break;
@@ -266,6 +273,33 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
         c = nc;
 #pragma unroll
         for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+    }
+}
+
+// ---- activations with one range for the whole tensor, c = max |X|: pass 1 reduces into a device float
+// (zero-filled before; non-negative floats order like their bit patterns, so an integer atomic max serves),
+// pass 2 is quantize_act_kernel reading its clip from that float.
+__global__ __launch_bounds__(256) void tensor_absmax_kernel(const float4 *__restrict__ X, int64_t n4,
+                                                            float *__restrict__ c)
+{
+    __shared__ float part[4];
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float mx = 0.0f;
+    for (; i + 3 * stride < n4; i += 4 * stride) {  // four loads in flight
+        const float4 a = X[i], b = X[i + stride], d = X[i + 2 * stride], e = X[i + 3 * stride];
+        mx = absmax4(a, mx);
+        mx = absmax4(b, mx);
+        mx = absmax4(d, mx);
+        mx = absmax4(e, mx);
+    }
+    for (; i < n4; i += stride) mx = absmax4(X[i], mx);
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        atomicMax(reinterpret_cast<unsigned int *>(c), __float_as_uint(mx));
     }
 }
 
@@ -642,8 +676,27 @@ extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float
     // at most 8 workgroups per CU; fewer rows than that: one wavefront per row
     unsigned blocks = (unsigned)((T + 3) / 4);
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(quantize_act_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), X, (int)T,
-                       (int)K, clip, Xq, rs_x);
+    hipLaunchKernelGGL(quantize_act_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), X, (int)T,
+                       (int)K, clip, static_cast<const float *>(nullptr), Xq, rs_x, static_cast<float *>(nullptr));
+    return launch_status();
+}
+
+extern "C" qb_status qb_quantize_act_dyn_tensor(const float *X, int64_t T, int64_t K, int8_t *Xq, int32_t *rs_x,
+                                                float *hx_rows, float *c_out, void *stream)
+{
+    if (!X || !Xq || !rs_x || !hx_rows || !c_out) return QB_ERR_NULL;
+    if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n4 = T * K / 4;
+    unsigned rblocks = (unsigned)((n4 + 1023) / 1024);
+    if (rblocks > 2048) rblocks = 2048;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, st, c_out, 1);
+    hipLaunchKernelGGL(tensor_absmax_kernel, dim3(rblocks), dim3(256), 0, st, reinterpret_cast<const float4 *>(X), n4,
+                       c_out);
+    unsigned blocks = (unsigned)((T + 3) / 4);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(quantize_act_kernel<true>, dim3(blocks), dim3(256), 0, st, X, (int)T, (int)K, 0.0f,
+                       static_cast<const float *>(c_out), Xq, rs_x, hx_rows);
     return launch_status();
 }
 

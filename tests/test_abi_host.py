@@ -111,6 +111,10 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     # quantize_act_dyn(X,T,K,Xq,rs_x,hx,stream), qlinear_fwd_dyn(Xq,rs_x,hx,packed,h,rs_w,bits,groups,T,N,K,bias,Y,A4,stream)
     assert lib.qb_quantize_act_dyn(P, 16, 64, P, P, NULL, NULL) == 1
     assert lib.qb_quantize_act_dyn(P, 16, 65, P, P, P, NULL) == 3
+    # quantize_act_dyn_tensor(X,T,K,Xq,rs_x,hx,c,stream)
+    assert lib.qb_quantize_act_dyn_tensor(P, 16, 64, P, P, P, NULL, NULL) == 1
+    assert lib.qb_quantize_act_dyn_tensor(P, 0, 64, P, P, P, P, NULL) == 3
+    assert lib.qb_quantize_act_dyn_tensor(P, 16, 65, P, P, P, P, NULL) == 3
     assert lib.qb_qlinear_fwd_dyn(P, P, NULL, P, P, P, 4, 128, 16, 768, 768, NULL, P, NULL, NULL) == 1
     assert lib.qb_qlinear_fwd_dyn(P, P, P, P, P, P, 6, 128, 16, 768, 768, NULL, P, NULL, NULL) == 2
     assert lib.qb_qlinear_fwd_dyn(P, P, P, P, P, P, 4, 128, 16, 770, 768, NULL, P, NULL, NULL) == 3

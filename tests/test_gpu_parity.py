@@ -469,6 +469,53 @@ def test_forward_dynamic_scales(qb, bits, shape):
         assert torch.equal(Y2, Y)   # the call without the debug output
 
 
+@pytest.mark.parametrize("shape", [(1, 64), (5, 192), (1000, 768), (4096, 3072), (257, 4096), (3, 16384)])
+def test_quantize_act_dynamic_tensor(qb, shape):
+    """One max-abs range for the whole tensor: codes, row sums, the range and the per-row scales bit for bit; a
+    second call into the same buffers with a smaller tensor (the range must not survive from the first); zeros."""
+    T, K = shape
+    say("act quant dynamic, per tensor", shape)
+    X = wl.activation(T, K, seed=T + K + 2)
+    X[T // 2, K // 3] = 41.5          # the maximum, somewhere in the middle
+    Xq, rs_x, hx, c = qb.qb_quantize_act_dyn_tensor(X.to(DEV))
+    torch.cuda.synchronize()
+    oq, ors, ohx = oracle.quantize_act_dyn_tensor(X.numpy())
+    assert c.cpu().numpy()[0] == np.abs(X.numpy()).max()
+    assert (Xq.cpu().numpy() == oq).all()
+    assert (rs_x.cpu().numpy() == ors).all()
+    assert (hx.cpu().numpy().view(np.uint32) == np.float32(ohx).view(np.uint32)).all()
+    X2 = (0.01 * X).contiguous()
+    qb.qb_quantize_act_dyn_tensor(X2.to(DEV), Xq, rs_x, hx, c)
+    torch.cuda.synchronize()
+    oq, ors, ohx = oracle.quantize_act_dyn_tensor(X2.numpy())
+    assert (Xq.cpu().numpy() == oq).all() and (rs_x.cpu().numpy() == ors).all()
+    assert (hx.cpu().numpy().view(np.uint32) == np.float32(ohx).view(np.uint32)).all()
+    qb.qb_quantize_act_dyn_tensor(torch.zeros_like(X).to(DEV), Xq, rs_x, hx, c)
+    torch.cuda.synchronize()
+    assert (Xq == -128).all() and (rs_x == -128 * K).all() and (hx == 0).all() and (c == 0).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_forward_dynamic_tensor_range_equals_fixed_clip(qb, bits):
+    """Quantize with the tensor's own range, multiply with the per-token-scale forward: the oracle's result, and the
+    fixed-clip forward's at clip = max|X| bit for bit."""
+    T, N, K, G = 777, 768, 768, 128
+    say("fwd dynamic, per tensor", (T, N, K), "bits", bits)
+    W = wl.weight(N, K, seed=3 + bits)
+    X = wl.activation(T, K, seed=5 + bits)
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, G)
+    Xq, rs_x, hx, c = qb.qb_quantize_act_dyn_tensor(X.to(DEV))
+    Y, A4 = qb.qb_qlinear_fwd_dyn(Xq, rs_x, hx, packed, h, rs_w, bits, G, N, want_a4=True)
+    Y1 = qb.qb_qlinear_fwd(Xq, rs_x, float(c.item()), packed, h, rs_w, bits, G, N)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y1)
+    oc, oh, _, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    oq, _, ohx = oracle.quantize_act_dyn_tensor(X.numpy())
+    Yo, A4o = oracle.qlinear_fwd_dyn(oq, np.full(T, ohx, np.float32), oc, oh, bits, openmp=True)
+    assert (A4.cpu().numpy() == A4o).all()
+    assert_rel(Y.cpu().numpy(), Yo)
+
+
 def rel_fro(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
 
