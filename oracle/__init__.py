@@ -238,6 +238,29 @@ def qlinear_bwd_ste(dY_bf16, xq, clip, codes, h, bits, want_dx=True, want_dw=Tru
     return dX, dW
 
 
+def qlinear_bwd_ste_masked(dY_bf16, xq, clip, codes, h, bits, X=None, W=None, m=None, want_dx=True, want_dw=True,
+                           openmp=False):
+    """STE backward with the clamp's derivative: dX zero where |X| > clip, dW zero where |W| > m of its group."""
+    dY = _c(dY_bf16, np.uint16)
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    h = _c(h, np.float32)
+    X = None if X is None else _c(X, np.float32)
+    W = None if W is None else _c(W, np.float32)
+    m = None if m is None else _c(m, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert dY.shape == (T, N) and (X is None or X.shape == (T, K)) and (W is None or W.shape == (N, K))
+    assert m is None or m.shape == h.shape
+    dX = np.empty((T, K), np.float64) if want_dx else None
+    dW = np.empty((N, K), np.float64) if want_dw else None
+    rc = _lib(openmp).qbo_qlinear_bwd_ste_masked(_ptr(dY), _ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(h),
+                                                 int(bits), _I64(h.shape[0]), _I64(T), _I64(N), _I64(K),
+                                                 _ptr(X), _ptr(W), _ptr(m), _ptr(dX), _ptr(dW))
+    _check(rc, "qlinear_bwd_ste_masked")
+    return dX, dW
+
+
 def bwd_dx_sampled(dY_bf16, codes, h, bits, ts, js):
     dY = _c(dY_bf16, np.uint16)
     codes = _c(codes, np.uint8)

@@ -514,6 +514,29 @@ int qbo_qlinear_bwd_ste(const uint16_t *dY, const int8_t *xq, float clip, const 
     return QBO_OK;
 }
 
+/* The same backward with the clamp's own derivative kept (App.: X' = Clamp(X, q0, q_{2^k-1}) comes before the
+ * rounding; only the rounding is passed straight through): a value outside its range was moved to the range's
+ * end and has derivative 0, one inside (ends included) has derivative 1.
+ *   X [T,K] raw activations, range [-clip, +clip]  -> dX[t,j] = 0 where |X[t,j]| > clip     (NULL: no mask)
+ *   W [N,K] raw weights, m[G] the group ranges     -> dW[n,j] = 0 where |W[n,j]| > m[g(n)]  (NULL: no mask) */
+int qbo_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *xq, float clip, const uint8_t *codes,
+                               const float *h, int bits, int64_t G, int64_t T, int64_t N, int64_t K,
+                               const float *X, const float *W, const float *m, double *dX, double *dW)
+{
+    int64_t i, rows;
+    int rc = qbo_qlinear_bwd_ste(dY, xq, clip, codes, h, bits, G, T, N, K, dX, dW);
+    if (rc != QBO_OK) return rc;
+    if ((W == NULL) != (m == NULL)) return QBO_ERR_ARG;
+    rows = N / G;
+    if (dX && X)
+        for (i = 0; i < T * K; ++i)
+            if (fabsf(X[i]) > clip) dX[i] = 0.0;
+    if (dW && W)
+        for (i = 0; i < N * K; ++i)
+            if (fabsf(W[i]) > m[(i / K) / rows]) dW[i] = 0.0;
+    return QBO_OK;
+}
+
 /* Single entries of the two gradients, for full-size checks. */
 int qbo_bwd_dx_sampled(const uint16_t *dY, const uint8_t *codes, const float *h, int bits,
                        int64_t G, int64_t T, int64_t N, int64_t K,

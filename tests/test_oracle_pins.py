@@ -584,3 +584,66 @@ def test_dynamic_tensor_range_worked_example_and_special_cases():
     Z[1, 5] = np.inf
     with pytest.raises(Exception):
         oracle.quantize_act_dyn_tensor(Z)
+
+
+def test_masked_ste_is_the_gradient_of_the_clamped_layer():
+    """With only the rounding passed straight through, the layer is <dY, Clamp(X) What^T> in X and
+    <dY, Xhat Clamp_g(W)^T> in W: the masked backward must equal central differences of those (fp64, away from the
+    kinks), be exactly zero outside the ranges and untouched inside, pass at the range's ends, and equal the plain
+    backward when nothing lies outside."""
+    T, N, K, G, bits = 7, 8, 64, 2, 4
+    clip = 1.5
+    X = rng(95).standard_normal((T, K)).astype(np.float32)
+    X[0, 0], X[0, 1], X[0, 2] = clip, -clip, np.nextafter(np.float32(clip), np.float32(2))
+    W = (rng(96).standard_normal((N, K)) * 0.05).astype(np.float32)
+    m = np.array([0.06, np.abs(W[N // 2:]).max()], np.float32)      # group 0 clipped, group 1 at its max-abs
+    W[1, 3] = -m[0]
+    codes, h, rs_w = oracle.quantize_groupwise_clip(W, bits, m)
+    xq, rs_x = oracle.quantize_act(X, clip)
+    dYf = (rng(97).standard_normal((T, N)) * 1e-2).astype(np.float32)
+    dY_bits = (dYf.view(np.uint32) >> 16).astype(np.uint16)
+    dY = (dY_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    dX, dW = oracle.qlinear_bwd_ste(dY_bits, xq, clip, codes, h, bits)
+    dXm, dWm = oracle.qlinear_bwd_ste_masked(dY_bits, xq, clip, codes, h, bits, X=X, W=W, m=m)
+    outX = np.abs(X) > np.float32(clip)
+    mrow = np.repeat(m, N // G)[:, None]
+    outW = np.abs(W) > mrow
+    assert outX.sum() > 20 and outW[:N // 2].sum() > 20 and not outW[N // 2:].any()
+    assert not outX[0, 0] and not outX[0, 1] and outX[0, 2] and not outW[1, 3]
+    assert (dXm[outX] == 0).all() and (dXm[~outX] == dX[~outX]).all() and (dX[outX] != 0).all()
+    assert (dWm[outW] == 0).all() and (dWm[~outW] == dW[~outW]).all() and (dW[outW] != 0).all()
+    # only one side masked
+    a, b = oracle.qlinear_bwd_ste_masked(dY_bits, xq, clip, codes, h, bits, X=X)
+    assert (a == dXm).all() and (b == dW).all()
+    a, b = oracle.qlinear_bwd_ste_masked(dY_bits, xq, clip, codes, h, bits, W=W, m=m)
+    assert (a == dX).all() and (b == dWm).all()
+    # central differences of the clamped layer
+    What = oracle.dequantize_groupwise(codes, h, bits)
+    Xhat = oracle.dequantize_act(xq, clip)
+    X64, W64 = X.astype(np.float64), W.astype(np.float64)
+    fX = lambda Xv: ((np.clip(Xv, -clip, clip) @ What.T) * dY).sum()
+    fW = lambda Wv: ((Xhat @ np.clip(Wv, -mrow.astype(np.float64), mrow.astype(np.float64)).T) * dY).sum()
+    eps = 1e-4
+    r = rng(98)
+    checked_out = 0
+    for _ in range(60):
+        t, j = r.integers(0, T), r.integers(0, K)
+        if abs(abs(X64[t, j]) - clip) > 1e-2:
+            E = np.zeros_like(X64); E[t, j] = eps
+            num = (fX(X64 + E) - fX(X64 - E)) / (2 * eps)
+            assert abs(num - dXm[t, j]) <= 1e-10 + 1e-6 * abs(dX[t, j])
+            checked_out += int(outX[t, j])
+        n, j = r.integers(0, N), r.integers(0, K)
+        if abs(abs(W64[n, j]) - float(mrow[n, 0])) > 1e-3:
+            E = np.zeros_like(W64); E[n, j] = eps
+            num = (fW(W64 + E) - fW(W64 - E)) / (2 * eps)
+            assert abs(num - dWm[n, j]) <= 1e-10 + 1e-6 * abs(dW[n, j])
+            checked_out += int(outW[n, j])
+    assert checked_out >= 5
+    # nothing outside: the plain backward
+    Xs = (0.1 * X).astype(np.float32)
+    xqs, _ = oracle.quantize_act(Xs, clip)
+    c2, h2, m2, _ = oracle.quantize_groupwise(W, bits, G)
+    p = oracle.qlinear_bwd_ste(dY_bits, xqs, clip, c2, h2, bits)
+    q = oracle.qlinear_bwd_ste_masked(dY_bits, xqs, clip, c2, h2, bits, X=Xs, W=W, m=m2)
+    assert (p[0] == q[0]).all() and (p[1] == q[1]).all()
