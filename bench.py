@@ -386,7 +386,7 @@ def dynamic_range_leg(torch, qb, wl, dev):
 def backward_leg(torch, qb, wl, dev):
     """configs[2]: STE backward of the same layer, 3-bit weights, dY bf16; flops = 4*T*N*K."""
     T, b = T_TOKENS, 3
-    tot_sec, tot_flops, rows = 0.0, 0.0, []
+    tot_sec, tot_flops, tot_masked, rows = 0.0, 0.0, 0.0, []
     for i, (name, N, K) in enumerate(wl.BERT_BASE_LINEARS):
         W = wl.weight(N, K, seed=wl.config_seed(2, i)).to(dev)
         X = wl.activation(T, K, seed=wl.config_seed(2, 10 + i)).to(dev)
@@ -398,13 +398,18 @@ def backward_leg(torch, qb, wl, dev):
         ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=dev)
         sec = time_launches(torch, lambda: qb.qb_qlinear_bwd_ste(dY, Xq, CLIP, packed, h, b, GROUPS, dX=dX, dW=dW,
                                                                  workspace=ws), iters=20)
+        secm = time_launches(torch, lambda: qb.qb_qlinear_bwd_ste_masked(dY, Xq, CLIP, packed, h, b, GROUPS, X=X, W=W, m=m,
+                                                                         dX=dX, dW=dW, workspace=ws), iters=20)
         fl = 4.0 * T * N * K
-        rows.append({"linear": name, "us": round(sec * 1e6, 1), "tflops": round(fl / sec / 1e12, 1)})
+        rows.append({"linear": name, "us": round(sec * 1e6, 1), "tflops": round(fl / sec / 1e12, 1),
+                     "clamp_masked_us": round(secm * 1e6, 1)})
         tot_sec += sec
+        tot_masked += secm
         tot_flops += fl
     return {"workload": "configs[2]: dX and dW for the four linears, T=4096, 3-bit, bf16 MFMA / fp32 accumulate",
             "tflops": round(tot_flops / tot_sec / 1e12, 1), "frac_bf16_peak": round(tot_flops / tot_sec / 1e12 / PEAK_BF16_TFLOPS, 4),
-            "us_per_layer": round(tot_sec * 1e6, 1), "per_linear": rows}
+            "us_per_layer": round(tot_sec * 1e6, 1), "clamp_masked_us_per_layer": round(tot_masked * 1e6, 1),
+            "per_linear": rows}
 
 
 def embedding_leg(torch, qb, wl, dev):

@@ -98,7 +98,7 @@ qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, vo
  * clamped and get the end codes.  m_in = the max-abs gives the codes of qb_quantize_groupwise.
  *   m_in  in  [G] fp32, >= 0 and finite (not checked on the device)
  * The packed result feeds qb_qlinear_fwd and qb_qlinear_bwd_ste unchanged (the backward passes the
- * gradient through the clamp as well: plain straight-through).
+ * gradient through the clamp as well: plain straight-through; qb_qlinear_bwd_ste_masked does not).
  */
 qb_status qb_quantize_groupwise_clip(const float *W, int64_t N, int64_t K, int bits, int groups,
                                      const float *m_in, void *packed, float *h, int32_t *rs_w,
@@ -195,6 +195,23 @@ qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
                              const void *packed, const float *h, int bits, int groups,
                              int64_t T, int64_t N, int64_t K,
                              uint16_t *dX, float *dW, void *workspace, void *stream);
+
+/*
+ * The same backward with the clamp's own derivative kept (App.: X' = Clamp(X, q0, q_{2^k-1}) precedes the
+ * rounding; only the rounding is passed straight through): the gradient of a value that lay outside its
+ * range is zero, that of a value inside (ends included) is unchanged.
+ *   X  in  [T,K] fp32, the activations that qb_quantize_act saw, range [-clip, +clip]; NULL: dX unmasked
+ *   W  in  [N,K] fp32, the weights that qb_quantize_groupwise[_clip] saw, and
+ *   m  in  [G] fp32, the group ranges it used (its m output, or the m_in given); both NULL: dW unmasked
+ *          (one of the two NULL: QB_ERR_NULL)
+ * The masks are applied where the two products are written (no extra pass); other arguments, workspace
+ * and errors as qb_qlinear_bwd_ste.
+ */
+qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float clip,
+                                    const void *packed, const float *h, int bits, int groups,
+                                    int64_t T, int64_t N, int64_t K,
+                                    const float *X, const float *W, const float *m,
+                                    uint16_t *dX, float *dW, void *workspace, void *stream);
 
 /* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
  * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */

@@ -21,7 +21,7 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
-           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor")
+           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked")
 
 
 class _QuantJob(ctypes.Structure):
@@ -64,6 +64,8 @@ def load_library():
     lib.qb_qlinear_fwd_q8.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, ci, cf, vp, vp, vp]
     lib.qb_qlinear_bwd_ste.restype = ci
     lib.qb_qlinear_bwd_ste.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_bwd_ste_masked.restype = ci
+    lib.qb_qlinear_bwd_ste_masked.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.qb_unpack_codes.restype = ci
     lib.qb_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.qb_embedding_quantize.restype = ci
@@ -218,6 +220,39 @@ def qb_qlinear_bwd_ste(dY, Xq, clip, packed, h, bits, groups, want_dx=True, want
         workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
     _check(lib.qb_qlinear_bwd_ste(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
                                   _p(dX), _p(dW), _p(workspace), _stream()))
+    return dX, dW
+
+
+def qb_qlinear_bwd_ste_masked(dY, Xq, clip, packed, h, bits, groups, X=None, W=None, m=None, want_dx=True,
+                              want_dw=True, dX=None, dW=None, workspace=None):
+    """The backward with the clamp's derivative: dX zero where |X| > clip (X given), dW zero where |W| > m of
+    its group (W and m given)."""
+    lib = load_library()
+    _dev(dY, torch.bfloat16, "dY")
+    _dev(Xq, torch.int8, "Xq")
+    T, N = dY.shape
+    K = Xq.shape[1]
+    dev = dY.device
+    if X is not None:
+        _dev(X, torch.float32, "X")
+        if tuple(X.shape) != (T, K):
+            raise ValueError("X must be [T, K]")
+    if W is not None:
+        _dev(W, torch.float32, "W")
+        if tuple(W.shape) != (N, K):
+            raise ValueError("W must be [N, K]")
+    if m is not None:
+        _dev(m, torch.float32, "m")
+        if m.numel() != groups:
+            raise ValueError("m must hold one range per group")
+    if want_dx and dX is None:
+        dX = torch.empty((T, K), dtype=torch.bfloat16, device=dev)
+    if want_dw and dW is None:
+        dW = torch.empty((N, K), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
+    _check(lib.qb_qlinear_bwd_ste_masked(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
+                                         _p(X), _p(W), _p(m), _p(dX), _p(dW), _p(workspace), _stream()))
     return dX, dW
 
 

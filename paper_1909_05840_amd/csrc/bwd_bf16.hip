@@ -198,10 +198,19 @@ __device__ __forceinline__ void wait_vmcnt()
 //                    for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
 //                           wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
 //   MFMA wavefronts: BARRIER; for s: multiply stage s % NSTAGE; BARRIER
-template <int NSTAGE, int OUT>
+// The clamp's derivative (MASK): element (r, n) of the result is set to zero where |src[r, n]| exceeds its
+// range, lim[r / rows_per_lim] if lim is given (weights: one range per group of rows), else lim_all.
+struct ClampMask {
+    const float *src;
+    const float *lim;
+    float lim_all;
+    int rows_per_lim;
+};
+
+template <int NSTAGE, int OUT, bool MASK>
 __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int Nc, int Kc, int lda, int ldb,
-    int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n)
+    int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n, const ClampMask mask)
 {
     constexpr int TM = 2, WN = 3, NPROD = 2;
     constexpr int BM = 128, BN = 96, BKB = 128;  // 64 bf16 per step
@@ -337,6 +346,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
                 const int r = r0 + 8 * (i >> 2) + (i & 3);
                 if (r < M && n < Nc) {
                     const size_t at = (size_t)r * Nc + n;
+                    if constexpr (MASK && OUT != 2) {
+                        const float lim = mask.lim ? mask.lim[r / mask.rows_per_lim] : mask.lim_all;
+                        if (fabsf(mask.src[at]) > lim) acc[tm][i] = 0.0f;
+                    }
                     if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][i]);
                     else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][i] * scale;
                     else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][i];
@@ -346,26 +359,35 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
     }
 }
 
+template <bool MASK>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int64_t n, int splits,
-                                                              float scale, float *__restrict__ out)
+                                                              float scale, float *__restrict__ out, int cols,
+                                                              const ClampMask mask)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     float s = 0.0f;
     for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
+    if constexpr (MASK) {
+        if (fabsf(mask.src[i]) > mask.lim[(i / cols) / mask.rows_per_lim]) s = 0.0f;
+    }
     out[i] = s * scale;
 }
 
 template <int OUT>
 void launch_gemm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
-                 float scale, void *C, hipStream_t st)
+                 float scale, void *C, hipStream_t st, const ClampMask *mask = nullptr)
 {
     // 128 x 96 tiles, 3 stages of 28 KB, one workgroup per CU; persistent grid of at most 256 per split
     const int tm = (M + 127) / 128, tn = (Nc + 95) / 96;
     int grid = tm * tn;
     if (grid > 256) grid = 256;
-    hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc, lda, ldb,
-                       ksplit, scale, C, tm, tn);
+    if (mask && OUT != 2)
+        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, true>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn, *mask);
+    else
+        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, false>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn, ClampMask{nullptr, nullptr, 0.0f, 1});
 }
 
 struct BwdPlan {
@@ -410,9 +432,9 @@ extern "C" size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K)
     return make_plan(T, N, K).total;
 }
 
-extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
-                                        const float *h, int bits, int groups, int64_t T, int64_t N, int64_t K,
-                                        uint16_t *dX, float *dW, void *workspace, void *stream)
+static qb_status bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed, const float *h, int bits,
+                         int groups, int64_t T, int64_t N, int64_t K, const float *X, const float *W, const float *m,
+                         uint16_t *dX, float *dW, void *workspace, void *stream)
 {
     if (!dY || !Xq || !packed || !h) return QB_ERR_NULL;
     if (!bits_ok(bits)) return QB_ERR_BITS;
@@ -451,18 +473,41 @@ extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, fl
             hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((T * Np + 255) / 256)), dim3(256), 0, st, dY, T, (int)N, Np, dYp);
             Aop = dYp;
         }
-        launch_gemm<0>(Aop, WT, (int)T, (int)K, Np, Np, Np, 1, Np, 1.0f, dX, st);
+        const ClampMask mx{X, nullptr, clip, 1};
+        launch_gemm<0>(Aop, WT, (int)T, (int)K, Np, Np, Np, 1, Np, 1.0f, dX, st, X ? &mx : nullptr);
     }
     if (dW) {
         const float hx = clip / 255.0f;
+        const ClampMask mw{W, m, 0.0f, rpg};
         if (p.splits > 1) {
             float *part = reinterpret_cast<float *>(ws + p.off_part);
+            const dim3 rgrid((unsigned)((N * K + 255) / 256));
             launch_gemm<2>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, p.splits, p.ksplit, 1.0f, part, st);
-            hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((N * K + 255) / 256)), dim3(256), 0, st, part,
-                               N * K, p.splits, hx, dW);
+            if (W)
+                hipLaunchKernelGGL(reduce_partials_kernel<true>, rgrid, dim3(256), 0, st, part, N * K, p.splits, hx, dW,
+                                   (int)K, mw);
+            else
+                hipLaunchKernelGGL(reduce_partials_kernel<false>, rgrid, dim3(256), 0, st, part, N * K, p.splits, hx, dW,
+                                   (int)K, mw);
         } else {
-            launch_gemm<1>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, 1, Tp, hx, dW, st);
+            launch_gemm<1>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, 1, Tp, hx, dW, st, W ? &mw : nullptr);
         }
     }
     return launch_status();
+}
+
+extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
+                                        const float *h, int bits, int groups, int64_t T, int64_t N, int64_t K,
+                                        uint16_t *dX, float *dW, void *workspace, void *stream)
+{
+    return bwd_ste(dY, Xq, clip, packed, h, bits, groups, T, N, K, nullptr, nullptr, nullptr, dX, dW, workspace, stream);
+}
+
+extern "C" qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
+                                               const float *h, int bits, int groups, int64_t T, int64_t N, int64_t K,
+                                               const float *X, const float *W, const float *m, uint16_t *dX,
+                                               float *dW, void *workspace, void *stream)
+{
+    if ((W == nullptr) != (m == nullptr)) return QB_ERR_NULL;
+    return bwd_ste(dY, Xq, clip, packed, h, bits, groups, T, N, K, X, W, m, dX, dW, workspace, stream);
 }

@@ -87,6 +87,12 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, ctypes.c_void_p(0x1010), NULL) == 5
     assert lib.qb_qlinear_bwd_ste(P, NULL, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, P, NULL) == 1
     assert lib.qb_qlinear_bwd_ste(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, NULL, NULL, NULL, NULL) == 0  # nothing asked
+    # qlinear_bwd_ste_masked(dY,Xq,clip,packed,h,bits,groups,T,N,K,X,W,m,dX,dW,workspace,stream)
+    assert lib.qb_qlinear_bwd_ste_masked(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, NULL, P, P, P, NULL) == 1  # W without m
+    assert lib.qb_qlinear_bwd_ste_masked(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, NULL, P, P, P, P, NULL) == 1
+    assert lib.qb_qlinear_bwd_ste_masked(P, P, f(6.0), P, P, 5, 128, 16, 768, 768, P, P, P, P, P, P, NULL) == 2
+    assert lib.qb_qlinear_bwd_ste_masked(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, P, P, P, NULL, NULL) == 5
+    assert lib.qb_qlinear_bwd_ste_masked(P, P, f(6.0), P, P, 4, 128, 16, 768, 768, P, P, P, NULL, NULL, NULL, NULL) == 0
     # batched quantize: host array of descriptors, every job checked before any launch
     from paper_1909_05840_amd.binding import _QuantJob
     good = _QuantJob(0x1000, 768, 768, 4, 128, 0x1000, 0x1000, 0x1000, 0x1000)

@@ -543,6 +543,47 @@ def test_backward_full_compare(qb, bits, shape):
     assert none is None and torch.equal(dX2, dX)
 
 
+@pytest.mark.parametrize("bits", [3, 8])
+@pytest.mark.parametrize("shape", [(300, 160, 192, 8), (65, 6, 64, 6), (1500, 768, 768, 128), (256, 3072, 768, 128),
+                                   (1000, 96, 320, 96)])
+def test_backward_clamp_masked(qb, bits, shape):
+    """The backward that keeps the clamp's derivative: against the oracle (norms), exact zeros where the value lay
+    outside its range, the plain backward's bits everywhere else, values at the range's ends pass; with the
+    contraction split over T and unsplit, and with one side masked only."""
+    T, N, K, G = shape
+    say("bwd masked", shape, "bits", bits)
+    clip = 1.5
+    W = wl.weight(N, K, seed=N + K + bits)
+    X = wl.activation(T, K, seed=T + bits)
+    X[0, 0], X[0, 1] = clip, -clip
+    dY = wl.grad_output_bf16(T, N, seed=T + N)
+    m_in = (0.5 * W.abs().reshape(G, -1).max(dim=1).values).contiguous()
+    W[0, 0] = m_in[0]
+    packed, h, rs_w = qb.qb_quantize_groupwise_clip(W.to(DEV), bits, m_in.to(DEV))
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), clip)
+    dYd, Xd, Wd, md = dY.to(DEV), X.to(DEV), W.to(DEV), m_in.to(DEV)
+    dX0, dW0 = qb.qb_qlinear_bwd_ste(dYd, Xq, clip, packed, h, bits, G)
+    dX, dW = qb.qb_qlinear_bwd_ste_masked(dYd, Xq, clip, packed, h, bits, G, X=Xd, W=Wd, m=md)
+    torch.cuda.synchronize()
+    outX = X.abs() > clip
+    outW = W.abs() > m_in.repeat_interleave(N // G)[:, None]
+    assert outX.sum() > 0 and outW.sum() > 0 and not outX[0, 0] and not outX[0, 1] and not outW[0, 0]
+    assert torch.equal(dX.cpu(), torch.where(outX, torch.zeros_like(dX0.cpu()), dX0.cpu()))
+    assert torch.equal(dW.cpu(), torch.where(outW, torch.zeros_like(dW0.cpu()), dW0.cpu()))
+    oc, oh, _ = oracle.quantize_groupwise_clip(W.numpy(), bits, m_in.numpy())
+    oq, _ = oracle.quantize_act(X.numpy(), clip)
+    odX, odW = oracle.qlinear_bwd_ste_masked(wl.bf16_bits(dY), oq, clip, oc, oh, bits, X=X.numpy(), W=W.numpy(),
+                                             m=m_in.numpy(), openmp=True)
+    assert ((odX == 0) == outX.numpy()).all() and ((odW == 0) == outW.numpy()).all()
+    assert rel_fro(dX.float().cpu().numpy(), odX) <= 2e-2
+    assert rel_fro(dW.cpu().numpy(), odW) <= 1e-4
+    # one side only
+    a, b = qb.qb_qlinear_bwd_ste_masked(dYd, Xq, clip, packed, h, bits, G, X=Xd)
+    assert torch.equal(a, dX) and torch.equal(b, dW0)
+    a, b = qb.qb_qlinear_bwd_ste_masked(dYd, Xq, clip, packed, h, bits, G, W=Wd, m=md)
+    assert torch.equal(a, dX0) and torch.equal(b, dW)
+
+
 @pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
 def test_backward_config3_full_size(qb, lin):
     """Configuration 3: T = 4096, 3-bit weights, 128 groups; sampled entries + norms."""
