@@ -199,7 +199,7 @@ __device__ __forceinline__ void wait_vmcnt()
 //                           wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
 //   MFMA wavefronts: BARRIER; for s: multiply stage s % NSTAGE; BARRIER
 // The clamp's derivative (MASK): element (r, n) of the result is set to zero where |src[r, n]| exceeds its
-// range, lim[r / rows_per_lim] if lim is given (weights: one range per group of rows), else lim_all.
+// range: lim[r / rows_per_lim] for dW (weights: one range per group of rows), lim_all for dX.
 struct ClampMask {
     const float *src;
     const float *lim;
@@ -313,6 +313,23 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][i] = 0.0f;
+        // the clamp mask's source values for this wavefront's 2 x 16 results: loaded before the K-loop, which
+        // hides their latency (rows and columns past the end re-read a valid element; their results are not stored)
+        float msrc[TM][16], mlim[TM][16];  // (no load may be left for the write-out: waiting for it would also wait
+                                           // for every store before it)
+        if constexpr (MASK && OUT != 2) {
+            const int nn = tile_n * BN + wn * 32 + l32;
+            const int nc = nn < Nc ? nn : Nc - 1;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    int r = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf + 8 * (i >> 2) + (i & 3);
+                    r = r < M ? r : M - 1;
+                    msrc[tm][i] = mask.src[(size_t)r * Nc + nc];
+                    mlim[tm][i] = (OUT == 1) ? mask.lim[r / mask.rows_per_lim] : mask.lim_all;
+                }
+        }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -337,6 +354,20 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
+        // all mask decisions first, as one bit each: the stores below then depend on no load (a wait for a load
+        // between two stores would also wait for the stores before it)
+        uint32_t outside = 0;
+        if constexpr (MASK && OUT != 2) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    // the empty statement consumes the loaded values here, so the compiler places its waits for
+                    // the loads here and not next to the uses it would otherwise sink between the stores
+                    asm volatile("" : "+v"(msrc[tm][i]), "+v"(mlim[tm][i]));
+                    outside |= (fabsf(msrc[tm][i]) > mlim[tm][i] ? 1u : 0u) << (tm * 16 + i);
+                }
+        }
         const int n = tile_n * BN + wn * 32 + l32;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
@@ -347,8 +378,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
                 if (r < M && n < Nc) {
                     const size_t at = (size_t)r * Nc + n;
                     if constexpr (MASK && OUT != 2) {
-                        const float lim = mask.lim ? mask.lim[r / mask.rows_per_lim] : mask.lim_all;
-                        if (fabsf(mask.src[at]) > lim) acc[tm][i] = 0.0f;
+                        if ((outside >> (tm * 16 + i)) & 1u) acc[tm][i] = 0.0f;
                     }
                     if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][i]);
                     else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][i] * scale;
@@ -359,19 +389,32 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
     }
 }
 
+// out[row, 4c..4c+3] = scale * sum_z part[z][row, 4c..4c+3]; grid (ceil(cols/1024), rows)
 template <bool MASK>
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, int64_t n, int splits,
-                                                              float scale, float *__restrict__ out, int cols,
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float4 *__restrict__ part, int rows, int cols,
+                                                              int splits, float scale, float4 *__restrict__ out,
                                                               const ClampMask mask)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    float s = 0.0f;
-    for (int z = 0; z < splits; ++z) s += part[(int64_t)z * n + i];
-    if constexpr (MASK) {
-        if (fabsf(mask.src[i]) > mask.lim[(i / cols) / mask.rows_per_lim]) s = 0.0f;
+    const int c4 = blockIdx.x * 256 + threadIdx.x, row = blockIdx.y;
+    if (c4 >= (cols >> 2)) return;
+    const size_t at = (size_t)row * (cols >> 2) + c4, n4 = (size_t)rows * (cols >> 2);
+    float4 s = part[at];
+    for (int z = 1; z < splits; ++z) {
+        const float4 v = part[(size_t)z * n4 + at];
+        s.x += v.x;
+        s.y += v.y;
+        s.z += v.z;
+        s.w += v.w;
     }
-    out[i] = s * scale;
+    if constexpr (MASK) {
+        const float lim = mask.lim[row / mask.rows_per_lim];
+        const float4 w = reinterpret_cast<const float4 *>(mask.src)[at];
+        if (fabsf(w.x) > lim) s.x = 0.0f;
+        if (fabsf(w.y) > lim) s.y = 0.0f;
+        if (fabsf(w.z) > lim) s.z = 0.0f;
+        if (fabsf(w.w) > lim) s.w = 0.0f;
+    }
+    out[at] = make_float4(s.x * scale, s.y * scale, s.z * scale, s.w * scale);
 }
 
 template <int OUT>
@@ -481,14 +524,16 @@ static qb_status bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const
         const ClampMask mw{W, m, 0.0f, rpg};
         if (p.splits > 1) {
             float *part = reinterpret_cast<float *>(ws + p.off_part);
-            const dim3 rgrid((unsigned)((N * K + 255) / 256));
+            const dim3 rgrid((unsigned)((K / 4 + 255) / 256), (unsigned)N);
             launch_gemm<2>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, p.splits, p.ksplit, 1.0f, part, st);
+            const float4 *part4 = reinterpret_cast<const float4 *>(part);
+            float4 *dW4 = reinterpret_cast<float4 *>(dW);
             if (W)
-                hipLaunchKernelGGL(reduce_partials_kernel<true>, rgrid, dim3(256), 0, st, part, N * K, p.splits, hx, dW,
-                                   (int)K, mw);
+                hipLaunchKernelGGL(reduce_partials_kernel<true>, rgrid, dim3(256), 0, st, part4, (int)N, (int)K, p.splits,
+                                   hx, dW4, mw);
             else
-                hipLaunchKernelGGL(reduce_partials_kernel<false>, rgrid, dim3(256), 0, st, part, N * K, p.splits, hx, dW,
-                                   (int)K, mw);
+                hipLaunchKernelGGL(reduce_partials_kernel<false>, rgrid, dim3(256), 0, st, part4, (int)N, (int)K,
+                                   p.splits, hx, dW4, mw);
         } else {
             launch_gemm<1>(dYT, XT, (int)N, (int)K, Tp, Tp, Tp, 1, Tp, hx, dW, st, W ? &mw : nullptr);
         }

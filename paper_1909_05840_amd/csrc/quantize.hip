@@ -279,12 +279,13 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
 // ---- activations with one range for the whole tensor, c = max |X|: pass 1 reduces into a device float
 // (zero-filled before; non-negative floats order like their bit patterns, so an integer atomic max serves),
 // pass 2 is quantize_act_kernel reading its clip from that float.
-__global__ __launch_bounds__(256) void tensor_absmax_kernel(const float4 *__restrict__ X, int64_t n4,
-                                                            float *__restrict__ c)
+__global__ __launch_bounds__(1024) void tensor_absmax_kernel(const float4 *__restrict__ X, int64_t n4,
+                                                             float *__restrict__ c)
 {
-    __shared__ float part[4];
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // few, large workgroups: the atomics of all workgroups meet at one address, which takes them one at a time
+    __shared__ float part[16];
+    const int64_t stride = (int64_t)gridDim.x * 1024;
+    int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x;
     float mx = 0.0f;
     for (; i + 3 * stride < n4; i += 4 * stride) {  // four loads in flight
         const float4 a = X[i], b = X[i + stride], d = X[i + 2 * stride], e = X[i + 3 * stride];
@@ -297,9 +298,9 @@ __global__ __launch_bounds__(256) void tensor_absmax_kernel(const float4 *__rest
     mx = wave_max(mx);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        mx = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
-        atomicMax(reinterpret_cast<unsigned int *>(c), __float_as_uint(mx));
+    if (threadIdx.x < 64) {
+        mx = wave_max(threadIdx.x < 16 ? part[threadIdx.x] : 0.0f);
+        if (threadIdx.x == 0) atomicMax(reinterpret_cast<unsigned int *>(c), __float_as_uint(mx));
     }
 }
 
@@ -688,10 +689,10 @@ extern "C" qb_status qb_quantize_act_dyn_tensor(const float *X, int64_t T, int64
     if (T <= 0 || T > (1 << 30) || !k_ok(K)) return QB_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t n4 = T * K / 4;
-    unsigned rblocks = (unsigned)((n4 + 1023) / 1024);
-    if (rblocks > 2048) rblocks = 2048;
+    unsigned rblocks = (unsigned)((n4 + 4095) / 4096);
+    if (rblocks > 256) rblocks = 256;
     hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, st, c_out, 1);
-    hipLaunchKernelGGL(tensor_absmax_kernel, dim3(rblocks), dim3(256), 0, st, reinterpret_cast<const float4 *>(X), n4,
+    hipLaunchKernelGGL(tensor_absmax_kernel, dim3(rblocks), dim3(1024), 0, st, reinterpret_cast<const float4 *>(X), n4,
                        c_out);
     unsigned blocks = (unsigned)((T + 3) / 4);
     if (blocks > 2048) blocks = 2048;
