@@ -311,3 +311,59 @@ def embedding_gather(codes, h, ids, bits=8):
     _check(_lib().qbo_embedding_gather_bits(_ptr(codes), _ptr(h), _I64(V), _I64(d), int(bits), _I64(h.shape[0]),
                                             _ptr(ids), _I64(ids.shape[0]), _ptr(out)), "embedding_gather")
     return out
+
+
+def quantize_groupwise_asym(W, bits, groups):
+    """Group ranges [min, max] of the data. Returns codes[N,K] u8, delta[G] f32, q0[G] f32, rs_w[N] i32."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    codes = np.empty((N, K), np.uint8)
+    delta = np.empty(groups, np.float32)
+    q0 = np.empty(groups, np.float32)
+    rs = np.empty(N, np.int32)
+    _check(_lib().qbo_quantize_groupwise_asym(_ptr(W), _I64(N), _I64(K), int(bits), _I64(groups), _ptr(codes),
+                                              _ptr(delta), _ptr(q0), _ptr(rs)), "quantize_groupwise_asym")
+    return codes, delta, q0, rs
+
+
+def dequantize_groupwise_asym(codes, delta, q0):
+    codes = _c(codes, np.uint8)
+    delta = _c(delta, np.float32)
+    q0 = _c(q0, np.float32)
+    N, K = codes.shape
+    Wq = np.empty((N, K), np.float64)
+    _check(_lib().qbo_dequantize_groupwise_asym(_ptr(codes), _ptr(delta), _ptr(q0), _I64(N), _I64(K),
+                                                _I64(delta.shape[0]), _ptr(Wq)), "dequantize_groupwise_asym")
+    return Wq
+
+
+def qlinear_fwd_asym(xq, clip, codes, delta, q0, bias=None, want_s=False, openmp=False):
+    """Forward with asymmetric weights. Returns Y[T,N] f32 (and S[T,N] i64 if asked)."""
+    xq = _c(xq, np.int8)
+    codes = _c(codes, np.uint8)
+    delta = _c(delta, np.float32)
+    q0 = _c(q0, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == K
+    Y = np.empty((T, N), np.float32)
+    S = np.empty((T, N), np.int64) if want_s else None
+    _check(_lib(openmp).qbo_qlinear_fwd_asym(_ptr(xq), ctypes.c_float(clip), _ptr(codes), _ptr(delta), _ptr(q0),
+                                             _I64(delta.shape[0]), _I64(T), _I64(N), _I64(K), _ptr(bias), _ptr(Y),
+                                             _ptr(S)), "qlinear_fwd_asym")
+    return (Y, S) if want_s else Y
+
+
+def qlinear_bwd_dx_asym(dY_bf16, codes, delta, q0, openmp=False):
+    dY = _c(dY_bf16, np.uint16)
+    codes = _c(codes, np.uint8)
+    delta = _c(delta, np.float32)
+    q0 = _c(q0, np.float32)
+    T, N = dY.shape
+    K = codes.shape[1]
+    dX = np.empty((T, K), np.float64)
+    _check(_lib(openmp).qbo_qlinear_bwd_dx_asym(_ptr(dY), _ptr(codes), _ptr(delta), _ptr(q0), _I64(delta.shape[0]),
+                                                _I64(T), _I64(N), _I64(K), _ptr(dX)), "qlinear_bwd_dx_asym")
+    return dX
+

@@ -651,3 +651,122 @@ int qbo_num_threads(void)
     return 1;
 #endif
 }
+
+/* ---- asymmetric group ranges -------------------------------------------------------------------------
+ * The appendix states the quantizer for a general range [q0, q_{2^k-1}] (Delta = (q_{2^k-1} - q0)/(2^k - 1),
+ * X^I = round((X' - q0)/Delta), Q(X) = Delta*X^I + q0); the hot path takes the symmetric [-m, +m].  Here the
+ * range of a group is its own [min, max].  Each arithmetic step that decides a code is one binary32
+ * operation, as in quantize_one.  A constant group (max == min) has Delta = 0, codes 0 and Q = q0.
+ * out: codes[N,K], delta[G], q0[G], rs_w[N] = sum_j (u - 2^(k-1)) (the row sums the integer product uses). */
+int qbo_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, int64_t G, uint8_t *codes,
+                                float *delta, float *q0, int32_t *rs_w)
+{
+    int64_t g, rows;
+    int L, half;
+    if (!W || !codes || !delta || !q0 || !rs_w || !bits_ok(bits)) return QBO_ERR_ARG;
+    if (N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    L = (1 << bits) - 1;
+    half = 1 << (bits - 1);
+    rows = N / G;
+    for (g = 0; g < G; ++g) {
+        const float *Wg = W + g * rows * K;
+        uint8_t *cg = codes + g * rows * K;
+        float lo = Wg[0], hi = Wg[0], d;
+        int64_t i, r, j;
+        for (i = 0; i < rows * K; ++i) {
+            if (!isfinite(Wg[i])) return QBO_ERR_NONFINITE;
+            if (Wg[i] < lo) lo = Wg[i];
+            if (Wg[i] > hi) hi = Wg[i];
+        }
+        d = hi - lo;
+        d = d / (float)L;
+        delta[g] = d;
+        q0[g] = lo;
+        for (r = 0; r < rows; ++r) {
+            int32_t acc = 0;
+            for (j = 0; j < K; ++j) {
+                int u = 0;
+                if (d != 0.0f) {
+                    float sft = Wg[r * K + j] - lo;   /* X' - q0; nothing to clamp: the range is the data's */
+                    float t = sft / d;
+                    u = (int)rintf(t);
+                    if (u < 0) u = 0;
+                    if (u > L) u = L;
+                }
+                cg[r * K + j] = (uint8_t)u;
+                acc += u - half;
+            }
+            rs_w[g * rows + r] = acc;
+        }
+    }
+    return QBO_OK;
+}
+
+/* Q(w) = Delta*u + q0 in binary64 from the binary32 Delta and q0. */
+int qbo_dequantize_groupwise_asym(const uint8_t *codes, const float *delta, const float *q0, int64_t N, int64_t K,
+                                  int64_t G, double *Wq)
+{
+    int64_t n, j, rows;
+    if (!codes || !delta || !q0 || !Wq || N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    rows = N / G;
+    for (n = 0; n < N; ++n)
+        for (j = 0; j < K; ++j)
+            Wq[n * K + j] = (double)delta[n / rows] * (double)codes[n * K + j] + (double)q0[n / rows];
+    return QBO_OK;
+}
+
+/* Forward with asymmetric weights: integer sums first, one de-quantization after (App., last paragraph).
+ * With x' = xq (the activation level is h_x*(2x'+1)):
+ *   S[t,n] = sum_j (2x'+1)*u[n,j]      R[t] = sum_j (2x'+1)
+ *   Y[t,n] = h_x*(Delta_g*S + q0_g*R) (+ bias[n]),  evaluated in binary64 from the binary32 scales.
+ * out: Y[T,N] fp32, S[T,N] int64 or NULL. */
+int qbo_qlinear_fwd_asym(const int8_t *xq, float clip, const uint8_t *codes, const float *delta, const float *q0,
+                         int64_t G, int64_t T, int64_t N, int64_t K, const float *bias, float *Y, int64_t *S_out)
+{
+    int64_t t, rows;
+    float hx;
+    if (!xq || !codes || !delta || !q0 || !Y || !(clip > 0.0f)) return QBO_ERR_ARG;
+    if (T <= 0 || N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    hx = clip / 255.0f;
+    rows = N / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (t = 0; t < T; ++t) {
+        int64_t n, j, R = 0;
+        for (j = 0; j < K; ++j) R += 2 * (int)xq[t * K + j] + 1;
+        for (n = 0; n < N; ++n) {
+            int64_t S = 0;
+            double y;
+            for (j = 0; j < K; ++j) S += (int64_t)(2 * (int)xq[t * K + j] + 1) * (int64_t)codes[n * K + j];
+            y = (double)hx * ((double)delta[n / rows] * (double)S + (double)q0[n / rows] * (double)R);
+            if (bias) y += (double)bias[n];
+            Y[t * N + n] = (float)y;
+            if (S_out) S_out[t * N + n] = S;
+        }
+    }
+    return QBO_OK;
+}
+
+/* Straight-through backward with asymmetric weights: dX = dY * Q(W), dW as in qbo_qlinear_bwd_ste (it does
+ * not involve the weights). */
+int qbo_qlinear_bwd_dx_asym(const uint16_t *dY, const uint8_t *codes, const float *delta, const float *q0,
+                            int64_t G, int64_t T, int64_t N, int64_t K, double *dX)
+{
+    int64_t t, rows;
+    if (!dY || !codes || !delta || !q0 || !dX || T <= 0 || N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    rows = N / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (t = 0; t < T; ++t) {
+        int64_t n, j;
+        for (j = 0; j < K; ++j) dX[t * K + j] = 0.0;
+        for (n = 0; n < N; ++n) {
+            double g = bf16_to_double(dY[t * N + n]);
+            double d = (double)delta[n / rows], z = (double)q0[n / rows];
+            for (j = 0; j < K; ++j) dX[t * K + j] += g * (d * (double)codes[n * K + j] + z);
+        }
+    }
+    return QBO_OK;
+}

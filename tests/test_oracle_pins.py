@@ -647,3 +647,101 @@ def test_masked_ste_is_the_gradient_of_the_clamped_layer():
     p = oracle.qlinear_bwd_ste(dY_bits, xqs, clip, c2, h2, bits)
     q = oracle.qlinear_bwd_ste_masked(dY_bits, xqs, clip, c2, h2, bits, X=Xs, W=W, m=m2)
     assert (p[0] == q[0]).all() and (p[1] == q[1]).all()
+
+
+# ---- asymmetric group ranges [min, max] (App. A, general q0) ----------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+def test_asymmetric_range_lattice_nearest_level_and_special_cases(bits):
+    """Closed-form lattice (weights on q0 + Delta*u come back as u, de-quantize exactly), nearest level by exact
+    rational arithmetic, both ends of the range are codes 0 and L, all levels used; a symmetric group gives the
+    symmetric quantizer's codes; a constant group has Delta = 0, codes 0 and Q = q0; an all-positive group spends
+    no level on negative values."""
+    from fractions import Fraction
+    L = 2 ** bits - 1
+    # lattice: q0 = -0.75, Delta = 2^-5: exact in binary32
+    K = 64
+    u = (np.arange(2 * K) * 7 % (L + 1)).reshape(2, K)
+    u[0, 0], u[1, 1] = 0, L
+    W = (-0.75 + u * 2.0 ** -5).astype(np.float32)
+    codes, delta, q0, rs = oracle.quantize_groupwise_asym(W, bits, 1)
+    assert delta[0] == np.float32(2.0 ** -5) and q0[0] == np.float32(-0.75)
+    assert (codes == u).all()
+    assert (rs == (u - 2 ** (bits - 1)).sum(axis=1)).all()
+    assert (oracle.dequantize_groupwise_asym(codes, delta, q0) == W.astype(np.float64)).all()
+    # random data, two groups with different offsets
+    r = rng(110 + bits)
+    W = np.concatenate([r.uniform(0.1, 0.9, (3, K)), r.normal(-2.0, 0.3, (3, K))]).astype(np.float32)
+    codes, delta, q0, rs = oracle.quantize_groupwise_asym(W, bits, 2)
+    for g in range(2):
+        Wg, cg = W[3 * g:3 * g + 3], codes[3 * g:3 * g + 3]
+        assert q0[g] == Wg.min() and delta[g] == np.float32(np.float32(Wg.max() - Wg.min()) / np.float32(L))
+        assert cg[Wg == Wg.min()].max() == 0 and cg[Wg == Wg.max()].min() == L
+        if bits <= 4 and g == 0:                                   # uniform data: every level occurs
+            assert np.unique(cg).size == L + 1
+        d, z = Fraction(float(delta[g])), Fraction(float(q0[g]))
+        for w, c in zip(Wg.ravel()[:60], cg.ravel()[:60]):
+            err = abs(Fraction(float(w)) - (d * int(c) + z))
+            assert err <= d / 2 * (1 + Fraction(1, 10 ** 5))       # nearest of the levels (up to binary32 rounding)
+    assert (q0[0] > 0) and codes[:3].min() == 0                     # all-positive group: level 0 is its minimum
+    # symmetric group: same codes as the symmetric quantizer
+    Ws = r.standard_normal((4, K)).astype(np.float32)
+    Ws[0, 0] = -np.abs(Ws).max() * 1.5
+    Ws[1, 1] = -Ws[0, 0]
+    ca, da, qa, rsa = oracle.quantize_groupwise_asym(Ws, bits, 1)
+    cs, hs, ms, rss = oracle.quantize_groupwise(Ws, bits, 1)
+    assert qa[0] == -ms[0] and (ca == cs).all() and (rsa == rss).all()
+    # constant group
+    Wc = np.full((2, K), 0.3, np.float32)
+    cc, dc, qc, rc = oracle.quantize_groupwise_asym(Wc, bits, 1)
+    assert dc[0] == 0 and qc[0] == np.float32(0.3) and (cc == 0).all()
+    assert (oracle.dequantize_groupwise_asym(cc, dc, qc) == float(np.float32(0.3))).all()
+    assert (rc == -K * 2 ** (bits - 1)).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+def test_asymmetric_forward_and_backward_equal_fp64_gemm(bits):
+    """Y and dX against numpy fp64 products of the de-quantized operands; the integer sum S by Python integers; on a
+    symmetric group the result agrees with the symmetric forward; the error of the layer is smaller than the
+    symmetric quantizer's on one-sided weights (what the wider use of the levels buys)."""
+    T, N, K, G = 11, 12, 64, 3
+    r = rng(120 + bits)
+    W = (r.uniform(0.0, 0.08, (N, K))).astype(np.float32)      # one-sided, like weights after a ReLU-style shift
+    X = r.standard_normal((T, K)).astype(np.float32)
+    bias = r.standard_normal(N).astype(np.float32)
+    codes, delta, q0, rs_w = oracle.quantize_groupwise_asym(W, bits, G)
+    xq, rs_x = oracle.quantize_act(X, 6.0)
+    What = oracle.dequantize_groupwise_asym(codes, delta, q0)
+    Xhat = oracle.dequantize_act(xq, 6.0)
+    Y, S = oracle.qlinear_fwd_asym(xq, 6.0, codes, delta, q0, want_s=True)
+    ref = Xhat @ What.T
+    scale = (np.abs(Xhat) @ np.abs(What).T)
+    assert (np.abs(Y - ref) <= 1e-6 * scale).all()
+    xi = 2 * xq.astype(object) + 1
+    assert S[3, 5] == sum(int(a) * int(c) for a, c in zip(xi[3], codes[5]))
+    assert S[10, 11] == sum(int(a) * int(c) for a, c in zip(xi[10], codes[11]))
+    Yb = oracle.qlinear_fwd_asym(xq, 6.0, codes, delta, q0, bias=bias)
+    assert (np.abs(Yb - (ref + bias[None, :])) <= 1e-6 * (scale + np.abs(bias)[None, :])).all()
+    dYf = (r.standard_normal((T, N)) * 1e-2).astype(np.float32)
+    dY_bits = (dYf.view(np.uint32) >> 16).astype(np.uint16)
+    dY = (dY_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    dX = oracle.qlinear_bwd_dx_asym(dY_bits, codes, delta, q0)
+    assert np.allclose(dX, dY @ What, rtol=1e-12, atol=1e-15)
+    # less layer error than the symmetric range on one-sided weights
+    cs, hs, ms, _ = oracle.quantize_groupwise(W, bits, G)
+    full = Xhat @ W.astype(np.float64).T
+    e_asym = np.linalg.norm(ref - full)
+    e_sym = np.linalg.norm(Xhat @ oracle.dequantize_groupwise(cs, hs, bits).T - full)
+    assert e_asym < 0.7 * e_sym
+    # symmetric groups: the two forwards agree
+    Wsym = r.standard_normal((N, K)).astype(np.float32) * 0.05
+    for g in range(G):
+        blk = Wsym[g * (N // G):(g + 1) * (N // G)]
+        mval = np.abs(blk).max()
+        blk[0, 0], blk[0, 1] = mval, -mval
+    ca, da, qa, _ = oracle.quantize_groupwise_asym(Wsym, bits, G)
+    cs, hs, ms, _ = oracle.quantize_groupwise(Wsym, bits, G)
+    assert (ca == cs).all()
+    Ya = oracle.qlinear_fwd_asym(xq, 6.0, ca, da, qa)
+    Ys, _, _ = oracle.qlinear_fwd(xq, 6.0, cs, hs, bits)
+    sc = np.abs(Xhat) @ np.abs(oracle.dequantize_groupwise(cs, hs, bits)).T
+    assert (np.abs(Ya - Ys) <= 2e-6 * sc).all()
