@@ -213,6 +213,34 @@ qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float 
                                     const float *X, const float *W, const float *m,
                                     uint16_t *dX, float *dW, void *workspace, void *stream);
 
+/*
+ * Asymmetric group ranges (App., the quantizer in its general form: range [q0, q_{2^k-1}],
+ * Delta = (q_{2^k-1} - q0)/(2^k - 1), X^I = round((X - q0)/Delta), Q(X) = Delta*X^I + q0): the range of a group
+ * is its own [min, max] instead of the symmetric [-max|w|, +max|w|] of qb_quantize_groupwise, so that no level
+ * is spent outside the data (one-sided or shifted weight groups).
+ *   delta  out  [G] fp32, Delta_g (0 for a constant group, whose codes are 0)
+ *   q0     out  [G] fp32, the group's minimum
+ *   packed, rs_w  as qb_quantize_groupwise (same layout, same row sums: qb_unpack_codes applies)
+ * Both delta and q0 serve as scratch of the min/max reduction during the call.  Four launches on `stream`.
+ *
+ * qb_qlinear_fwd_asym: Y[t,n] = h_x * (Delta_g * S[t,n] + q0_g * R[t]) (+ bias[n]) with the integer sums
+ * S = sum_j (2x'+1) u[n,j] and R = sum_j (2x'+1) = 2 rs_x[t] + K, both taken from the same int8 matrix-core
+ * product as qb_qlinear_fwd (S = (A4 + (2^k-1) R)/2, exact).  A4_debug as there.  Fixed activation clip only.
+ *
+ * qb_qlinear_bwd_ste_asym: qb_qlinear_bwd_ste with Q(w) = Delta*u + q0 in dX; dW does not involve the weights.
+ * Errors as the symmetric calls.
+ */
+qb_status qb_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, int groups,
+                                     void *packed, float *delta, float *q0, int32_t *rs_w, void *stream);
+qb_status qb_qlinear_fwd_asym(const int8_t *Xq, const int32_t *rs_x, float clip,
+                              const void *packed, const float *delta, const float *q0, const int32_t *rs_w,
+                              int bits, int groups, int64_t T, int64_t N, int64_t K,
+                              const float *bias, float *Y, int32_t *A4_debug, void *stream);
+qb_status qb_qlinear_bwd_ste_asym(const uint16_t *dY, const int8_t *Xq, float clip,
+                                  const void *packed, const float *delta, const float *q0, int bits, int groups,
+                                  int64_t T, int64_t N, int64_t K,
+                                  uint16_t *dX, float *dW, void *workspace, void *stream);
+
 /* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
  * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */
 qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits,

@@ -21,7 +21,8 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
-           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked")
+           "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
+           "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym")
 
 
 class _QuantJob(ctypes.Structure):
@@ -64,6 +65,12 @@ def load_library():
     lib.qb_qlinear_fwd_q8.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, ci, cf, vp, vp, vp]
     lib.qb_qlinear_bwd_ste.restype = ci
     lib.qb_qlinear_bwd_ste.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_quantize_groupwise_asym.restype = ci
+    lib.qb_quantize_groupwise_asym.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
+    lib.qb_qlinear_fwd_asym.restype = ci
+    lib.qb_qlinear_fwd_asym.argtypes = [vp, vp, cf, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_bwd_ste_asym.restype = ci
+    lib.qb_qlinear_bwd_ste_asym.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_bwd_ste_masked.restype = ci
     lib.qb_qlinear_bwd_ste_masked.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.qb_unpack_codes.restype = ci
@@ -253,6 +260,59 @@ def qb_qlinear_bwd_ste_masked(dY, Xq, clip, packed, h, bits, groups, X=None, W=N
         workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
     _check(lib.qb_qlinear_bwd_ste_masked(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
                                          _p(X), _p(W), _p(m), _p(dX), _p(dW), _p(workspace), _stream()))
+    return dX, dW
+
+
+def qb_quantize_groupwise_asym(W, bits, groups, packed=None, delta=None, q0=None, rs_w=None):
+    """Group ranges [min, max]: W[N,K] fp32 -> (packed, delta[G], q0[G], rs_w[N])."""
+    lib = load_library()
+    _dev(W, torch.float32, "W")
+    N, K = W.shape
+    dev = W.device
+    if packed is None:
+        packed = torch.empty(max(qb_packed_nbytes(N, K, bits), 1), dtype=torch.uint8, device=dev)
+    if delta is None:
+        delta = torch.empty(groups, dtype=torch.float32, device=dev)
+    if q0 is None:
+        q0 = torch.empty(groups, dtype=torch.float32, device=dev)
+    if rs_w is None:
+        rs_w = torch.empty(N, dtype=torch.int32, device=dev)
+    _check(lib.qb_quantize_groupwise_asym(_p(W), N, K, bits, groups, _p(packed), _p(delta), _p(q0), _p(rs_w), _stream()))
+    return packed, delta, q0, rs_w
+
+
+def qb_qlinear_fwd_asym(Xq, rs_x, clip, packed, delta, q0, rs_w, bits, groups, N, bias=None, Y=None, want_a4=False):
+    """Forward with asymmetric group ranges. Returns Y[T,N] fp32 (and A4[T,N] int32 if asked)."""
+    lib = load_library()
+    _dev(Xq, torch.int8, "Xq")
+    _dev(delta, torch.float32, "delta")
+    _dev(q0, torch.float32, "q0")
+    T, K = Xq.shape
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=Xq.device)
+    A4 = torch.empty((T, N), dtype=torch.int32, device=Xq.device) if want_a4 else None
+    _check(lib.qb_qlinear_fwd_asym(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(delta), _p(q0), _p(rs_w), bits, groups,
+                                   T, N, K, _p(bias), _p(Y), _p(A4), _stream()))
+    return (Y, A4) if want_a4 else Y
+
+
+def qb_qlinear_bwd_ste_asym(dY, Xq, clip, packed, delta, q0, bits, groups, want_dx=True, want_dw=True, dX=None, dW=None,
+                            workspace=None):
+    """STE backward with asymmetric group ranges: dY[T,N] bf16 -> (dX[T,K] bf16 or None, dW[N,K] fp32 or None)."""
+    lib = load_library()
+    _dev(dY, torch.bfloat16, "dY")
+    _dev(Xq, torch.int8, "Xq")
+    T, N = dY.shape
+    K = Xq.shape[1]
+    dev = dY.device
+    if want_dx and dX is None:
+        dX = torch.empty((T, K), dtype=torch.bfloat16, device=dev)
+    if want_dw and dW is None:
+        dW = torch.empty((N, K), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
+    _check(lib.qb_qlinear_bwd_ste_asym(_p(dY), _p(Xq), float(clip), _p(packed), _p(delta), _p(q0), bits, groups, T, N, K,
+                                       _p(dX), _p(dW), _p(workspace), _stream()))
     return dX, dW
 
 

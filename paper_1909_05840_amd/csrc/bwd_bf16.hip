@@ -29,11 +29,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-// packed slots -> WT[j][n] = bf16(h_g * (2u - L)); one thread per (n, 32-code run); n < Np
+// packed slots -> WT[j][n] = bf16(h_g * (2u - L)), or with asymmetric ranges (q0 given, h holds Delta)
+// bf16(Delta_g * u + q0_g); one thread per (n, 32-code run); n < Np
 template <int BITS>
 __device__ __forceinline__ void dequant_transpose_body(int bx, const uint8_t *__restrict__ packed,
-                                                       const float *__restrict__ h, int N, int Np, int K,
-                                                       int rows_per_group, uint16_t *__restrict__ WT)
+                                                       const float *__restrict__ h, const float *__restrict__ q0, int N,
+                                                       int Np, int K, int rows_per_group, uint16_t *__restrict__ WT)
 {
     const int runs = K >> 5;
     const int64_t id = (int64_t)bx * 256 + threadIdx.x;
@@ -52,6 +53,15 @@ __device__ __forceinline__ void dequant_transpose_body(int bx, const uint8_t *__
     unpack_run<BITS>(in, d);
     const float hg = h[n / rows_per_group];
     constexpr int L = (1 << BITS) - 1;
+    if (q0) {
+        const float z = q0[n / rows_per_group];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const int u = (int)((d[i >> 2] >> (8 * (i & 3))) & 255u);
+            dst[(size_t)i * Np] = f32_to_bf16_rne(hg * (float)u + z);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
         const int u = (int)((d[i >> 2] >> (8 * (i & 3))) & 255u);
@@ -128,7 +138,7 @@ __device__ __forceinline__ void transpose_body(int bx, int by, uint16_t (*tile)[
 // (for dX), the next nb_y blocks transpose dY and the last nb_x blocks transpose-and-convert the activation codes
 // (for dW).  A section with zero blocks is skipped.
 struct StageArgs {
-    const uint8_t *packed; const float *h; int N, Np, K, rows_per_group; uint16_t *WT; int nb_w;
+    const uint8_t *packed; const float *h; const float *q0; int N, Np, K, rows_per_group; uint16_t *WT; int nb_w;
     const uint16_t *dY; int T, Tp; uint16_t *dYT; int nb_y;
     const int8_t *Xq; uint16_t *XT; int nb_x;
 };
@@ -139,7 +149,7 @@ __global__ __launch_bounds__(256) void stage_operands_kernel(const StageArgs a)
     __shared__ uint16_t tile[64][66];
     int b = blockIdx.x;
     if (b < a.nb_w) {
-        dequant_transpose_body<BITS>(b, a.packed, a.h, a.N, a.Np, a.K, a.rows_per_group, a.WT);
+        dequant_transpose_body<BITS>(b, a.packed, a.h, a.q0, a.N, a.Np, a.K, a.rows_per_group, a.WT);
         return;
     }
     b -= a.nb_w;
@@ -477,7 +487,7 @@ extern "C" size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K)
 
 static qb_status bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed, const float *h, int bits,
                          int groups, int64_t T, int64_t N, int64_t K, const float *X, const float *W, const float *m,
-                         uint16_t *dX, float *dW, void *workspace, void *stream)
+                         uint16_t *dX, float *dW, void *workspace, void *stream, const float *q0 = nullptr)
 {
     if (!dY || !Xq || !packed || !h) return QB_ERR_NULL;
     if (!bits_ok(bits)) return QB_ERR_BITS;
@@ -497,7 +507,7 @@ static qb_status bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip, const
     uint16_t *XT = reinterpret_cast<uint16_t *>(ws + p.off_xt);
     {
         StageArgs a;
-        a.packed = static_cast<const uint8_t *>(packed); a.h = h; a.N = (int)N; a.Np = Np; a.K = (int)K; a.rows_per_group = rpg;
+        a.packed = static_cast<const uint8_t *>(packed); a.h = h; a.q0 = q0; a.N = (int)N; a.Np = Np; a.K = (int)K; a.rows_per_group = rpg;
         a.WT = WT; a.nb_w = dX ? (int)(((int64_t)Np * (K / 32) + 255) / 256) : 0;
         a.dY = dY; a.T = (int)T; a.Tp = Tp; a.dYT = dYT; a.nb_y = dW ? (Tp / 64) * (int)((N + 63) / 64) : 0;
         a.Xq = Xq; a.XT = XT; a.nb_x = dW ? (Tp / 64) * (int)((K + 63) / 64) : 0;
@@ -555,4 +565,13 @@ extern "C" qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t 
 {
     if ((W == nullptr) != (m == nullptr)) return QB_ERR_NULL;
     return bwd_ste(dY, Xq, clip, packed, h, bits, groups, T, N, K, X, W, m, dX, dW, workspace, stream);
+}
+
+extern "C" qb_status qb_qlinear_bwd_ste_asym(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
+                                             const float *delta, const float *q0, int bits, int groups, int64_t T,
+                                             int64_t N, int64_t K, uint16_t *dX, float *dW, void *workspace, void *stream)
+{
+    if (!q0) return QB_ERR_NULL;
+    return bwd_ste(dY, Xq, clip, packed, delta, bits, groups, T, N, K, nullptr, nullptr, nullptr, dX, dW, workspace, stream,
+                   q0);
 }

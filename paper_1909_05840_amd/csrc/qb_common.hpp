@@ -123,6 +123,16 @@ struct Quantizer {
         rinv = __fdiv_rn(1.0f, delta);
         fast = delta >= 1.0e-30f && delta <= 1.0e30f;
     }
+    // a general range [lo, lo + L*d] (q0 = lo): code = rint(fl(fl(w - lo) / d)); d = 0 (a constant group) gives
+    // code 0 for every w = lo.  For lo <= w <= hi and d = fl(fl(hi - lo)/L) the quotient stays below L + 1/2.
+    __device__ __forceinline__ void set_range(float lo, float d)
+    {
+        m = -lo;
+        Lf = 0.0f;
+        delta = (d == 0.0f) ? 1.0f : d;
+        rinv = __fdiv_rn(1.0f, delta);
+        fast = delta >= 1.0e-30f && delta <= 1.0e30f;
+    }
     __device__ __forceinline__ float half_step() const { return (m == 0.0f) ? 0.0f : __fdiv_rn(m, Lf); }
     // rint((w + m)/Delta) as a float.  No clamp to [0, L] is needed: |w| <= m gives 0 <= s <= 2m(1+2^-24),
     // so 0 <= t <= L(1+2^-23) and rint(t) is already in 0..L (callers clamp activations to [-m, m] first).

@@ -35,14 +35,24 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
+// Asymmetric group ranges (weights Delta*u + q0, u = 0..L): with R = sum_j (2x'+1) = 2*rs_x + K and
+// S = sum_j (2x'+1)*u = (A4 + L*R)/2 the output is h_x*(Delta*S + q0*R).  A4 and R are even (K is), and
+// S = A4/2 + L*(R/2) stays inside int32 for every K the library accepts.  rh = R/2 = rs_x + K/2.
+__device__ __forceinline__ float asym_value(int a4, int rh, int L, float hx, float delta, float q0)
+{
+    const int S = (a4 >> 1) + L * rh;
+    return hx * (delta * (float)S + q0 * (float)(2 * rh));
+}
+
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
 __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
-    int tiles_m, int tiles_n, const float *__restrict__ hx_rows)
+    int tiles_m, int tiles_n, const float *__restrict__ hx_rows, const float *__restrict__ q0)
 {
     // hx_rows: one activation scale per token (dynamic range) instead of hx, or null
+    // q0: asymmetric group ranges: h holds Delta and q0 the lower end of every group, or null
     constexpr int THREADS = 64 * WM * WN;
     constexpr bool QB_SKIP_STORES = false;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64 * KU, LDA = BK + 16;
@@ -195,6 +205,18 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
                 if (sum == 0x12345678) Y[0] = 1.0f;
+            } else if (q0) {
+                const float zn = q0[nn / rows_per_group];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int t = t0 + 8 * (i >> 2) + (i & 3);
+                    if (t < T && n_ok) {
+                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                        const size_t at = (size_t)t * N + n;
+                        Y[at] = asym_value(a4, rs_x[t] + (K >> 1), L, hx, hg, zn) + bv;
+                        if (A4out) A4out[at] = a4;
+                    }
+                }
             } else if (hx_rows) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -593,7 +615,8 @@ __device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_addr)
 template <int BM, int BN>
 __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *pp, int e2, int tl, int nl, int t0, int n0,
                                                 int T, int N, int K, float hx, bool has_bias, bool fast,
-                                                float *__restrict__ Y, int32_t *__restrict__ A4out, bool dyn = false)
+                                                float *__restrict__ Y, int32_t *__restrict__ A4out, bool dyn = false,
+                                                int asym_L = 0)
 {
     // one 32x32 block: acc[r] is token tl + 8*(r/4) + (r%4) of the tile, neuron nl
     const int *p_rx = reinterpret_cast<const int *>(pp);
@@ -629,6 +652,22 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
         rx[4 * q + 2] = qb_mad24(e2, v.z, coln);
         rx[4 * q + 3] = qb_mad24(e2, v.w, coln);
     }
+    if (asym_L) {  // asymmetric group ranges: Delta in the place of h, q0 in the place of the per-token scales
+        const float dn = p_h[nl], zn = (p_b + BN)[nl];
+        const bool n_ok = n0 + nl < N;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = tl + 8 * (r >> 2) + (r & 3);
+            const int t = t0 + row;
+            if (n_ok && t < T) {
+                const int a4 = 4 * acc[r] + rx[r];
+                const size_t at = (size_t)t * N + n0 + nl;
+                Y[at] = asym_value(a4, p_rx[row] + (K >> 1), asym_L, hx, dn, zn) + bv;
+                if (A4out) A4out[at] = a4;
+            }
+        }
+        return;
+    }
     if (fast) {
         char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
 #pragma unroll
@@ -658,6 +697,8 @@ struct OutQ {
     float clip_out;   // range [-clip_out, +clip_out]
     int act;          // 0 none, 1 GELU
     const float *hx_rows;  // fp32 output only: one activation scale per token (dynamic range) instead of hx, or null
+    const float *q0;       // fp32 output only: asymmetric group ranges (h holds Delta, q0 the lower ends), or null;
+                           // not together with hx_rows (its values take the same place in the parameter block)
 };
 
 // One 32x32 block of the 8-bit output: the value that decides the code is formed in binary32 with one
@@ -728,13 +769,16 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
 // OUTQ: instead of Y the tile is quantized to 8 bits (quant_block_lds) into an LDS staging tile and, after one
 // more barrier per tile (E, executed by the producers once the next tile's first copies are on their way), written
 // out in whole rows; the rows' sums are collected in LDS and added to rs_y one tile later.
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, bool OUTQ>
+// OUT: 0 fp32 Y, 1 the 8-bit output (OUTQ), 2 fp32 Y from asymmetric group ranges (ASYM; a variant of its own so
+// that the others carry none of its code)
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, int OUT>
 __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
     int tiles_m, int tiles_n, OutQ oq)
 {
+    constexpr bool OUTQ = OUT == 1, ASYM = OUT == 2;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
     constexpr int NC = WM * WN;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 128;
@@ -749,9 +793,11 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int PERP = A_PER + B_PER;             // per producer and step
     constexpr int D = NSTAGE - 1;
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
-    static_assert((D - 1) * PERP + 2 * (BM / 64) + 3 * ((BN + 63) / 64) < 64, "vmcnt has six bits");
+    static_assert((D - 1) * PERP + 2 * (BM / 64) + 4 * ((BN + 63) / 64) < 64, "vmcnt has six bits");
     constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
     constexpr int PARAM_BYTES = (2 * BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias | per-token scales
+                                                         // (or, in their place, q0 of the neuron's group)
+    static_assert(BNP <= BM, "the per-neuron q0 values take the place of the per-token scales");
     static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
 
     // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
@@ -848,6 +894,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                     copy4_to_lds(rs_w + n, pbase + BM * 4 + c * 256);
                     copy4_to_lds(h + n / rows_per_group, pbase + (BM + BNP) * 4 + c * 256);
                     if (bias) copy4_to_lds(bias + n, pbase + (BM + 2 * BNP) * 4 + c * 256);
+                    if constexpr (ASYM) copy4_to_lds(oq.q0 + n / rows_per_group, pbase + (BM + 3 * BNP) * 4 + c * 256);
                 }
             }
             pb ^= 1;
@@ -859,9 +906,10 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
             // that issued them, the parameter copies (their number depends on bias and per-token scales)
             if (nsteps >= D) {
                 constexpr int W0 = (D - 1) * PERP, PM = BM / 64, PN = BNP / 64;
+                constexpr int PA = ASYM ? PN : 0;
                 if (p != 0) wait_vmcnt<W0>();
-                else if (oq.hx_rows) { if (bias) wait_vmcnt<W0 + 2 * PM + 3 * PN>(); else wait_vmcnt<W0 + 2 * PM + 2 * PN>(); }
-                else { if (bias) wait_vmcnt<W0 + PM + 3 * PN>(); else wait_vmcnt<W0 + PM + 2 * PN>(); }
+                else if (oq.hx_rows) { if (bias) wait_vmcnt<W0 + 2 * PM + 3 * PN + PA>(); else wait_vmcnt<W0 + 2 * PM + 2 * PN + PA>(); }
+                else { if (bias) wait_vmcnt<W0 + PM + 3 * PN + PA>(); else wait_vmcnt<W0 + PM + 2 * PN + PA>(); }
             } else {
                 wait_vmcnt<0>();
             }
@@ -1058,7 +1106,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
             for (int tn = 0; tn < TN; ++tn)
                 store_block_lds<BM, BNP>(acc[tm][tn], lds + NSTAGE * STAGE_BYTES + pb * PARAM_BYTES, E2,
                                         (wm * TM + tm) * 32 + 4 * hf, (wn * TN + tn) * 32 + l32, tile_m * BM, tile_n * BN,
-                                        T, N, K, hx, bias != nullptr, fast, Y, A4out, oq.hx_rows != nullptr);
+                                        T, N, K, hx, bias != nullptr, fast, Y, A4out, oq.hx_rows != nullptr,
+                                        ASYM ? L : 0);
         }
         pb ^= 1;
     }
@@ -1075,15 +1124,21 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
 void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
-               int grid_cap, const float *hx_rows = nullptr)
+               int grid_cap, const float *hx_rows = nullptr, const float *q0 = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, false>), dim3(grid),
-                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                       tiles_m, tiles_n, OutQ{nullptr, nullptr, 1.0f, 0, hx_rows});
+    const OutQ oq{nullptr, nullptr, 1.0f, 0, hx_rows, q0};
+    if (q0)
+        hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 2>), dim3(grid),
+                           dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
+                           tiles_m, tiles_n, oq);
+    else
+        hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 0>), dim3(grid),
+                           dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
+                           tiles_m, tiles_n, oq);
 }
 
 // the same with the 8-bit output
@@ -1095,7 +1150,7 @@ void launch_ws_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, 
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, true>), dim3(grid),
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 1>), dim3(grid),
                        dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, nullptr, nullptr, T, N, K, rpg,
                        hx, tiles_m, tiles_n, oq);
 }
@@ -1103,12 +1158,12 @@ void launch_ws_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, 
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
 void launch_cfg(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                 const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
-                const float *hx_rows = nullptr)
+                const float *hx_rows = nullptr, const float *q0 = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     hipLaunchKernelGGL((qgemm_i8_kernel<BITS, TM, TN, WM, WN, KU>), dim3(tiles_m * tiles_n), dim3(64 * WM * WN), 0, st,
-                       Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n, hx_rows);
+                       Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n, hx_rows, q0);
 }
 
 // grid_cap: upper bound of workgroups (a multiple of 8); 0 = one workgroup per tile
@@ -1128,7 +1183,7 @@ void launch_dma(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, co
 template <int BITS>
 void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                  const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
-                 const float *hx_rows = nullptr)
+                 const float *hx_rows = nullptr, const float *q0 = nullptr)
 {
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     if (tiles128 <= 160) {
@@ -1136,13 +1191,13 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
         // and pay ~6.5 us at least; 32x64 tiles of the register-staged kernel spread the work over the chip
         // (measured 4.4-5 us against 8 at T <= 1024, N = 768; 6.8 against 8.4 at 1024 x 2304 x 768; equal
         // at about 190 tiles).  Long contractions take 256 features per step.
-        if (K % 256 == 0 && K >= 2048) launch_cfg<BITS, 1, 1, 1, 2, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
-        else if (K % 128 == 0) launch_cfg<BITS, 1, 1, 1, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
-        else launch_cfg<BITS, 1, 1, 1, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
+        if (K % 256 == 0 && K >= 2048) launch_cfg<BITS, 1, 1, 1, 2, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows, q0);
+        else if (K % 128 == 0) launch_cfg<BITS, 1, 1, 1, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows, q0);
+        else launch_cfg<BITS, 1, 1, 1, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows, q0);
         return;
     }
     if (K % 128 != 0) {  // odd number of 64-feature units: register-staged kernel, one unit per step
-        launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows);
+        launch_cfg<BITS, 2, 2, 2, 2, 1>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, hx_rows, q0);
         return;
     }
     // Tile choice (measured on BERT-base and BERT-large shapes).  Copies issued on a SIMD that is busy
@@ -1159,9 +1214,9 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
     if (86 * rounds96 < 100 * rounds128)
-        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows);
-    else if (hx_rows || tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))  // (per-token scales: role-split kernels only)
-        launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows);
+        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows, q0);
+    else if (hx_rows || q0 || tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))  // (per-token scales, asymmetric ranges: role-split kernels only)
+        launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows, q0);
     else
         launch_dma<BITS, 2, 2, 2, 2, 2>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512);
 }
@@ -1338,6 +1393,29 @@ extern "C" qb_status qb_qlinear_fwd_dyn(const int8_t *Xq, const int32_t *rs_x, c
         case 3: launch_bits<3>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
         case 4: launch_bits<4>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
         default: launch_bits<8>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows); break;
+    }
+    return launch_status();
+}
+
+extern "C" qb_status qb_qlinear_fwd_asym(const int8_t *Xq, const int32_t *rs_x, float clip, const void *packed,
+                                         const float *delta, const float *q0, const int32_t *rs_w, int bits, int groups,
+                                         int64_t T, int64_t N, int64_t K, const float *bias, float *Y, int32_t *A4_debug,
+                                         void *stream)
+{
+    if (!Xq || !rs_x || !packed || !delta || !q0 || !rs_w || !Y) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0)
+        return QB_ERR_SHAPE;
+    if (!(clip > 0.0f) || !(clip < 3.0e38f)) return QB_ERR_CLIP;
+    const int rpg = (int)(N / groups);
+    const float hx = clip / 255.0f;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    switch (bits) {
+        case 2: launch_bits<2>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
+        case 3: launch_bits<3>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
+        case 4: launch_bits<4>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
+        default: launch_bits<8>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
     }
     return launch_status();
 }

@@ -32,7 +32,8 @@ __device__ __forceinline__ int fast_div(int e, int d, float inv)
 // group.  FUSED: the panel is the whole group, max-abs is found here and m/h are written.
 // Otherwise m was found by absmax_slices_kernel and only the panel starting a group writes h.
 // LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then THREADS/64 floats.
-template <int BITS, int THREADS, int V, bool FUSED>
+// ASYM (with !FUSED): the group's range is [m[g], m[g] + L*h[g]], found before (q0 in m, Delta in h; both read only).
+template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
 __device__ __forceinline__ void quantize_panel_body(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
     uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
@@ -74,12 +75,13 @@ __device__ __forceinline__ void quantize_panel_body(
         __syncthreads();
     }
     Quantizer qz;
-    qz.set(mg, Lf);
-    if (tid == 0 && row0 % rows_per_group == 0) {
+    if constexpr (ASYM) qz.set_range(mg, h[g]);
+    else qz.set(mg, Lf);
+    if (!ASYM && tid == 0 && row0 % rows_per_group == 0) {
         h[g] = qz.half_step();
         if (FUSED) m[g] = mg;
     }
-    if (!FUSED) {  // the range was given: it may be smaller than the group's max-abs (clipped range)
+    if (!FUSED && !ASYM) {  // the range was given: it may be smaller than the group's max-abs (clipped range)
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             v[i].x = __builtin_amdgcn_fmed3f(v[i].x, -mg, mg);
@@ -134,14 +136,76 @@ __device__ __forceinline__ void quantize_panel_body(
     for (int r = tid; r < prow; r += THREADS) rs_w[row0 + r] = rowsum[r] - K * (1 << (BITS - 1));
 }
 
-template <int BITS, int THREADS, int V, bool FUSED>
+template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
 __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
     uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    quantize_panel_body<BITS, THREADS, V, FUSED>(W, K, rows_per_group, prow, inv_K, inv_prow, packed, h, m, rs_w,
-                                                 blockIdx.x, smem);
+    quantize_panel_body<BITS, THREADS, V, FUSED, ASYM>(W, K, rows_per_group, prow, inv_K, inv_prow, packed, h, m, rs_w,
+                                                       blockIdx.x, smem);
+}
+
+// ---- asymmetric ranges: min and max of every group.  Floats are mapped to unsigned keys that order like the
+// floats (sign bit flipped for non-negative values, all bits flipped for negative ones), so that slices of a
+// group combine through integer atomic max / min.  hi_key must start at 0, lo_key at 0xffffffff.
+__device__ __forceinline__ uint32_t float_key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+__global__ void range_init_kernel(uint32_t *hi_key, uint32_t *lo_key, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        hi_key[i] = 0u;
+        lo_key[i] = 0xffffffffu;
+    }
+}
+__global__ __launch_bounds__(256) void minmax_slices_kernel(const float *__restrict__ W, int64_t group_elems, int slices,
+                                                            uint32_t *__restrict__ hi_key, uint32_t *__restrict__ lo_key)
+{
+    __shared__ float red[8];
+    const int g = blockIdx.x / slices, s = blockIdx.x % slices;
+    const int64_t n4 = group_elems >> 2;
+    const int64_t per = (n4 + slices - 1) / slices;
+    const int64_t lo = (int64_t)s * per, hi = (lo + per < n4) ? lo + per : n4;
+    const float4 *src = reinterpret_cast<const float4 *>(W + (int64_t)g * group_elems);
+    if (lo >= hi) return;  // (uniform per workgroup)
+    float mx = src[lo].x, mn = mx;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
+        const float4 v = src[i];
+        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+        mn = fminf(fminf(mn, fminf(v.x, v.y)), fminf(v.z, v.w));
+    }
+    mx = wave_max(mx);
+    mn = -wave_max(-mn);
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6] = mx;
+        red[4 + (threadIdx.x >> 6)] = mn;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        mn = fminf(fminf(red[4], red[5]), fminf(red[6], red[7]));
+        atomicMax(hi_key + g, float_key(mx));
+        atomicMin(lo_key + g, float_key(mn));
+    }
+}
+// keys -> q0 = min and Delta = fl(fl(max - min)/L), in place
+__global__ void range_finish_kernel(float *delta, float *q0, int n, float L)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const float hi = key_float(reinterpret_cast<const uint32_t *>(delta)[i]);
+        const float lo = key_float(reinterpret_cast<const uint32_t *>(q0)[i]);
+        delta[i] = __fdiv_rn(__fsub_rn(hi, lo), L);
+        q0[i] = lo;
+    }
 }
 
 constexpr int kMaxFusedElems = 1024 * 4 * 8;  // one group in the registers of 1024 threads, 8 float4 each
@@ -522,12 +586,12 @@ __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__
 }
 
 
-template <int BITS, int THREADS>
+template <int BITS, int THREADS, bool ASYM = false>
 void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h, float *m,
                   int32_t *rs_w, hipStream_t st)
 {
     const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 64;
-    hipLaunchKernelGGL((quantize_panel_kernel<BITS, THREADS, 8, false>), dim3(panels), dim3(THREADS), lds, st, W, K,
+    hipLaunchKernelGGL((quantize_panel_kernel<BITS, THREADS, 8, false, ASYM>), dim3(panels), dim3(THREADS), lds, st, W, K,
                        rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w);
 }
 
@@ -568,12 +632,52 @@ qb_status quantize_given_range(const float *W, int64_t N, int64_t K, int groups,
     return launch_status();
 }
 
+// asymmetric ranges: keys, min/max by slices, Delta and q0, then the panels
+template <int BITS>
+qb_status quantize_asym(const float *W, int64_t N, int64_t K, int groups, uint8_t *packed, float *delta, float *q0,
+                        int32_t *rs_w, hipStream_t st)
+{
+    const int rpg = (int)(N / groups);
+    const int64_t gelems = (int64_t)rpg * K;
+    int prow = 1;
+    for (int p = rpg; p >= 1; --p)
+        if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
+    const int slices = (int)((gelems + 65535) / 65536);
+    const dim3 gg((groups + 255) / 256);
+    hipLaunchKernelGGL(range_init_kernel, gg, dim3(256), 0, st, reinterpret_cast<uint32_t *>(delta),
+                       reinterpret_cast<uint32_t *>(q0), groups);
+    hipLaunchKernelGGL(minmax_slices_kernel, dim3(groups * slices), dim3(256), 0, st, W, gelems, slices,
+                       reinterpret_cast<uint32_t *>(delta), reinterpret_cast<uint32_t *>(q0));
+    hipLaunchKernelGGL(range_finish_kernel, gg, dim3(256), 0, st, delta, q0, groups, (float)((1 << BITS) - 1));
+    const int64_t pelems = (int64_t)prow * K;
+    if (pelems <= 8192) launch_panel<BITS, 256, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st);
+    else if (pelems <= 16384) launch_panel<BITS, 512, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st);
+    else launch_panel<BITS, 1024, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st);
+    return launch_status();
+}
+
 }  // namespace
 }  // namespace qb
 
 using namespace qb;
 
 extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
+
+extern "C" qb_status qb_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, int groups, void *packed,
+                                                float *delta, float *q0, int32_t *rs_w, void *stream)
+{
+    if (!W || !packed || !delta || !q0 || !rs_w) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *p = static_cast<uint8_t *>(packed);
+    switch (bits) {
+        case 2: return quantize_asym<2>(W, N, K, groups, p, delta, q0, rs_w, st);
+        case 3: return quantize_asym<3>(W, N, K, groups, p, delta, q0, rs_w, st);
+        case 4: return quantize_asym<4>(W, N, K, groups, p, delta, q0, rs_w, st);
+        default: return quantize_asym<8>(W, N, K, groups, p, delta, q0, rs_w, st);
+    }
+}
 
 extern "C" qb_status qb_quantize_groupwise_clip(const float *W, int64_t N, int64_t K, int bits, int groups, const float *m_in,
                                                 void *packed, float *h, int32_t *rs_w, void *stream)

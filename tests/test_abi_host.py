@@ -117,6 +117,18 @@ def test_invalid_arguments_are_refused_on_the_host(lib):
     # quantize_act_dyn(X,T,K,Xq,rs_x,hx,stream), qlinear_fwd_dyn(Xq,rs_x,hx,packed,h,rs_w,bits,groups,T,N,K,bias,Y,A4,stream)
     assert lib.qb_quantize_act_dyn(P, 16, 64, P, P, NULL, NULL) == 1
     assert lib.qb_quantize_act_dyn(P, 16, 65, P, P, P, NULL) == 3
+    # quantize_groupwise_asym(W,N,K,bits,groups,packed,delta,q0,rs_w,stream)
+    assert lib.qb_quantize_groupwise_asym(P, 768, 768, 4, 128, P, P, NULL, P, NULL) == 1
+    assert lib.qb_quantize_groupwise_asym(P, 768, 768, 7, 128, P, P, P, P, NULL) == 2
+    assert lib.qb_quantize_groupwise_asym(P, 768, 768, 4, 100, P, P, P, P, NULL) == 3
+    # qlinear_fwd_asym(Xq,rs_x,clip,packed,delta,q0,rs_w,bits,groups,T,N,K,bias,Y,A4,stream)
+    assert lib.qb_qlinear_fwd_asym(P, P, f(6.0), P, P, NULL, P, 4, 128, 16, 768, 768, NULL, P, NULL, NULL) == 1
+    assert lib.qb_qlinear_fwd_asym(P, P, f(6.0), P, P, P, P, 5, 128, 16, 768, 768, NULL, P, NULL, NULL) == 2
+    assert lib.qb_qlinear_fwd_asym(P, P, f(6.0), P, P, P, P, 4, 128, 16, 768, 800, NULL, P, NULL, NULL) == 3
+    assert lib.qb_qlinear_fwd_asym(P, P, f(-1.0), P, P, P, P, 4, 128, 16, 768, 768, NULL, P, NULL, NULL) == 4
+    # qlinear_bwd_ste_asym(dY,Xq,clip,packed,delta,q0,bits,groups,T,N,K,dX,dW,workspace,stream)
+    assert lib.qb_qlinear_bwd_ste_asym(P, P, f(6.0), P, P, NULL, 4, 128, 16, 768, 768, P, P, P, NULL) == 1
+    assert lib.qb_qlinear_bwd_ste_asym(P, P, f(6.0), P, P, P, 4, 128, 16, 768, 768, P, P, NULL, NULL) == 5
     # quantize_act_dyn_tensor(X,T,K,Xq,rs_x,hx,c,stream)
     assert lib.qb_quantize_act_dyn_tensor(P, 16, 64, P, P, P, NULL, NULL) == 1
     assert lib.qb_quantize_act_dyn_tensor(P, 0, 64, P, P, P, P, NULL) == 3

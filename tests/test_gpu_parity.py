@@ -679,3 +679,102 @@ def test_runs_are_deterministic(qb):
     for o in outs[1:]:
         for a, b in zip(outs[0], o):
             assert torch.equal(a, b)
+
+
+# ---- asymmetric group ranges --------------------------------------------------------------------------------------------
+def shifted_weight(N, K, G, seed):
+    """Groups with their own offsets: one-sided, shifted and near-symmetric ones, one constant group."""
+    W = wl.weight(N, K, seed=seed)
+    rows = N // G
+    for g in range(G):
+        blk = W[g * rows:(g + 1) * rows]
+        if g % 4 == 0:
+            blk.abs_()                       # one-sided
+        elif g % 4 == 1:
+            blk += 0.07 * (g % 5 + 1)        # shifted
+        elif g % 4 == 2 and g > 2:
+            blk.fill_(0.03125)               # constant
+    return W.contiguous()
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(768, 768, 128), (2304, 768, 12), (768, 3072, 128), (6, 64, 6), (40, 192, 8), (1030, 64, 1),
+                                   (4096, 1024, 2)])
+def test_quantize_asymmetric_ranges(qb, bits, shape):
+    """Codes, Delta and q0 (bit patterns) and row sums against the oracle; groups in one panel and groups split over
+    panels and slices; a second call into the same buffers."""
+    N, K, G = shape
+    say("quantize asym", shape, "bits", bits)
+    W = shifted_weight(N, K, G, seed=N + K + bits)
+    packed, delta, q0, rs = qb.qb_quantize_groupwise_asym(W.to(DEV), bits, G)
+    codes = qb.qb_unpack_codes(packed, N, K, bits)
+    torch.cuda.synchronize()
+    oc, od, oq0, ors = oracle.quantize_groupwise_asym(W.numpy(), bits, G)
+    assert (delta.cpu().numpy().view(np.uint32) == od.view(np.uint32)).all()
+    assert (q0.cpu().numpy() == oq0).all()
+    assert (codes.cpu().numpy() == oc).all()
+    assert (rs.cpu().numpy() == ors).all()
+    W2 = (-0.5 * W).contiguous()
+    qb.qb_quantize_groupwise_asym(W2.to(DEV), bits, G, packed, delta, q0, rs)
+    codes = qb.qb_unpack_codes(packed, N, K, bits)
+    torch.cuda.synchronize()
+    oc, od, oq0, ors = oracle.quantize_groupwise_asym(W2.numpy(), bits, G)
+    assert (delta.cpu().numpy().view(np.uint32) == od.view(np.uint32)).all() and (q0.cpu().numpy() == oq0).all()
+    assert (codes.cpu().numpy() == oc).all() and (rs.cpu().numpy() == ors).all()
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(300, 160, 192, 8), (1, 32, 64, 1), (129, 130, 320, 10), (513, 768, 768, 128), (64, 6, 128, 6),
+                                   (2048, 1024, 128, 128), (2304, 1536, 128, 128), (4096, 768, 256, 128), (100, 96, 2048, 96)])
+def test_forward_asymmetric_ranges(qb, bits, shape):
+    """Y against the oracle within 1e-6 of h_x*(Delta*|S| + |q0|*|R|) (the two products that are added), A4 bit for
+    bit; through the register-staged kernel (few tiles, K not a multiple of 128) and both role-split layouts; ragged
+    T and N; with bias."""
+    T, N, K, G = shape
+    say("fwd asym", shape, "bits", bits)
+    W = shifted_weight(N, K, G, seed=3 * N + K + bits)
+    X = wl.activation(T, K, seed=T + K + bits)
+    bias = (0.3 * wl.activation(1, N, seed=11)[0]).contiguous()
+    packed, delta, q0, rs_w = qb.qb_quantize_groupwise_asym(W.to(DEV), bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    oc, od, oq0, _ = oracle.quantize_groupwise_asym(W.numpy(), bits, G)
+    oq, ors_x = oracle.quantize_act(X.numpy(), CLIP)
+    Yo, S = oracle.qlinear_fwd_asym(oq, CLIP, oc, od, oq0, want_s=True, openmp=True)
+    L = 2 ** bits - 1
+    R = (2 * ors_x.astype(np.int64) + K)[:, None]
+    rows = N // G
+    dn = np.repeat(od.astype(np.float64), rows)[None, :]
+    zn = np.repeat(oq0.astype(np.float64), rows)[None, :]
+    bound = 1e-6 * (CLIP / 255.0) * (dn * np.abs(S) + np.abs(zn) * np.abs(R))
+    for b in (None, bias):
+        Y, A4 = qb.qb_qlinear_fwd_asym(Xq, rs_x, CLIP, packed, delta, q0, rs_w, bits, G, N,
+                                       bias=None if b is None else b.to(DEV), want_a4=True)
+        torch.cuda.synchronize()
+        assert (A4.cpu().numpy().astype(np.int64) == 2 * S - L * R).all()
+        ref = Yo.astype(np.float64) if b is None else oracle.qlinear_fwd_asym(oq, CLIP, oc, od, oq0, bias=b.numpy(), openmp=True)
+        extra = 0 if b is None else 1e-6 * np.abs(b.numpy())[None, :]
+        assert (np.abs(Y.cpu().numpy().astype(np.float64) - ref) <= bound + extra + 1e-30).all()
+        Y2 = qb.qb_qlinear_fwd_asym(Xq, rs_x, CLIP, packed, delta, q0, rs_w, bits, G, N, bias=None if b is None else b.to(DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, Y)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("shape", [(300, 160, 192, 8), (513, 768, 768, 128), (1000, 96, 320, 96)])
+def test_backward_asymmetric_ranges(qb, bits, shape):
+    T, N, K, G = shape
+    say("bwd asym", shape, "bits", bits)
+    W = shifted_weight(N, K, G, seed=N + K + bits)
+    X = wl.activation(T, K, seed=T + bits)
+    dY = wl.grad_output_bf16(T, N, seed=T + N)
+    packed, delta, q0, rs_w = qb.qb_quantize_groupwise_asym(W.to(DEV), bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    dX, dW = qb.qb_qlinear_bwd_ste_asym(dY.to(DEV), Xq, CLIP, packed, delta, q0, bits, G)
+    torch.cuda.synchronize()
+    oc, od, oq0, _ = oracle.quantize_groupwise_asym(W.numpy(), bits, G)
+    oq, _ = oracle.quantize_act(X.numpy(), CLIP)
+    odX = oracle.qlinear_bwd_dx_asym(wl.bf16_bits(dY), oc, od, oq0, openmp=True)
+    _, odW = oracle.qlinear_bwd_ste(wl.bf16_bits(dY), oq, CLIP, oc, np.ones(G, np.float32), bits, want_dx=False, openmp=True)
+    assert rel_fro(dX.float().cpu().numpy(), odX) <= 2e-2
+    assert rel_fro(dW.cpu().numpy(), odW) <= 1e-4
+
