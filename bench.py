@@ -258,6 +258,7 @@ def main():
         out["shapes"] = per_shape(torch, qb, wl, dev)
         out["q8_output"] = q8_output_leg(torch, qb, wl, dev)
         out["dynamic_range"] = dynamic_range_leg(torch, qb, wl, dev)
+        out["asymmetric_ranges"] = asymmetric_leg(torch, qb, wl, dev)
         out["backward"] = backward_leg(torch, qb, wl, dev)
         out["embedding"] = embedding_leg(torch, qb, wl, dev)
     if not args.no_cpu_baseline:
@@ -379,6 +380,27 @@ def dynamic_range_leg(torch, qb, wl, dev):
         res.append({"linear": name, "act_quant_us": round(sa * 1e6, 2), "act_quant_dyn_us": round(sad * 1e6, 2),
                     "act_quant_dyn_tensor_us": round(sat * 1e6, 2),
                     "fwd_us": round(sf * 1e6, 2), "fwd_dyn_us": round(sfd * 1e6, 2)})
+        del W, X, Y, Xq
+    return res
+
+
+def asymmetric_leg(torch, qb, wl, dev):
+    """Asymmetric group ranges [min, max]: quantize/pack and the forward next to the symmetric calls (4 bits, T = 4096)."""
+    res = []
+    for (name, N, K) in wl.BERT_BASE_LINEARS:
+        T, b = T_TOKENS, 4
+        W = wl.weight(N, K, seed=N + K).to(dev)
+        X = wl.activation(T, K, seed=T + K).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        pa, delta, q0, rs_a = qb.qb_quantize_groupwise_asym(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        Y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        sq = time_launches(torch, lambda: qb.qb_quantize_groupwise(W, b, GROUPS, packed, h, m, rs_w))
+        sqa = time_launches(torch, lambda: qb.qb_quantize_groupwise_asym(W, b, GROUPS, pa, delta, q0, rs_a))
+        sf = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        sfa = time_launches(torch, lambda: qb.qb_qlinear_fwd_asym(Xq, rs_x, CLIP, pa, delta, q0, rs_a, b, GROUPS, N, Y=Y))
+        res.append({"linear": name, "quantize_us": round(sq * 1e6, 2), "quantize_asym_us": round(sqa * 1e6, 2),
+                    "fwd_us": round(sf * 1e6, 2), "fwd_asym_us": round(sfa * 1e6, 2)})
         del W, X, Y, Xq
     return res
 

@@ -654,16 +654,33 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
     }
     if (asym_L) {  // asymmetric group ranges: Delta in the place of h, q0 in the place of the per-token scales
         const float dn = p_h[nl], zn = (p_b + BN)[nl];
-        const bool n_ok = n0 + nl < N;
+        int rh[16];  // R/2 = rs_x + K/2 per row
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = tl + 8 * (r >> 2) + (r & 3);
-            const int t = t0 + row;
-            if (n_ok && t < T) {
+        for (int q = 0; q < 4; ++q) {
+            const int4 v = *reinterpret_cast<const int4 *>(p_rx + tl + 8 * q);
+            rh[4 * q + 0] = v.x + (K >> 1);
+            rh[4 * q + 1] = v.y + (K >> 1);
+            rh[4 * q + 2] = v.z + (K >> 1);
+            rh[4 * q + 3] = v.w + (K >> 1);
+        }
+        if (fast) {
+            char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
                 const int a4 = 4 * acc[r] + rx[r];
-                const size_t at = (size_t)t * N + n0 + nl;
-                Y[at] = asym_value(a4, p_rx[row] + (K >> 1), asym_L, hx, dn, zn) + bv;
-                if (A4out) A4out[at] = a4;
+                __builtin_nontemporal_store(asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv,
+                                            reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
+            }
+        } else if (n0 + nl < N) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = t0 + tl + 8 * (r >> 2) + (r & 3);
+                if (t < T) {
+                    const int a4 = 4 * acc[r] + rx[r];
+                    const size_t at = (size_t)t * N + n0 + nl;
+                    Y[at] = asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv;
+                    if (A4out) A4out[at] = a4;
+                }
             }
         }
         return;
