@@ -155,6 +155,53 @@ def test_hip_graph_replays_match_eager(qb):
             assert torch.equal(Y2, Y_eager)
 
 
+def test_hip_graph_replays_of_range_variants_and_backward(qb):
+    """The entry points that clear or initialise device scratch themselves (per-tensor dynamic range, asymmetric ranges)
+    and the backward, captured in one graph: every replay, with the outputs and scratch overwritten and eager work in
+    between, gives the eager result."""
+    T, N, K, G, bits = 640, 768, 768, 128, 3
+    W = wl.weight(N, K, seed=31).abs().contiguous().to(DEV)
+    X = wl.activation(T, K, seed=32).to(DEV)
+    dY = wl.grad_output_bf16(T, N, seed=33).to(DEV)
+    clip = 1.5
+    e_xq, e_rs, e_hx, e_c = [t.clone() for t in qb.qb_quantize_act_dyn_tensor(X)]
+    e_p, e_d, e_q0, e_rw = [t.clone() for t in qb.qb_quantize_groupwise_asym(W, bits, G)]
+    Xq, rs_x = qb.qb_quantize_act(X, clip)
+    e_Y = qb.qb_qlinear_fwd_asym(Xq, rs_x, clip, e_p, e_d, e_q0, e_rw, bits, G, N).clone()
+    e_dX, e_dW = [t.clone() for t in qb.qb_qlinear_bwd_ste_asym(dY, Xq, clip, e_p, e_d, e_q0, bits, G)]
+    e_mX, _ = qb.qb_qlinear_bwd_ste_masked(dY, Xq, clip, e_p, e_d, bits, G, X=X, want_dw=False)
+    e_mX = e_mX.clone()
+    torch.cuda.synchronize()
+    xq, rs, hx, c = [torch.empty_like(t) for t in (e_xq, e_rs, e_hx, e_c)]
+    p, d, q0, rw = [torch.empty_like(t) for t in (e_p, e_d, e_q0, e_rw)]
+    Y, dX, dW, mX = [torch.empty_like(t) for t in (e_Y, e_dX, e_dW, e_mX)]
+    ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=DEV)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            qb.qb_quantize_act_dyn_tensor(X, xq, rs, hx, c)
+            qb.qb_quantize_groupwise_asym(W, bits, G, p, d, q0, rw)
+            qb.qb_qlinear_fwd_asym(Xq, rs_x, clip, p, d, q0, rw, bits, G, N, Y=Y)
+            qb.qb_qlinear_bwd_ste_asym(dY, Xq, clip, p, d, q0, bits, G, dX=dX, dW=dW, workspace=ws)
+            qb.qb_qlinear_bwd_ste_masked(dY, Xq, clip, p, d, bits, G, X=X, want_dw=False, dX=mX, workspace=ws)
+        for rep in range(3):
+            for t in (xq, rs, hx, p, rw, Y, dX, dW, mX, ws):
+                t.zero_()
+            c.fill_(1.0e30)     # the reduction's scratch: cleared by the call on every replay
+            d.fill_(7.0)
+            q0.fill_(-7.0)
+            stream.synchronize()
+            g.replay()
+            stream.synchronize()
+            for a, b in ((xq, e_xq), (rs, e_rs), (hx, e_hx), (c, e_c), (p, e_p), (d, e_d), (q0, e_q0), (rw, e_rw), (Y, e_Y),
+                         (dX, e_dX), (dW, e_dW), (mX, e_mX)):
+                assert torch.equal(a, b), rep
+            Y2 = qb.qb_qlinear_fwd_asym(Xq, rs_x, clip, e_p, e_d, e_q0, e_rw, bits, G, N)   # eager work between replays
+            stream.synchronize()
+            assert torch.equal(Y2, e_Y)
+
+
 # ---- activations ---------------------------------------------------------------------------------
 @pytest.mark.parametrize("shape", [(1024, 768), (4096, 768), (4096, 3072), (1, 64), (1023, 768), (7, 1024), (130, 4096)])
 def test_quantize_act(qb, shape):
