@@ -367,3 +367,34 @@ def qlinear_bwd_dx_asym(dY_bf16, codes, delta, q0, openmp=False):
                                                 _I64(T), _I64(N), _I64(K), _ptr(dX)), "qlinear_bwd_dx_asym")
     return dX
 
+
+
+# ---- Hessian-based sensitivity (Sec. 3.2, Eq. 2; Alg. 1) -- plain numpy, binary64 ---------------------------------
+def sensitivity_omega(lams):
+    """Eq. 2: Omega_i = |mean(lambda_i)| + std(lambda_i) over the runs of layer i (population standard deviation).
+    lams[layers, runs] -> omega[layers]."""
+    lams = np.asarray(lams, np.float64)
+    return np.abs(lams.mean(axis=1)) + lams.std(axis=1)
+
+
+def rank_by_sensitivity(omega):
+    """Layers in descending order of Omega (Sec. 3.2: sorted in descending order); equal values keep layer order."""
+    omega = np.asarray(omega, np.float64)
+    return np.argsort(-omega, kind="stable").astype(np.int32)
+
+
+def power_iteration(hv, v0, iters):
+    """Alg. 1 with the Hessian-vector product as a callable: v = v0/|v0|; n times: Hv = hv(v), the step's eigenvalue
+    estimate v.Hv (v has unit length), v = Hv/|Hv|.  Returns (estimates[iters], v)."""
+    v = np.asarray(v0, np.float64)
+    v = v / np.sqrt((v * v).sum())
+    lam = np.empty(iters, np.float64)
+    for i in range(iters):
+        Hv = np.asarray(hv(v), np.float64)
+        lam[i] = (v * Hv).sum()
+        nrm = np.sqrt((Hv * Hv).sum())
+        if nrm == 0.0:
+            lam[i:] = 0.0
+            break
+        v = Hv / nrm
+    return lam, v

@@ -745,3 +745,28 @@ def test_asymmetric_forward_and_backward_equal_fp64_gemm(bits):
     Ys, _, _ = oracle.qlinear_fwd(xq, 6.0, cs, hs, bits)
     sc = np.abs(Xhat) @ np.abs(oracle.dequantize_groupwise(cs, hs, bits)).T
     assert (np.abs(Ya - Ys) <= 2e-6 * sc).all()
+
+
+# ---- Hessian sensitivity: Eq. 2 and Alg. 1 -------------------------------------------------------------------------
+def test_sensitivity_omega_and_power_iteration():
+    """Eq. 2 on cases worked by hand; the ranking; Alg. 1 against a symmetric matrix built from a known spectrum (the
+    estimate converges to the eigenvalue of largest magnitude, sign included, at the rate (l2/l1)^2 per step, and v to
+    its eigenvector) and against numpy's eigensolver."""
+    om = oracle.sensitivity_omega([[1.0, 3.0], [-1.0, -3.0], [2.0, 2.0], [-4.0, 4.0]])
+    assert np.allclose(om, [3.0, 3.0, 2.0, 4.0], rtol=0, atol=1e-15)       # mean 2, std 1 | mean -2 | constant | mean 0, std 4
+    assert oracle.rank_by_sensitivity(om).tolist() == [3, 0, 1, 2]          # descending, ties in layer order
+    r = rng(130)
+    n = 40
+    Q, _ = np.linalg.qr(r.standard_normal((n, n)))
+    spec = np.concatenate([[-5.0, 3.0], r.uniform(-2.0, 2.0, n - 2)])      # the top eigenvalue is negative
+    H = (Q * spec) @ Q.T
+    H = 0.5 * (H + H.T)
+    lam, v = oracle.power_iteration(lambda x: H @ x, r.standard_normal(n), 60)
+    assert abs(lam[-1] + 5.0) < 1e-9
+    assert min(np.abs(v - Q[:, 0]).max(), np.abs(v + Q[:, 0]).max()) < 1e-6
+    w = np.linalg.eigvalsh(H)
+    assert abs(lam[-1] - w[np.argmax(np.abs(w))]) < 1e-9
+    err = np.abs(lam + 5.0)
+    assert err[30] < err[10] * (0.6 ** 2) ** 15                             # (3/5)^2 per step, with slack
+    lam0, _ = oracle.power_iteration(lambda x: 0.0 * x, r.standard_normal(n), 3)
+    assert (lam0 == 0).all()
