@@ -241,6 +241,33 @@ qb_status qb_qlinear_bwd_ste_asym(const uint16_t *dY, const int8_t *Xq, float cl
                                   int64_t T, int64_t N, int64_t K,
                                   uint16_t *dX, float *dW, void *workspace, void *stream);
 
+/*
+ * Hessian-based sensitivity (Sec. 3.2).  The Hessian-vector product itself (Eq. 1: a second back-propagation
+ * through the model) is the caller's: it is handed in as a function.
+ *
+ * qb_power_iteration -- Alg. 1: v = v/|v|; `iters` times: Hv = hv(v); estimate = v.Hv; v = Hv/|Hv|.
+ *   hv         host function; must enqueue on `stream` work that reads v[n] and writes out[n] (device fp32),
+ *              and return 0 (anything else ends the call with QB_ERR_HIP).  Called `iters` times, in order.
+ *   v          in/out [n] fp32 device: the random start vector drawn by the caller (Alg. 1, line 2), on
+ *              return the last normalised vector (all zeros if some Hv was the zero vector)
+ *   hv_buf     [n] fp32 device, the product's destination; contents undefined afterwards
+ *   scratch    [qb_power_iteration_scratch_floats()] fp32 device
+ *   estimates  out [iters] fp32 device: v.Hv of every step, the last one being the top eigenvalue's estimate
+ * Nothing is copied to the host and nothing waits: 3 + 3*iters small launches around the caller's own.  The
+ * reductions run in a fixed order (the result does not depend on scheduling).
+ *
+ * qb_sensitivity_omega -- Eq. 2, host only: omega[i] = |mean_r lambdas[i][r]| + std_r lambdas[i][r] (population
+ * standard deviation over the `runs` estimates of layer i; arithmetic in binary64).
+ * qb_rank_by_sensitivity -- host only: order[] = the layers by descending omega (ties keep layer order); the
+ * paper gives more bits to the layers that come first and sets the cut by hand.
+ */
+typedef int (*qb_hv_fn)(void *ctx, const float *v, float *out, void *stream);
+size_t qb_power_iteration_scratch_floats(void);
+qb_status qb_power_iteration(qb_hv_fn hv, void *ctx, int64_t n, int iters,
+                             float *v, float *hv_buf, float *scratch, float *estimates, void *stream);
+qb_status qb_sensitivity_omega(const float *lambdas, int layers, int runs, float *omega);
+qb_status qb_rank_by_sensitivity(const float *omega, int layers, int32_t *order);
+
 /* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
  * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */
 qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits,

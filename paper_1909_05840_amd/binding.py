@@ -22,7 +22,12 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
-           "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym")
+           "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
+           "qb_power_iteration_scratch_floats", "qb_power_iteration", "qb_sensitivity_omega", "qb_rank_by_sensitivity")
+
+
+# int hv(void *ctx, const float *v, float *out, void *stream)
+HV_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p)
 
 
 class _QuantJob(ctypes.Structure):
@@ -71,6 +76,14 @@ def load_library():
     lib.qb_qlinear_fwd_asym.argtypes = [vp, vp, cf, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_bwd_ste_asym.restype = ci
     lib.qb_qlinear_bwd_ste_asym.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_power_iteration_scratch_floats.restype = ctypes.c_size_t
+    lib.qb_power_iteration_scratch_floats.argtypes = []
+    lib.qb_power_iteration.restype = ci
+    lib.qb_power_iteration.argtypes = [HV_FN, vp, i64, ci, vp, vp, vp, vp, vp]
+    lib.qb_sensitivity_omega.restype = ci
+    lib.qb_sensitivity_omega.argtypes = [vp, ci, ci, vp]
+    lib.qb_rank_by_sensitivity.restype = ci
+    lib.qb_rank_by_sensitivity.argtypes = [vp, ci, vp]
     lib.qb_qlinear_bwd_ste_masked.restype = ci
     lib.qb_qlinear_bwd_ste_masked.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.qb_unpack_codes.restype = ci
@@ -314,6 +327,50 @@ def qb_qlinear_bwd_ste_asym(dY, Xq, clip, packed, delta, q0, bits, groups, want_
     _check(lib.qb_qlinear_bwd_ste_asym(_p(dY), _p(Xq), float(clip), _p(packed), _p(delta), _p(q0), bits, groups, T, N, K,
                                        _p(dX), _p(dW), _p(workspace), _stream()))
     return dX, dW
+
+
+def qb_power_iteration(hv, v, iters, hv_buf=None, scratch=None, estimates=None):
+    """Alg. 1.  hv(v, out) is a Python callable that enqueues out = H v on the current stream (v and out are the
+    tensors given here); v[n] fp32 device is the start vector and is overwritten.  Returns (estimates[iters], v)."""
+    lib = load_library()
+    _dev(v, torch.float32, "v")
+    n = v.numel()
+    if hv_buf is None:
+        hv_buf = torch.empty_like(v)
+    if scratch is None:
+        scratch = torch.empty(lib.qb_power_iteration_scratch_floats(), dtype=torch.float32, device=v.device)
+    if estimates is None:
+        estimates = torch.empty(iters, dtype=torch.float32, device=v.device)
+
+    def trampoline(ctx, v_ptr, out_ptr, stream):
+        if v_ptr != v.data_ptr() or out_ptr != hv_buf.data_ptr():
+            return 1
+        hv(v, hv_buf)
+        return 0
+    cb = HV_FN(trampoline)
+    _check(lib.qb_power_iteration(cb, None, n, iters, _p(v), _p(hv_buf), _p(scratch), _p(estimates), _stream()))
+    return estimates, v
+
+
+def qb_sensitivity_omega(lambdas):
+    """Eq. 2 on the host: lambdas[layers, runs] (numpy or nested lists) -> omega[layers] numpy fp32."""
+    import numpy as np
+    lib = load_library()
+    lam = np.ascontiguousarray(lambdas, dtype=np.float32)
+    layers, runs = lam.shape
+    omega = np.empty(layers, np.float32)
+    _check(lib.qb_sensitivity_omega(ctypes.c_void_p(lam.ctypes.data), layers, runs, ctypes.c_void_p(omega.ctypes.data)))
+    return omega
+
+
+def qb_rank_by_sensitivity(omega):
+    """Layers by descending omega (host): numpy int32."""
+    import numpy as np
+    lib = load_library()
+    om = np.ascontiguousarray(omega, dtype=np.float32)
+    order = np.empty(om.shape[0], np.int32)
+    _check(lib.qb_rank_by_sensitivity(ctypes.c_void_p(om.ctypes.data), om.shape[0], ctypes.c_void_p(order.ctypes.data)))
+    return order
 
 
 def qb_unpack_codes(packed, N, K, bits, codes=None):

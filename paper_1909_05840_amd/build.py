@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqbert.so")
-SOURCES = ("api.hip", "quantize.hip", "qgemm_i8.hip", "bwd_bf16.hip")
+SOURCES = ("api.hip", "quantize.hip", "qgemm_i8.hip", "bwd_bf16.hip", "hessian.hip")
 # packed-fp32 instructions are switched off for every device translation unit
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

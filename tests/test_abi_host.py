@@ -151,3 +151,30 @@ def test_package_never_imports_the_oracle():
             if fn.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, fn)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "qbert_oracle" not in src, fn
+
+
+def test_sensitivity_host_functions_against_eq2():
+    """Eq. 2 and the ranking run on the host: checked here against the oracle and hand-worked values, plus the
+    argument errors of the device-side power iteration (no launch happens for those)."""
+    import numpy as np
+    from oracle import sensitivity_omega, rank_by_sensitivity
+    lam = np.array([[1.0, 3.0], [-1.0, -3.0], [2.0, 2.0], [-4.0, 4.0]], np.float32)
+    om = qb.qb_sensitivity_omega(lam)
+    assert np.allclose(om, [3.0, 3.0, 2.0, 4.0], rtol=1e-7)
+    assert qb.qb_rank_by_sensitivity(om).tolist() == [3, 0, 1, 2]
+    r = np.random.default_rng(3)
+    lam = r.normal(1.0, 5.0, (12, 10)).astype(np.float32)        # 12 encoder layers, 10 runs (Sec. 4)
+    om = qb.qb_sensitivity_omega(lam)
+    assert np.allclose(om, sensitivity_omega(lam), rtol=1e-6)
+    assert (qb.qb_rank_by_sensitivity(om) == rank_by_sensitivity(om)).all()
+    lib = qb.load_library()
+    P, NULL = ctypes.c_void_p(0x1000), None
+    cb = qb.binding.HV_FN(lambda ctx, v, out, stream: 0)
+    assert lib.qb_power_iteration(cb, NULL, 100, 5, P, P, P, NULL, NULL) == 1
+    assert lib.qb_power_iteration(cb, NULL, 0, 5, P, P, P, P, NULL) == 3
+    assert lib.qb_power_iteration(cb, NULL, 100, 0, P, P, P, P, NULL) == 3
+    assert lib.qb_sensitivity_omega(NULL, 3, 3, P) == 1
+    assert lib.qb_sensitivity_omega(P, 0, 3, P) == 3
+    assert lib.qb_rank_by_sensitivity(P, 0, P) == 3
+    assert lib.qb_power_iteration_scratch_floats() >= 2
+

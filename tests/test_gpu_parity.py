@@ -825,3 +825,48 @@ def test_backward_asymmetric_ranges(qb, bits, shape):
     assert rel_fro(dX.float().cpu().numpy(), odX) <= 2e-2
     assert rel_fro(dW.cpu().numpy(), odW) <= 1e-4
 
+
+# ---- Hessian sensitivity: power iteration on the device ----------------------------------------------------------------
+@pytest.mark.parametrize("case", ["dense-512", "diag-3000001", "zero"])
+def test_power_iteration(qb, case):
+    """Alg. 1 around a Hessian-vector product supplied as a callback, against the oracle's binary64 iteration from
+    the same start vector: every step's estimate, and the final vector up to rounding.  A dense symmetric matrix with
+    a known spectrum (top eigenvalue negative), a long diagonal operator (several partial sums per reduction, ragged
+    tail), and the zero operator."""
+    say("power iteration", case)
+    r = np.random.default_rng(7)
+    if case == "dense-512":
+        n, iters = 512, 40
+        Q, _ = np.linalg.qr(r.standard_normal((n, n)))
+        spec = np.concatenate([[-5.0, 3.0], r.uniform(-2.0, 2.0, n - 2)])
+        H = (Q * spec) @ Q.T
+        H = (0.5 * (H + H.T)).astype(np.float32)
+        Hd = torch.from_numpy(H).to(DEV)
+        hv_gpu = lambda v, out: torch.mv(Hd, v, out=out)
+        hv_cpu = lambda x: H.astype(np.float64) @ x
+    elif case == "zero":
+        n, iters = 1000, 3
+        hv_gpu = lambda v, out: out.zero_()
+        hv_cpu = lambda x: 0.0 * x
+    else:
+        n, iters = 3000001, 25
+        d = r.uniform(-1.0, 1.0, n).astype(np.float32)
+        d[12345], d[n - 1] = 4.0, -3.0
+        dd = torch.from_numpy(d).to(DEV)
+        hv_gpu = lambda v, out: torch.mul(dd, v, out=out)
+        hv_cpu = lambda x: d.astype(np.float64) * x
+    v0 = r.standard_normal(n).astype(np.float32)
+    est, v = qb.qb_power_iteration(hv_gpu, torch.from_numpy(v0).to(DEV), iters)
+    torch.cuda.synchronize()
+    lam, vo = oracle.power_iteration(hv_cpu, v0, iters)
+    est = est.cpu().numpy().astype(np.float64)
+    if case == "zero":
+        assert (est == 0).all() and (v == 0).all()
+        return
+    assert np.abs(est - lam).max() <= 1e-4 * np.abs(lam).max()
+    vv = v.cpu().numpy().astype(np.float64)
+    assert abs(np.linalg.norm(vv) - 1.0) < 1e-5
+    assert np.abs(vv - vo).max() <= 2e-4
+    top = -5.0 if case == "dense-512" else 4.0
+    assert abs(est[-1] - top) < 1e-3 * abs(top) + (0.05 if case != "dense-512" else 0)
+
