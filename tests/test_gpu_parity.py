@@ -806,6 +806,40 @@ def test_forward_asymmetric_ranges(qb, bits, shape):
         assert torch.equal(Y2, Y)
 
 
+@pytest.mark.parametrize("shape", [(96, 64, 32768, 32), (2048, 768, 32768, 128)])
+@pytest.mark.parametrize("bits", (2, 8))
+def test_forward_asymmetric_maximum_K_and_extreme_codes(qb, bits, shape):
+    """The longest contraction with operands at the ends of their ranges: S = sum (2x'+1) u reaches 255 * L * K
+    (2.13e9 at 8 bits) and must stay inside int32 on the way (S = A4/2 + L*(R/2)); the register-staged and the
+    role-split kernel."""
+    T, N, K, G = shape
+    say("fwd asym max K", shape, "bits", bits)
+    L = 2 ** bits - 1
+    W = torch.full((N, K), 0.1)
+    W[:, ::2] = 0.3                     # every group holds its minimum and its maximum: codes 0 and L
+    W[1::2] = 0.3                       # rows of all-L codes
+    W[5, ::3] = 0.17
+    X = torch.full((T, K), 6.0)         # x' = 127: 2x'+1 = 255
+    X[1::3] = -6.0
+    X[2::3] = wl.activation(T, K, seed=5)[2::3]
+    packed, delta, q0, rs_w = qb.qb_quantize_groupwise_asym(W.to(DEV), bits, G)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    Y = qb.qb_qlinear_fwd_asym(Xq, rs_x, CLIP, packed, delta, q0, rs_w, bits, G, N)
+    torch.cuda.synchronize()
+    oc, od, oq0, _ = oracle.quantize_groupwise_asym(W.numpy(), bits, G)
+    oq, ors_x = oracle.quantize_act(X.numpy(), CLIP)
+    assert (qb.qb_unpack_codes(packed, N, K, bits).cpu().numpy() == oc).all()
+    ts = np.arange(0, T, max(1, T // 48))
+    Yo, S = oracle.qlinear_fwd_asym(oq[ts], CLIP, oc, od, oq0, want_s=True, openmp=True)
+    assert int(np.abs(S).max()) == 255 * L * K
+    R = (2 * ors_x[ts].astype(np.int64) + K)[:, None]
+    rows = N // G
+    dn = np.repeat(od.astype(np.float64), rows)[None, :]
+    zn = np.repeat(oq0.astype(np.float64), rows)[None, :]
+    bound = 1e-6 * (CLIP / 255.0) * (dn * np.abs(S) + np.abs(zn) * np.abs(R))
+    assert (np.abs(Y.cpu().numpy()[ts].astype(np.float64) - Yo) <= bound).all()
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("shape", [(300, 160, 192, 8), (513, 768, 768, 128), (1000, 96, 320, 96)])
 def test_backward_asymmetric_ranges(qb, bits, shape):
