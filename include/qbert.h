@@ -221,7 +221,8 @@ qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float 
  *   delta  out  [G] fp32, Delta_g (0 for a constant group, whose codes are 0)
  *   q0     out  [G] fp32, the group's minimum
  *   packed, rs_w  as qb_quantize_groupwise (same layout, same row sums: qb_unpack_codes applies)
- * Both delta and q0 serve as scratch of the min/max reduction during the call.  Four launches on `stream`.
+ * One launch when a group (N/G rows of K) has at most 32768 weights, else four (delta and q0 then serve as
+ * scratch of the min/max reduction during the call).
  *
  * qb_qlinear_fwd_asym: Y[t,n] = h_x * (Delta_g * S[t,n] + q0_g * R[t]) (+ bias[n]) with the integer sums
  * S = sum_j (2x'+1) u[n,j] and R = sum_j (2x'+1) = 2 rs_x[t] + K, both taken from the same int8 matrix-core

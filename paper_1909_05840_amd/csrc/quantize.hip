@@ -32,7 +32,8 @@ __device__ __forceinline__ int fast_div(int e, int d, float inv)
 // group.  FUSED: the panel is the whole group, max-abs is found here and m/h are written.
 // Otherwise m was found by absmax_slices_kernel and only the panel starting a group writes h.
 // LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then THREADS/64 floats.
-// ASYM (with !FUSED): the group's range is [m[g], m[g] + L*h[g]], found before (q0 in m, Delta in h; both read only).
+// ASYM: the group's range is [q0, q0 + L*Delta] with q0 in m[g] and Delta in h[g]: read (found before) if !FUSED,
+// found here as the group's minimum and fl(fl(max - min)/L) and written if FUSED.
 template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
 __device__ __forceinline__ void quantize_panel_body(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
@@ -51,35 +52,61 @@ __device__ __forceinline__ void quantize_panel_body(
     constexpr float Lf = (float)((1 << BITS) - 1);
 
     float4 v[V];
-    float mx = 0.0f;
+    float mx = 0.0f, mn = 0.0f;
+    if constexpr (FUSED && ASYM) mx = mn = W[(size_t)row0 * K];  // any element of the group
 #pragma unroll
     for (int i = 0; i < V; ++i) {
         const int idx = tid + i * THREADS;
         if (idx < n4) {
             v[i] = src[idx];
-            if (FUSED) mx = absmax4(v[i], mx);
+            if constexpr (FUSED && ASYM) {
+                mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+                mn = fminf(fminf(mn, fminf(v[i].x, v[i].y)), fminf(v[i].z, v[i].w));
+            } else if (FUSED) {
+                mx = absmax4(v[i], mx);
+            }
         }
     }
     for (int r = tid; r < prow; r += THREADS) rowsum[r] = 0;
 
-    float mg;
+    float mg, dg = 0.0f;
     if (FUSED) {
+        constexpr int NW = THREADS / 64;
         mx = wave_max(mx);
-        if ((tid & 63) == 0) red[tid >> 6] = mx;
+        if constexpr (ASYM) mn = -wave_max(-mn);
+        if ((tid & 63) == 0) {
+            red[tid >> 6] = mx;
+            if constexpr (ASYM) red[NW + (tid >> 6)] = mn;
+        }
         __syncthreads();
         mg = red[0];
 #pragma unroll
-        for (int w = 1; w < THREADS / 64; ++w) mg = fmaxf(mg, red[w]);
+        for (int w = 1; w < NW; ++w) mg = fmaxf(mg, red[w]);
+        if constexpr (ASYM) {
+            float lo = red[NW];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) lo = fminf(lo, red[NW + w]);
+            dg = __fdiv_rn(__fsub_rn(mg, lo), Lf);
+            mg = lo;
+        }
     } else {
         mg = m[g];
+        if constexpr (ASYM) dg = h[g];
         __syncthreads();
     }
     Quantizer qz;
-    if constexpr (ASYM) qz.set_range(mg, h[g]);
+    if constexpr (ASYM) qz.set_range(mg, dg);
     else qz.set(mg, Lf);
-    if (!ASYM && tid == 0 && row0 % rows_per_group == 0) {
-        h[g] = qz.half_step();
-        if (FUSED) m[g] = mg;
+    if (tid == 0 && row0 % rows_per_group == 0) {
+        if constexpr (ASYM) {
+            if (FUSED) {
+                h[g] = dg;
+                m[g] = mg;
+            }
+        } else {
+            h[g] = qz.half_step();
+            if (FUSED) m[g] = mg;
+        }
     }
     if (!FUSED && !ASYM) {  // the range was given: it may be smaller than the group's max-abs (clipped range)
 #pragma unroll
@@ -590,7 +617,7 @@ template <int BITS, int THREADS, bool ASYM = false>
 void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h, float *m,
                   int32_t *rs_w, hipStream_t st)
 {
-    const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 64;
+    const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 128;
     hipLaunchKernelGGL((quantize_panel_kernel<BITS, THREADS, 8, false, ASYM>), dim3(panels), dim3(THREADS), lds, st, W, K,
                        rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w);
 }
@@ -632,13 +659,28 @@ qb_status quantize_given_range(const float *W, int64_t N, int64_t K, int groups,
     return launch_status();
 }
 
-// asymmetric ranges: keys, min/max by slices, Delta and q0, then the panels
+// asymmetric ranges: fused when a group fits one workgroup; else keys, min/max by slices, Delta and q0, then the panels
 template <int BITS>
 qb_status quantize_asym(const float *W, int64_t N, int64_t K, int groups, uint8_t *packed, float *delta, float *q0,
                         int32_t *rs_w, hipStream_t st)
 {
     const int rpg = (int)(N / groups);
     const int64_t gelems = (int64_t)rpg * K;
+    if (gelems <= kMaxFusedElems) {  // a group fits one workgroup's registers: one pass, one launch
+        const size_t lds = (size_t)rpg * (K + 16) + (size_t)rpg * 4 + 128;
+        const float inv_K = 1.0f / (float)K, inv_rows = 1.0f / (float)rpg;
+        const dim3 grid(groups);
+        if (gelems <= 256 * 4 * 8)
+            hipLaunchKernelGGL((quantize_panel_kernel<BITS, 256, 8, true, true>), grid, dim3(256), lds, st, W, (int)K, rpg, rpg,
+                               inv_K, inv_rows, packed, delta, q0, rs_w);
+        else if (gelems <= 512 * 4 * 10)
+            hipLaunchKernelGGL((quantize_panel_kernel<BITS, 512, 10, true, true>), grid, dim3(512), lds, st, W, (int)K, rpg, rpg,
+                               inv_K, inv_rows, packed, delta, q0, rs_w);
+        else
+            hipLaunchKernelGGL((quantize_panel_kernel<BITS, 1024, 8, true, true>), grid, dim3(1024), lds, st, W, (int)K, rpg,
+                               rpg, inv_K, inv_rows, packed, delta, q0, rs_w);
+        return launch_status();
+    }
     int prow = 1;
     for (int p = rpg; p >= 1; --p)
         if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
