@@ -814,7 +814,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
     constexpr int PARAM_BYTES = (2 * BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias | per-token scales
                                                          // (or, in their place, q0 of the neuron's group)
-    static_assert(BNP <= BM, "the per-neuron q0 values take the place of the per-token scales");
+    static_assert(OUT != 2 || BNP <= BM, "the per-neuron q0 values take the place of the per-token scales");
     static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
 
     // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
