@@ -1148,14 +1148,17 @@ void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, con
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
     const OutQ oq{nullptr, nullptr, 1.0f, 0, hx_rows, q0};
-    if (q0)
-        hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 2>), dim3(grid),
-                           dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                           tiles_m, tiles_n, oq);
-    else
-        hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 0>), dim3(grid),
-                           dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                           tiles_m, tiles_n, oq);
+    if constexpr ((BN + 63) / 64 * 64 <= BM) {  // (the asymmetric variant exists for the tile shapes it fits)
+        if (q0) {
+            hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 2>), dim3(grid),
+                               dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg,
+                               hx, tiles_m, tiles_n, oq);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 0>), dim3(grid),
+                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
+                       tiles_m, tiles_n, oq);
 }
 
 // the same with the 8-bit output
