@@ -218,6 +218,7 @@ def main():
     quant_bytes = sum(N * K * (4.0 + b / 8.0) + GROUPS * 8 + N * 4 for b in BITS_SWEEP for (_, N, K) in linears)
     act_bytes = sum(T * K * 5.0 + T * 4 for (_, N, K) in linears)
     gemm_tops = gemm_ops / (seg_ms[2] * 1e-3) / 1e12
+    mfma_peak = measured_mfma_peak(torch, qb, dev)
     quant_gbs = quant_bytes / (seg_ms[0] * 1e-3) / 1e9
     act_gbs = act_bytes / (seg_ms[1] * 1e-3) / 1e9
     value = gemm_ops / (wall / args.steps) / 1e12
@@ -237,7 +238,10 @@ def main():
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
                      "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
-                     "ops_per_launch": gemm_ops / n_gemm},
+                     "ops_per_launch": gemm_ops / n_gemm,
+                     "peak_measured": round(mfma_peak, 1), "frac_of_measured": round(gemm_tops / mfma_peak, 4),
+                     "peak_measured_note": "issue rate of v_mfma_i32_32x32x32_i8 alone (registers only, 2 wavefronts "
+                                           "per SIMD), measured in this run at the clock the chip holds under it"},
         "kernels": {
             "quantize_pack": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                               "frac": round(quant_gbs / PEAK_HBM_GBS, 4),
@@ -275,6 +279,24 @@ def measured_traffic(kernel):
             return json.load(f)[kernel]["bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         return None
+
+
+def measured_mfma_peak(torch, qb, dev):
+    """TOP/s of the int8 matrix-core instruction issued back to back with nothing else (the published peak assumes a
+    clock the chip may not hold): two wavefronts per SIMD on every CU, warmed up, best of three."""
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    wgs = 2 * torch.cuda.get_device_properties(0).multi_processor_count
+    best = 0.0
+    qb.qb_probe_mfma_i8(wgs, 20000, sink)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = qb.qb_probe_mfma_i8(wgs, 20000, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, ops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def time_launches(torch, fn, iters=100, warm=30):

@@ -269,6 +269,14 @@ qb_status qb_power_iteration(qb_hv_fn hv, void *ctx, int64_t n, int iters,
 qb_status qb_sensitivity_omega(const float *lambdas, int layers, int runs, float *omega);
 qb_status qb_rank_by_sensitivity(const float *omega, int layers, int32_t *order);
 
+/*
+ * Measurement aid (no part of the method): `workgroups` x 4 wavefronts each issue `iters` rounds of four
+ * independent 32x32x32 int8 matrix-core instructions on registers, i.e. workgroups * 4 * iters * 4 * 65536
+ * integer operations and nothing else; timed by the caller, it gives the issue-rate peak that the GEMM's
+ * percentage can be read against beside the published one.  sink: [1] int32 device (practically never written).
+ */
+qb_status qb_probe_mfma_i8(int workgroups, int iters, int32_t *sink, void *stream);
+
 /* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
  * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */
 qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits,

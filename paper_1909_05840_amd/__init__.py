@@ -9,7 +9,7 @@ from .binding import (QBError, load_library, qb_status_string, qb_packed_nbytes,
                       qb_unpack_codes, qb_embedding_quantize, qb_embedding_gather, qb_embedding_quantize_bits,
                       qb_embedding_gather_bits, qb_quantize_act_dyn, qb_qlinear_fwd_dyn, qb_quantize_groupwise_clip, qb_quantize_act_dyn_tensor, qb_qlinear_bwd_ste_masked,
                       qb_quantize_groupwise_asym, qb_qlinear_fwd_asym, qb_qlinear_bwd_ste_asym,
-                      qb_power_iteration, qb_sensitivity_omega, qb_rank_by_sensitivity,
+                      qb_power_iteration, qb_sensitivity_omega, qb_rank_by_sensitivity, qb_probe_mfma_i8,
                       EXPORTS, LIB_PATH)
 from . import workloads
 
@@ -18,4 +18,4 @@ __all__ = ["QBError", "load_library", "qb_status_string", "qb_packed_nbytes", "q
            "qb_unpack_codes", "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits",
            "qb_embedding_gather_bits", "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked", "qb_quantize_groupwise_asym",
            "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym", "qb_power_iteration", "qb_sensitivity_omega",
-           "qb_rank_by_sensitivity", "workloads", "EXPORTS", "LIB_PATH"]
+           "qb_rank_by_sensitivity", "qb_probe_mfma_i8", "workloads", "EXPORTS", "LIB_PATH"]

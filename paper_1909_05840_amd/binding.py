@@ -23,7 +23,8 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
            "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
-           "qb_power_iteration_scratch_floats", "qb_power_iteration", "qb_sensitivity_omega", "qb_rank_by_sensitivity")
+           "qb_power_iteration_scratch_floats", "qb_power_iteration", "qb_sensitivity_omega", "qb_rank_by_sensitivity",
+           "qb_probe_mfma_i8")
 
 
 # int hv(void *ctx, const float *v, float *out, void *stream)
@@ -80,6 +81,8 @@ def load_library():
     lib.qb_power_iteration_scratch_floats.argtypes = []
     lib.qb_power_iteration.restype = ci
     lib.qb_power_iteration.argtypes = [HV_FN, vp, i64, ci, vp, vp, vp, vp, vp]
+    lib.qb_probe_mfma_i8.restype = ci
+    lib.qb_probe_mfma_i8.argtypes = [ci, ci, vp, vp]
     lib.qb_sensitivity_omega.restype = ci
     lib.qb_sensitivity_omega.argtypes = [vp, ci, ci, vp]
     lib.qb_rank_by_sensitivity.restype = ci
@@ -350,6 +353,13 @@ def qb_power_iteration(hv, v, iters, hv_buf=None, scratch=None, estimates=None):
     cb = HV_FN(trampoline)
     _check(lib.qb_power_iteration(cb, None, n, iters, _p(v), _p(hv_buf), _p(scratch), _p(estimates), _stream()))
     return estimates, v
+
+
+def qb_probe_mfma_i8(workgroups, iters, sink):
+    """Enqueue the matrix-core issue-rate probe; returns the number of integer operations it performs."""
+    lib = load_library()
+    _check(lib.qb_probe_mfma_i8(int(workgroups), int(iters), _p(sink), _stream()))
+    return workgroups * 4 * iters * 4 * 65536
 
 
 def qb_sensitivity_omega(lambdas):

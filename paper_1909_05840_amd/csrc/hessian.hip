@@ -137,3 +137,37 @@ extern "C" qb_status qb_rank_by_sensitivity(const float *omega, int layers, int3
     }
     return QB_OK;
 }
+
+// ---- measurement aid: the issue rate of the int8 matrix-core instruction the GEMM uses -------------------------
+// Every wavefront runs `iters` rounds of four independent v_mfma_i32_32x32x32_i8 on registers, nothing else:
+// 4 * 65536 integer operations per round and wavefront.  Timed by the caller (events around the launch).
+namespace qb {
+namespace {
+typedef int pv4i __attribute__((ext_vector_type(4)));
+typedef int pv16i __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_i8_probe_kernel(int iters, int32_t *sink)
+{
+    const int lane = threadIdx.x & 63;
+    const pv4i a = {lane, lane + 1, lane + 2, lane + 3}, b = {1, 2, 3, lane};
+    pv16i c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c3, 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s == 0x7fffffff) sink[0] = s;  // keeps the loop alive; practically never taken
+}
+}  // namespace
+}  // namespace qb
+
+extern "C" qb_status qb_probe_mfma_i8(int workgroups, int iters, int32_t *sink, void *stream)
+{
+    if (!sink) return QB_ERR_NULL;
+    if (workgroups <= 0 || workgroups > 65536 || iters <= 0) return QB_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+    return launch_status();
+}

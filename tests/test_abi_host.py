@@ -177,4 +177,8 @@ def test_sensitivity_host_functions_against_eq2():
     assert lib.qb_sensitivity_omega(P, 0, 3, P) == 3
     assert lib.qb_rank_by_sensitivity(P, 0, P) == 3
     assert lib.qb_power_iteration_scratch_floats() >= 2
+    # probe_mfma_i8(workgroups,iters,sink,stream)
+    assert lib.qb_probe_mfma_i8(512, 100, NULL, NULL) == 1
+    assert lib.qb_probe_mfma_i8(0, 100, P, NULL) == 3
+    assert lib.qb_probe_mfma_i8(512, 0, P, NULL) == 3
 

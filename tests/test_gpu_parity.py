@@ -904,3 +904,11 @@ def test_power_iteration(qb, case):
     top = -5.0 if case == "dense-512" else 4.0
     assert abs(est[-1] - top) < 1e-3 * abs(top) + (0.05 if case != "dense-512" else 0)
 
+
+def test_mfma_probe_runs_and_leaves_its_sink_alone(qb):
+    """The measurement aid: it launches, finishes and reports the operation count its kernel performs."""
+    sink = torch.full((1,), 77, dtype=torch.int32, device=DEV)
+    ops = qb.qb_probe_mfma_i8(8, 10, sink)
+    torch.cuda.synchronize()
+    assert ops == 8 * 4 * 10 * 4 * 65536 and int(sink.item()) == 77
+
