@@ -504,7 +504,18 @@ def cpu_baseline(wl):
     sec = time.perf_counter() - t0
     return {"value": round(ops / sec / 1e12, 5), "unit": "TOPS", "cores": threads, "kind": "oracle",
             "sample": "one whole step: 4096 token rows, 4 linears x 4 bit-widths, incl. the quantize steps; %.1f s" % sec,
-            "host_cpus": os.cpu_count()}
+            "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 if __name__ == "__main__":
