@@ -607,11 +607,13 @@ __device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_addr)
 
 // Epilogue of the role-split kernel.  Its per-token and per-neuron parameters do not come from global
 // memory but from a block in LDS that a producer wavefront filled for the tile (BM ints rs_x, then BN
-// each of rs_w, h of the neuron's group, bias; indices past the end of the matrix were clamped).  The
+// each of rs_w, h of the neuron's group, bias, and last either BM per-token scales or BN values of q0 of the
+// neuron's group; indices past the end of the matrix were clamped).  The
 // consumer wavefronts thus issue no global loads at all: their memory counter holds stores only and is
 // never waited on, so the stores of one tile need not have completed before the next tile's go out.
 // acc[tm][tn][r]: token tl + 32*tm + 8*(r/4) + (r%4) of the tile (tl contains 4*hf), neuron nl + 32*tn
-// (nl contains l32).  A4 = 4*acc + 2e*rs_x[t] + 2*rs_w[n] + K,  Y = (h_x*h_g(n)) * float(A4) + bias[n].
+// (nl contains l32).  A4 = 4*acc + 2e*rs_x[t] + 2*rs_w[n] + K,  Y = (h_x*h_g(n)) * float(A4) + bias[n];
+// dyn: h_x per token; asym_L = 2^k - 1: asymmetric group ranges, Y = asym_value(...) + bias[n].
 template <int BM, int BN>
 __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *pp, int e2, int tl, int nl, int t0, int n0,
                                                 int T, int N, int K, float hx, bool has_bias, bool fast,
