@@ -323,21 +323,25 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][i] = 0.0f;
-        // the clamp mask's source values for this wavefront's 2 x 16 results: loaded before the K-loop, which
-        // hides their latency (rows and columns past the end re-read a valid element; their results are not stored)
-        float msrc[TM][16], mlim[TM][16];  // (no load may be left for the write-out: waiting for it would also wait
-                                           // for every store before it)
+        // The clamp mask's source values for this wavefront's 64 x 32 results, loaded before the K-loop (which hides
+        // their latency) as 2 x 4 float4: one instruction covers 8 rows x 32 columns, lane l the row l/8 and the four
+        // columns 4*(l%8)... of it.  That is not the accumulator's lane layout: after the K-loop every lane turns its
+        // values into predicate bits, and the bits change lanes (below).  Rows and columns past the end re-read valid
+        // elements; their results are not stored.  No load may be left for the write-out: waiting for it there would
+        // also wait for every store before it.
+        float4 mv[TM][4];
+        float ml[TM][4];
         if constexpr (MASK && OUT != 2) {
-            const int nn = tile_n * BN + wn * 32 + l32;
-            const int nc = nn < Nc ? nn : Nc - 1;
+            int cc = tile_n * BN + wn * 32 + 4 * (lane & 7);
+            cc = cc < Nc ? cc : Nc - 4;
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    int r = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf + 8 * (i >> 2) + (i & 3);
+                for (int q = 0; q < 4; ++q) {
+                    int r = tile_m * BM + (wm * TM + tm) * 32 + 8 * q + (lane >> 3);
                     r = r < M ? r : M - 1;
-                    msrc[tm][i] = mask.src[(size_t)r * Nc + nc];
-                    mlim[tm][i] = (OUT == 1) ? mask.lim[r / mask.rows_per_lim] : mask.lim_all;
+                    mv[tm][q] = *reinterpret_cast<const float4 *>(mask.src + (size_t)r * Nc + cc);
+                    ml[tm][q] = (OUT == 1) ? mask.lim[r / mask.rows_per_lim] : mask.lim_all;
                 }
         }
         asm volatile("" ::: "memory");
@@ -364,19 +368,38 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
-        // all mask decisions first, as one bit each: the stores below then depend on no load (a wait for a load
-        // between two stores would also wait for the stores before it)
+        // All mask decisions first, as one bit each, so that the stores below depend on no load.  A lane packs the
+        // predicates of its 4 x 4 loaded values into 16 bits (nibble q = load q); the lane that holds the result of
+        // row 4*hf + 8*q + j, column l32 finds them in lane (4*hf + j)*8 + l32/4, bit 4*q + l32%4.
         uint32_t outside = 0;
         if constexpr (MASK && OUT != 2) {
 #pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    // the empty statement consumes the loaded values here, so the compiler places its waits for
+                    // the loads here and not next to uses it would otherwise sink between the stores
+                    asm volatile("" : "+v"(mv[tm][q].x), "+v"(mv[tm][q].y), "+v"(mv[tm][q].z), "+v"(mv[tm][q].w), "+v"(ml[tm][q]));
+                    const float lim = ml[tm][q];
+                    w |= (fabsf(mv[tm][q].x) > lim ? 1u : 0u) << (4 * q);
+                    w |= (fabsf(mv[tm][q].y) > lim ? 2u : 0u) << (4 * q);
+                    w |= (fabsf(mv[tm][q].z) > lim ? 4u : 0u) << (4 * q);
+                    w |= (fabsf(mv[tm][q].w) > lim ? 8u : 0u) << (4 * q);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t g = (uint32_t)__shfl((int)w, (4 * hf + j) * 8 + (l32 >> 2)) >> (l32 & 3);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) outside |= ((g >> (4 * q)) & 1u) << (tm * 16 + 4 * q + j);
+                }
+            }
+            // applied here, as selects: inside the bounds-checked store loop the compiler turns the same test into
+            // a branch per element (seventy instructions per store instead of eleven, 4 us per tile)
+#pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    // the empty statement consumes the loaded values here, so the compiler places its waits for
-                    // the loads here and not next to the uses it would otherwise sink between the stores
-                    asm volatile("" : "+v"(msrc[tm][i]), "+v"(mlim[tm][i]));
-                    outside |= (fabsf(msrc[tm][i]) > mlim[tm][i] ? 1u : 0u) << (tm * 16 + i);
-                }
+                for (int i = 0; i < 16; ++i) acc[tm][i] = ((outside >> (tm * 16 + i)) & 1u) ? 0.0f : acc[tm][i];
         }
         const int n = tile_n * BN + wn * 32 + l32;
 #pragma unroll
@@ -387,9 +410,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
                 const int r = r0 + 8 * (i >> 2) + (i & 3);
                 if (r < M && n < Nc) {
                     const size_t at = (size_t)r * Nc + n;
-                    if constexpr (MASK && OUT != 2) {
-                        if ((outside >> (tm * 16 + i)) & 1u) acc[tm][i] = 0.0f;
-                    }
                     if (OUT == 0) static_cast<uint16_t *>(Cout)[at] = f32_to_bf16_rne(acc[tm][i]);
                     else if (OUT == 1) static_cast<float *>(Cout)[at] = acc[tm][i] * scale;
                     else static_cast<float *>(Cout)[(size_t)z * M * Nc + at] = acc[tm][i];
