@@ -402,9 +402,22 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
                 for (int i = 0; i < 16; ++i) acc[tm][i] = ((outside >> (tm * 16 + i)) & 1u) ? 0.0f : acc[tm][i];
         }
         const int n = tile_n * BN + wn * 32 + l32;
+        const bool interior = (tile_m + 1) * BM <= M && (tile_n + 1) * BN <= Nc;  // uniform over the workgroup
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int r0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
+            if (interior) {  // no per-element checks, one base address per block
+                const size_t at0 = (size_t)r0 * Nc + n + (OUT == 2 ? (size_t)z * M * Nc : 0);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const size_t at = at0 + (size_t)(8 * (i >> 2) + (i & 3)) * Nc;
+                    // results that no kernel of this call reads again are streamed past the caches
+                    if (OUT == 0) __builtin_nontemporal_store(f32_to_bf16_rne(acc[tm][i]), static_cast<uint16_t *>(Cout) + at);
+                    else if (OUT == 1) __builtin_nontemporal_store(acc[tm][i] * scale, static_cast<float *>(Cout) + at);
+                    else static_cast<float *>(Cout)[at] = acc[tm][i];
+                }
+                continue;
+            }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int r = r0 + 8 * (i >> 2) + (i & 3);
