@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference dispatch for HBM byte counters)")
+    ap.add_argument("--backward-only", action="store_true",
+                    help="run only the STE-backward leg (configs[2]) and print its result: the command profiled for "
+                         "the backward kernels")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -64,6 +67,9 @@ def main():
     torch.cuda.set_device(dev)
     linears = wl.BERT_BASE_LINEARS
     T = T_TOKENS
+    if args.backward_only:
+        print(json.dumps({"backward": backward_leg(torch, qb, wl, dev)}))
+        return
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
     Ws = [wl.weight(N, K, seed=wl.config_seed(1, i)).to(dev) for i, (_, N, K) in enumerate(linears)]
