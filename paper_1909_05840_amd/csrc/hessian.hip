@@ -65,9 +65,8 @@ __global__ __launch_bounds__(64) void pi_finish_kernel(const float *__restrict__
     }
 }
 
-// v = src / |src| with the norm read from device memory; a zero vector is left as zeros
-__global__ __launch_bounds__(256) void pi_scale_kernel(const float *__restrict__ src, int64_t n, const float *__restrict__ fin,
-                                                       float *__restrict__ v)
+// v = src / |src| with the norm read from device memory; a zero vector is left as zeros (src may be v itself)
+__global__ __launch_bounds__(256) void pi_scale_kernel(const float *src, int64_t n, const float *__restrict__ fin, float *v)
 {
     const float nrm = fin[1];
     const float inv = nrm > 0.0f ? 1.0f / nrm : 0.0f;
