@@ -345,13 +345,22 @@ def qb_power_iteration(hv, v, iters, hv_buf=None, scratch=None, estimates=None):
     if estimates is None:
         estimates = torch.empty(iters, dtype=torch.float32, device=v.device)
 
+    failure = []
+
     def trampoline(ctx, v_ptr, out_ptr, stream):
         if v_ptr != v.data_ptr() or out_ptr != hv_buf.data_ptr():
             return 1
-        hv(v, hv_buf)
+        try:
+            hv(v, hv_buf)
+        except BaseException as exc:   # an exception must not cross the C frames: hand it over and stop the iteration
+            failure.append(exc)
+            return 1
         return 0
     cb = HV_FN(trampoline)
-    _check(lib.qb_power_iteration(cb, None, n, iters, _p(v), _p(hv_buf), _p(scratch), _p(estimates), _stream()))
+    rc = lib.qb_power_iteration(cb, None, n, iters, _p(v), _p(hv_buf), _p(scratch), _p(estimates), _stream())
+    if failure:
+        raise failure[0]
+    _check(rc)
     return estimates, v
 
 

@@ -905,6 +905,17 @@ def test_power_iteration(qb, case):
     assert abs(est[-1] - top) < 1e-3 * abs(top) + (0.05 if case != "dense-512" else 0)
 
 
+def test_power_iteration_callback_failure_is_reported(qb):
+    """A product that fails ends the call: the exception of a Python callback comes back to the caller."""
+    v = torch.ones(1000, dtype=torch.float32, device=DEV)
+
+    def bad(v_, out_):
+        raise ValueError("no product today")
+    with pytest.raises(ValueError):
+        qb.qb_power_iteration(bad, v, 3)
+    torch.cuda.synchronize()
+
+
 def test_mfma_probe_runs_and_leaves_its_sink_alone(qb):
     """The measurement aid: it launches, finishes and reports the operation count its kernel performs."""
     sink = torch.full((1,), 77, dtype=torch.int32, device=DEV)
