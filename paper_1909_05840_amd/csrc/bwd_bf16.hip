@@ -217,13 +217,15 @@ struct ClampMask {
     int rows_per_lim;
 };
 
-template <int NSTAGE, int OUT, bool MASK>
+template <int NSTAGE, int OUT, bool MASK, int TM>
 __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int M, int Nc, int Kc, int lda, int ldb,
     int ksplit, float scale, void *__restrict__ Cout, int tiles_m, int tiles_n, const ClampMask mask)
 {
-    constexpr int TM = 2, WN = 3, NPROD = 2;
-    constexpr int BM = 128, BN = 96, BKB = 128;  // 64 bf16 per step
+    // TM 32-row blocks per MFMA wavefront: tiles of 64*TM x 96 (128 x 96, or 256 x 96 where that still fills the chip:
+    // half as many tile changes, a weight fragment serves four MFMAs instead of two)
+    constexpr int WN = 3, NPROD = 2;
+    constexpr int BM = 64 * TM, BN = 96, BKB = 128;  // 64 bf16 per step
     constexpr int A_TOTAL = BM / 8, B_TOTAL = BN / 8;
     constexpr int A_PER = A_TOTAL / NPROD, B_PER = B_TOTAL / NPROD, PERP = A_PER + B_PER;
     constexpr int D = NSTAGE - 1;
@@ -371,7 +373,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
         // All mask decisions first, as one bit each, so that the stores below depend on no load.  A lane packs the
         // predicates of its 4 x 4 loaded values into 16 bits (nibble q = load q); the lane that holds the result of
         // row 4*hf + 8*q + j, column l32 finds them in lane (4*hf + j)*8 + l32/4, bit 4*q + l32%4.
-        uint32_t outside = 0;
+        uint64_t outside = 0;
         if constexpr (MASK && OUT != 2) {
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t g = (uint32_t)__shfl((int)w, (4 * hf + j) * 8 + (l32 >> 2)) >> (l32 & 3);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) outside |= ((g >> (4 * q)) & 1u) << (tm * 16 + 4 * q + j);
+                    for (int q = 0; q < 4; ++q) outside |= (uint64_t)((g >> (4 * q)) & 1u) << (tm * 16 + 4 * q + j);
                 }
             }
             // applied here, as selects: inside the bounds-checked store loop the compiler turns the same test into
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nt_s3_kernel(
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[tm][i] = ((outside >> (tm * 16 + i)) & 1u) ? 0.0f : acc[tm][i];
+                for (int i = 0; i < 16; ++i) acc[tm][i] = ((outside >> (tm * 16 + i)) & 1ull) ? 0.0f : acc[tm][i];
         }
         const int n = tile_n * BN + wn * 32 + l32;
         const bool interior = (tile_m + 1) * BM <= M && (tile_n + 1) * BN <= Nc;  // uniform over the workgroup
@@ -460,20 +462,35 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float4 *__re
     out[at] = make_float4(s.x * scale, s.y * scale, s.z * scale, s.w * scale);
 }
 
+template <int OUT, int TM>
+void launch_gemm_tm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
+                    float scale, void *C, hipStream_t st, const ClampMask *mask)
+{
+    // 64*TM x 96 tiles, 3 stages, one workgroup per CU; persistent grid of at most 256 per split
+    const int tm = (M + 64 * TM - 1) / (64 * TM), tn = (Nc + 95) / 96;
+    int grid = tm * tn;
+    if (grid > 256) grid = 256;
+    if (mask && OUT != 2)
+        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, true, TM>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn, *mask);
+    else
+        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, false, TM>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
+                           lda, ldb, ksplit, scale, C, tm, tn, ClampMask{nullptr, nullptr, 0.0f, 1});
+}
+
 template <int OUT>
 void launch_gemm(const uint16_t *A, const uint16_t *B, int M, int Nc, int Kc, int lda, int ldb, int splits, int ksplit,
                  float scale, void *C, hipStream_t st, const ClampMask *mask = nullptr)
 {
-    // 128 x 96 tiles, 3 stages of 28 KB, one workgroup per CU; persistent grid of at most 256 per split
-    const int tm = (M + 127) / 128, tn = (Nc + 95) / 96;
-    int grid = tm * tn;
-    if (grid > 256) grid = 256;
-    if (mask && OUT != 2)
-        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, true>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
-                           lda, ldb, ksplit, scale, C, tm, tn, *mask);
-    else
-        hipLaunchKernelGGL((gemm_bf16_nt_s3_kernel<3, OUT, false>), dim3(grid, splits), dim3(512), 0, st, A, B, M, Nc, Kc,
-                           lda, ldb, ksplit, scale, C, tm, tn, ClampMask{nullptr, nullptr, 0.0f, 1});
+    // 256-row tiles where they come out in whole rounds over the 256 CUs, at least two of them
+    const long tiles256 = (long)((M + 255) / 256) * ((Nc + 95) / 96);
+    if constexpr (OUT != 2) {
+        if (splits == 1 && tiles256 >= 512 && tiles256 % 256 == 0) {
+            launch_gemm_tm<OUT, 4>(A, B, M, Nc, Kc, lda, ldb, splits, ksplit, scale, C, st, mask);
+            return;
+        }
+    }
+    launch_gemm_tm<OUT, 2>(A, B, M, Nc, Kc, lda, ldb, splits, ksplit, scale, C, st, mask);
 }
 
 struct BwdPlan {

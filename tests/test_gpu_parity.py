@@ -631,6 +631,30 @@ def test_backward_clamp_masked(qb, bits, shape):
     assert torch.equal(a, dX0) and torch.equal(b, dW)
 
 
+def test_backward_clamp_masked_full_size_tall_tiles(qb):
+    """FFN-down at T = 4096 (dX runs on 256 x 96 tiles): the masked result is the plain one with exact zeros where the
+    activation lay outside its range; sampled entries against the oracle."""
+    T, N, K, G, bits, clip = 4096, 768, 3072, 128, 3, 1.5
+    say("bwd masked, tall tiles", (T, N, K))
+    W = wl.weight(N, K, seed=5)
+    X = wl.activation(T, K, seed=6)
+    dY = wl.grad_output_bf16(T, N, seed=7)
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, G)
+    Xd = X.to(DEV)
+    Xq, _ = qb.qb_quantize_act(Xd, clip)
+    dX0, _ = qb.qb_qlinear_bwd_ste(dY.to(DEV), Xq, clip, packed, h, bits, G, want_dw=False)
+    dX, _ = qb.qb_qlinear_bwd_ste_masked(dY.to(DEV), Xq, clip, packed, h, bits, G, X=Xd, want_dw=False)
+    torch.cuda.synchronize()
+    outX = X.abs() > clip
+    assert torch.equal(dX.cpu(), torch.where(outX, torch.zeros_like(dX0.cpu()), dX0.cpu()))
+    oc, oh, _, _ = oracle.quantize_groupwise(W.numpy(), bits, G)
+    r = np.random.default_rng(11)
+    ts, js = r.integers(0, T, 2048), r.integers(0, K, 2048)
+    ref = oracle.bwd_dx_sampled(wl.bf16_bits(dY), oc, oh, bits, ts, js)
+    got = dX0.float().cpu().numpy()[ts, js]
+    assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 2e-2
+
+
 @pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
 def test_backward_config3_full_size(qb, lin):
     """Configuration 3: T = 4096, 3-bit weights, 128 groups; sampled entries + norms."""
