@@ -256,19 +256,10 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     }
 }
 
-// global -> LDS copy by the load unit: every lane supplies its own global address, the data of
-// lane l lands at LDS address m0 + 16*l (also for the 12-byte form).  Written as inline assembly
-// on purpose: the compiler then keeps no book on these copies, and the kernel states itself, with
-// wait_vmcnt, which of them must have landed before a barrier.
-__device__ __forceinline__ void copy16_to_lds(const void *g, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
-}
-__device__ __forceinline__ void copy12_to_lds(const void *g, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx3 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
-}
-// the same with a wavefront-uniform base address (in SGPRs) and a 32-bit byte offset per lane
+// global -> LDS copy by the load unit: the global address of a lane is a wavefront-uniform base (in SGPRs) plus
+// the lane's 32-bit byte offset, the data of lane l lands at LDS address m0 + 16*l (also for the 12-byte form).
+// Written as inline assembly on purpose: the compiler then keeps no book on these copies, and the kernel states
+// itself, with wait_vmcnt, which of them must have landed before a barrier.
 __device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(off), "s"(lds_addr) : "memory", "m0");
@@ -1388,7 +1379,7 @@ extern "C" qb_status qb_qlinear_fwd_q8(const int8_t *Xq, const int32_t *rs_x, fl
     const int rpg = (int)(N / groups);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint8_t *p = static_cast<const uint8_t *>(packed);
-    const OutQ oq{Yq, rs_y, clip_out, act, nullptr};
+    const OutQ oq{Yq, rs_y, clip_out, act, nullptr, nullptr};
     hipLaunchKernelGGL(fill_zero_i32_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, st, rs_y, (int)T);
     switch (bits) {
         case 2: launch_bits_q8<2>(Xq, rs_x, p, h, rs_w, bias, oq, (int)T, (int)N, (int)K, rpg, hx, st); break;
