@@ -51,8 +51,9 @@ const char *qb_status_string(qb_status s);
  * (qb_unpack_codes gives the codes back in row-major order). */
 size_t qb_packed_nbytes(int64_t N, int64_t K, int bits);
 
-/* Host, pure.  Bytes of scratch that qb_qlinear_bwd_ste needs for the given shape (the other
- * calls need none).  Returns 0 for invalid arguments. */
+/* Host, pure.  Bytes of scratch that qb_qlinear_bwd_ste and its _masked and _asym variants need for
+ * the given shape (of the other calls only qb_power_iteration takes scratch, sized by
+ * qb_power_iteration_scratch_floats).  Returns 0 for invalid arguments. */
 size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K);
 
 /*
