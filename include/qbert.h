@@ -135,6 +135,30 @@ qb_status qb_qlinear_fwd(const int8_t *Xq, const int32_t *rs_x, float clip,
                          const float *bias, float *Y, int32_t *A4_debug, void *stream);
 
 /*
+ * qb_qlinear_fwd for several independent linear layers in as few launches as possible (the linears of
+ * different layers or micro-batches of a model: Sec. 3.2, every layer at its own bit-width).  `jobs` is a
+ * HOST array of n_jobs descriptors whose pointer fields are DEVICE pointers with the meaning of the
+ * arguments of qb_qlinear_fwd (no A4_debug output); it is read during the call only.  The jobs must
+ * not depend on each other: no job's Y may be another job's input or output.  Jobs of one bit-width
+ * whose size makes a launch's fixed cost matter share launches (their tiles are walked as one
+ * sequence by one persistent grid); the results are those of separate qb_qlinear_fwd calls, bit for
+ * bit.  All jobs are validated before anything is launched.
+ */
+typedef struct {
+    const int8_t *Xq;
+    const int32_t *rs_x;
+    float clip;
+    const void *packed;
+    const float *h;
+    const int32_t *rs_w;
+    int bits, groups;
+    int64_t T, N, K;
+    const float *bias;   /* [N] or NULL */
+    float *Y;            /* [T,N] */
+} qb_fwd_job;
+qb_status qb_qlinear_fwd_batched(const qb_fwd_job *jobs, int n_jobs, void *stream);
+
+/*
  * Forward with an 8-bit output: the layer's result goes through the activation quantizer at once
  * (Table 1 caption: every matrix product takes 8-bit activations; App. quantizer with k = 8), so
  * the next layer's input is written instead of the fp32 result, a quarter of its bytes.

@@ -19,7 +19,7 @@ QB_K_ALIGN = 64
 QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
-           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
+           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
            "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
@@ -35,6 +35,13 @@ class _QuantJob(ctypes.Structure):
     _fields_ = [("W", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("bits", ctypes.c_int),
                 ("groups", ctypes.c_int), ("packed", ctypes.c_void_p), ("h", ctypes.c_void_p), ("m", ctypes.c_void_p),
                 ("rs_w", ctypes.c_void_p)]
+
+
+class _FwdJob(ctypes.Structure):
+    _fields_ = [("Xq", ctypes.c_void_p), ("rs_x", ctypes.c_void_p), ("clip", ctypes.c_float), ("packed", ctypes.c_void_p),
+                ("h", ctypes.c_void_p), ("rs_w", ctypes.c_void_p), ("bits", ctypes.c_int), ("groups", ctypes.c_int),
+                ("T", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("bias", ctypes.c_void_p),
+                ("Y", ctypes.c_void_p)]
 
 
 class QBError(RuntimeError):
@@ -67,6 +74,8 @@ def load_library():
     lib.qb_quantize_act.argtypes = [vp, i64, i64, cf, vp, vp, vp]
     lib.qb_qlinear_fwd.restype = ci
     lib.qb_qlinear_fwd.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_fwd_batched.restype = ci
+    lib.qb_qlinear_fwd_batched.argtypes = [ctypes.POINTER(_FwdJob), ci, vp]
     lib.qb_qlinear_fwd_q8.restype = ci
     lib.qb_qlinear_fwd_q8.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, ci, cf, vp, vp, vp]
     lib.qb_qlinear_bwd_ste.restype = ci
@@ -209,6 +218,30 @@ def qb_qlinear_fwd(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, bias=None, 
     _check(lib.qb_qlinear_fwd(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(h), _p(rs_w), bits, groups,
                               T, N, K, _p(bias), _p(Y), _p(A4_debug), _stream()))
     return (Y, A4_debug) if A4_debug is not None else Y
+
+
+def qb_qlinear_fwd_batched(jobs):
+    """jobs: list of dicts with Xq, rs_x, clip, packed, h, rs_w, bits, groups, N and optionally bias, Y (allocated
+    here if absent).  Independent linear layers, as few launches as possible.  Returns the list of Y tensors."""
+    lib = load_library()
+    arr = (_FwdJob * max(len(jobs), 1))()
+    outs = []
+    for i, j in enumerate(jobs):
+        Xq = _dev(j["Xq"], torch.int8, "Xq")
+        T, K = Xq.shape
+        N = int(j["N"])
+        Y = j.get("Y")
+        if Y is None:
+            Y = torch.empty((T, N), dtype=torch.float32, device=Xq.device)
+        bias = j.get("bias")
+        arr[i] = _FwdJob(Xq.data_ptr(), _dev(j["rs_x"], torch.int32, "rs_x").data_ptr(), float(j["clip"]),
+                         _dev(j["packed"], torch.uint8, "packed").data_ptr(), _dev(j["h"], torch.float32, "h").data_ptr(),
+                         _dev(j["rs_w"], torch.int32, "rs_w").data_ptr(), int(j["bits"]), int(j["groups"]), T, N, K,
+                         _p(_dev(bias, torch.float32, "bias")) if bias is not None else None,
+                         _dev(Y, torch.float32, "Y").data_ptr())
+        outs.append(Y)
+    _check(lib.qb_qlinear_fwd_batched(arr, len(jobs), _stream()))
+    return outs
 
 
 def qb_qlinear_fwd_q8(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, clip_out, bias=None, act=0, Yq=None,

@@ -31,6 +31,10 @@ namespace {
 // a*b + c for |a|, |b| < 2^23 (full-rate 24-bit multiplier instead of the quarter-rate 32-bit one)
 __device__ __forceinline__ int qb_mad24(int a, int b, int c) { return __mul24(a, b) + c; }
 
+// A4 = 4*acc + corr.  The result fits int32 for every K the library accepts, but 4*acc alone can reach 2^31 at
+// K = 32768 with end-of-range operands: the sum is formed modulo 2^32 in unsigned arithmetic.
+__device__ __forceinline__ int qb_a4(int acc, int corr) { return (int)(4u * (uint32_t)acc + (uint32_t)corr); }
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
@@ -54,7 +58,6 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     // hx_rows: one activation scale per token (dynamic range) instead of hx, or null
     // q0: asymmetric group ranges: h holds Delta and q0 the lower end of every group, or null
     constexpr int THREADS = 64 * WM * WN;
-    constexpr bool QB_SKIP_STORES = false;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64 * KU, LDA = BK + 16;
     constexpr int CHUNKS_PER_ROW = BK / 16;
     constexpr int A_PER_THREAD = BM * CHUNKS_PER_ROW / THREADS;
@@ -200,18 +203,13 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int t0 = tile_m * BM + (wm * TM + tm) * 32 + 4 * hf;
-            if constexpr (QB_SKIP_STORES) {
-                int sum = 0;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
-                if (sum == 0x12345678) Y[0] = 1.0f;
-            } else if (q0) {
+            if (q0) {
                 const float zn = q0[nn / rows_per_group];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
                     if (t < T && n_ok) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                        const int a4 = qb_a4(acc[tm][tn][i], E2 * rs_x[t] + coln);
                         const size_t at = (size_t)t * N + n;
                         Y[at] = asym_value(a4, rs_x[t] + (K >> 1), L, hx, hg, zn) + bv;
                         if (A4out) A4out[at] = a4;
@@ -222,7 +220,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
                     if (t < T && n_ok) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                        const int a4 = qb_a4(acc[tm][tn][i], E2 * rs_x[t] + coln);
                         const size_t at = (size_t)t * N + n;
                         Y[at] = (hx_rows[t] * hg) * (float)a4 + bv;
                         if (A4out) A4out[at] = a4;
@@ -235,7 +233,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
-                    const int a4 = 4 * acc[tm][tn][i] + qb_mad24(E2, rx[i], coln);
+                    const int a4 = qb_a4(acc[tm][tn][i], qb_mad24(E2, rx[i], coln));
                     const size_t at = (size_t)t * N + n;
                     Y[at] = scale * (float)a4 + bv;
                     if (A4out) A4out[at] = a4;
@@ -245,7 +243,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
                     if (t < T && n_ok) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln;
+                        const int a4 = qb_a4(acc[tm][tn][i], E2 * rs_x[t] + coln);
                         const size_t at = (size_t)t * N + n;
                         Y[at] = scale * (float)a4 + bv;
                         if (A4out) A4out[at] = a4;
@@ -302,10 +300,9 @@ template <> struct SlotRead<8> {
 };
 
 // vmcnt(N) with the other counters left alone (gfx9 encoding of s_waitcnt's immediate)
-template <int N, bool ENABLE = true>
+template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
-    if constexpr (!ENABLE) return;
     static_assert(N >= 0 && N < 64, "vmcnt has six bits");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
 }
@@ -318,7 +315,7 @@ __device__ __forceinline__ void wait_vmcnt()
 // The copies run NSTAGE-1 steps ahead of the matrix cores through a ring of NSTAGE stage
 // buffers; a step ends with "the copies for the next step have landed" (vmcnt leaves the younger
 // ones in flight; copies return in issue order) and a workgroup barrier.
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int SKIP = 0>
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
@@ -326,7 +323,6 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     int tiles_m, int tiles_n)
 {
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
-    constexpr bool QB_SKIP_STORES = (SKIP & 4) != 0;  // SKIP is non-zero only in developer timing builds
     constexpr int NW = WM * WN;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 128;
     constexpr int A_DMA = BM / 8 / NW;          // per wavefront and step; each fills 8 rows of 128 bytes
@@ -356,8 +352,6 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     // grid is a multiple of 8, so a workgroup stays on the tiles of its own XCD's range).
     const int nwg = tiles_m * tiles_n;
     for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
-    long long ts_[6];
-    if constexpr (SKIP & 8) ts_[0] = __builtin_readcyclecounter();
     int logical;
     {
         const int xcd = work & 7, idx = work >> 3;
@@ -415,7 +409,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
 
 #define QB_FETCH(step, stage)                                                                             \
-    if constexpr (!(SKIP & 1)) {                                                                          \
+    {                                                                                                     \
         const uint32_t st_ = lds_base + (stage) * STAGE_BYTES;                                            \
         _Pragma("unroll") for (int i = 0; i < B_DMA; ++i) {                                               \
             if constexpr (BITS == 3) copy12_to_lds(b_base + (size_t)(step) * PAIR, b_off[i], st_ + A_BYTES + b_ldst[i]); \
@@ -439,10 +433,8 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
             }                                                                                             \
             _Pragma("unroll") for (int sub = 0; sub < 2; ++sub) {                                         \
                 v4i a[TM], b[TN];                                                                         \
-                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm) {                                       \
-                    if constexpr (SKIP & 2) { a[tm][0] = lane + tm; a[tm][1] = sub; a[tm][2] = kk; a[tm][3] = 1; } \
-                    else a[tm] = *reinterpret_cast<const v4i *>(lds_a + a_frag[kk * 2 + sub] + tm * 32 * BK); \
-                }                                                                                         \
+                _Pragma("unroll") for (int tm = 0; tm < TM; ++tm)                                         \
+                    a[tm] = *reinterpret_cast<const v4i *>(lds_a + a_frag[kk * 2 + sub] + tm * 32 * BK);  \
                 _Pragma("unroll") for (int tn = 0; tn < TN; ++tn) {                                       \
                     b[tn][0] = (int)d[tn][4 * sub + 0];                                                   \
                     b[tn][1] = (int)d[tn][4 * sub + 1];                                                   \
@@ -472,11 +464,9 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
 #pragma unroll
     for (int u = 0; u < D; ++u)
         if (u < nsteps) QB_FETCH(u, u)
-    if constexpr (SKIP & 8) ts_[1] = __builtin_readcyclecounter();
-    if (nsteps >= D) wait_vmcnt<(D - 1) * PER, !(SKIP & 1)>();
-    else wait_vmcnt<0, !(SKIP & 1)>();
+    if (nsteps >= D) wait_vmcnt<(D - 1) * PER>();
+    else wait_vmcnt<0>();
     QB_STEP_BARRIER();
-    if constexpr (SKIP & 8) ts_[2] = __builtin_readcyclecounter();
 
     int s = 0;
     for (; s + NSTAGE <= nsteps; s += NSTAGE) {
@@ -485,8 +475,8 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
             const bool more = s + u + D < nsteps;  // uniform
             if (more) QB_FETCH(s + u + D, (u + D) % NSTAGE)
             QB_MMA(u)
-            if (more) wait_vmcnt<(D - 1) * PER, !(SKIP & 1)>();  // copies for the next step have landed, younger ones fly on
-            else wait_vmcnt<0, !(SKIP & 1)>();
+            if (more) wait_vmcnt<(D - 1) * PER>();  // copies for the next step have landed, younger ones fly on
+            else wait_vmcnt<0>();
             QB_STEP_BARRIER();
         }
     }
@@ -495,14 +485,13 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
     for (int u = 0; u < NSTAGE - 1; ++u)
         if (s + u < nsteps) {
             QB_MMA(u)
-            wait_vmcnt<0, !(SKIP & 1)>();
+            wait_vmcnt<0>();
             QB_STEP_BARRIER();
         }
 #undef QB_FETCH
 #undef QB_MMA
 #undef QB_STEP_BARRIER
 
-    if constexpr (SKIP & 8) ts_[3] = __builtin_readcyclecounter();
     // ---- epilogue: exact integer corrections, then one scale per column.  Everything the
     // stores depend on is loaded first: a load issued between two stores would make the wavefront
     // wait for the older store to complete (loads and stores share one in-order counter) and turn
@@ -522,7 +511,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
         scale[tn] = hx * h[nn / rows_per_group];
         bv[tn] = bias ? bias[nn] : 0.0f;
     }
-    if (interior && (A4out == nullptr || (SKIP & 8))) {
+    if (interior && A4out == nullptr) {
         // fast path (uniform branch): straight-line code, one scalar base per 32x32 block and one
         // 32-bit lane offset per accumulator register
         const int t_wave = tile_m * BM + wm * TM * 32, n_wave = tile_n * BN + wn * TN * 32;
@@ -543,17 +532,10 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 char *y_blk = reinterpret_cast<char *>(y_wave + (size_t)tm * 32 * N + tn * 32);
-                if constexpr (QB_SKIP_STORES) {
-                    int sum = 0;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += acc[tm][tn][i];
-                    if (sum == 0x12345678) Y[0] = 1.0f;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int a4 = 4 * acc[tm][tn][i] + qb_mad24(E2, rx[tm][i], coln[tn]);
-                        __builtin_nontemporal_store(scale[tn] * (float)a4 + bv[tn], reinterpret_cast<float *>(y_blk + voff[i]));
-                    }
+                for (int i = 0; i < 16; ++i) {
+                    const int a4 = qb_a4(acc[tm][tn][i], qb_mad24(E2, rx[tm][i], coln[tn]));
+                    __builtin_nontemporal_store(scale[tn] * (float)a4 + bv[tn], reinterpret_cast<float *>(y_blk + voff[i]));
                 }
             }
     } else {
@@ -568,23 +550,13 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
                 for (int i = 0; i < 16; ++i) {
                     const int t = t0 + 8 * (i >> 2) + (i & 3);
                     if (t < T && n_ok[tn]) {
-                        const int a4 = 4 * acc[tm][tn][i] + E2 * rs_x[t] + coln[tn];
+                        const int a4 = qb_a4(acc[tm][tn][i], E2 * rs_x[t] + coln[tn]);
                         const size_t at = (size_t)t * N + n;
                         Y[at] = scale[tn] * (float)a4 + bv[tn];
                         if (A4out) A4out[at] = a4;
                     }
                 }
             }
-        }
-    }
-    if constexpr (SKIP & 8) {
-        ts_[4] = __builtin_readcyclecounter();
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        ts_[5] = __builtin_readcyclecounter();
-        if (tid == 0) {
-            long long *dbg = reinterpret_cast<long long *>(A4out) + (size_t)work * 8;
-            for (int i = 0; i < 6; ++i) dbg[i] = ts_[i];
-            dbg[6] = __builtin_amdgcn_s_getreg((3 << 11) | (6 << 6) | 4) /* HW_ID: cu/se bits */;
         }
     }
     }  // persistent tile loop
@@ -660,7 +632,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
             char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int a4 = 4 * acc[r] + rx[r];
+                const int a4 = qb_a4(acc[r], rx[r]);
                 __builtin_nontemporal_store(asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv,
                                             reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
             }
@@ -669,7 +641,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
             for (int r = 0; r < 16; ++r) {
                 const int t = t0 + tl + 8 * (r >> 2) + (r & 3);
                 if (t < T) {
-                    const int a4 = 4 * acc[r] + rx[r];
+                    const int a4 = qb_a4(acc[r], rx[r]);
                     const size_t at = (size_t)t * N + n0 + nl;
                     Y[at] = asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv;
                     if (A4out) A4out[at] = a4;
@@ -682,7 +654,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
         char *y_blk = reinterpret_cast<char *>(Y + (size_t)(t0 + tl) * N + n0 + nl);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int a4 = 4 * acc[r] + rx[r];
+            const int a4 = qb_a4(acc[r], rx[r]);
             __builtin_nontemporal_store(sc[r] * (float)a4 + bv,
                                         reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
         }
@@ -691,7 +663,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
         for (int r = 0; r < 16; ++r) {
             const int t = t0 + tl + 8 * (r >> 2) + (r & 3);
             if (t < T) {
-                const int a4 = 4 * acc[r] + rx[r];
+                const int a4 = qb_a4(acc[r], rx[r]);
                 const size_t at = (size_t)t * N + n0 + nl;
                 Y[at] = sc[r] * (float)a4 + bv;
                 if (A4out) A4out[at] = a4;
@@ -710,6 +682,48 @@ struct OutQ {
     const float *q0;       // fp32 output only: asymmetric group ranges (h holds Delta, q0 the lower ends), or null;
                            // not together with hx_rows (its values take the same place in the parameter block)
 };
+
+// One linear layer of a launch of the role-split kernel, and the list of them that one launch walks through.
+// The workgroups take the tiles of all problems in one sequence (each problem's share padded to a multiple of 8, so
+// that the renumbering by XCD stays inside a problem), the copy wavefronts running ahead across problem boundaries
+// as they do across tiles: a launch's fixed cost (start, first copies from HBM, drain) is paid once for the list.
+struct Problem {
+    const int8_t *Xq;
+    const int32_t *rs_x;
+    const uint8_t *packed;
+    const float *h;
+    const int32_t *rs_w;
+    const float *bias;
+    float *Y;
+    int32_t *A4out;
+    int T, N, K, rows_per_group;
+    float hx;
+    int tiles_m, tiles_n;
+    OutQ oq;
+};
+constexpr int kMaxGroup = QB_MAX_BATCH;
+struct Group {
+    int n;                            // problems in the list
+    int tile_start[kMaxGroup + 1];    // first tile of problem i in the launch's sequence; [n] = length of the sequence
+    Problem p[kMaxGroup];
+};
+// which problem tile `work` of the sequence belongs to (uniform over the workgroup)
+__device__ __forceinline__ int problem_of(const Group &g, int work)
+{
+    int pi = 0;
+    while (pi + 1 < g.n && work >= g.tile_start[pi + 1]) ++pi;
+    return pi;
+}
+// Tile `local` of a problem with nwg = tiles_m*tiles_n tiles -> its number in row-major order, or -1 for a padding
+// slot.  Workgroups are dealt to the 8 XCDs in turn; XCD x gets a contiguous range of tiles (n fastest), so that a
+// token panel is fetched into one L2 only.
+__device__ __forceinline__ int logical_tile(int local, int nwg)
+{
+    const int xcd = local & 7, idx = local >> 3;
+    const int q = nwg >> 3, r = nwg & 7;
+    if (idx >= q + (xcd < r ? 1 : 0)) return -1;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
 
 // One 32x32 block of the 8-bit output: the value that decides the code is formed in binary32 with one
 // rounding per step, scale = h_x*h_g, y = scale*float(A4), y = y + bias; then the optional GELU, the clamp to
@@ -735,7 +749,7 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
         const int4 v = *reinterpret_cast<const int4 *>(p_rx + tl + 8 * q);
         const int rx[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) y[4 * q + i] = scale * (float)(4 * acc[4 * q + i] + qb_mad24(e2, rx[i], coln)) + bv;  // |rs_x| < 2^23
+        for (int i = 0; i < 4; ++i) y[4 * q + i] = scale * (float)qb_a4(acc[4 * q + i], qb_mad24(e2, rx[i], coln)) + bv;  // |rs_x| < 2^23
     }
     if (act == 1) {
 #pragma unroll
@@ -782,11 +796,7 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
 // OUT: 0 fp32 Y, 1 the 8-bit output (OUTQ), 2 fp32 Y from asymmetric group ranges (ASYM; a variant of its own so
 // that the others carry none of its code)
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, int OUT>
-__global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
-    const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
-    const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
-    float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
-    int tiles_m, int tiles_n, OutQ oq)
+__global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(const Group g)
 {
     constexpr bool OUTQ = OUT == 1, ASYM = OUT == 2;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
@@ -823,10 +833,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nsteps = K / BK;
-    const int kunits = K >> 6;
-    const int ncb = (N + 31) >> 5;
-    const int nwg = tiles_m * tiles_n;
+    const int nseq = g.tile_start[g.n];  // tiles (and padding slots) of all problems of the launch
 
     // Roles.  The wavefronts of a workgroup are dealt to the four SIMDs of the CU in turn (wavefront w runs
     // on SIMD w%4), and a global load or global -> LDS copy issued on a SIMD that is busy with 32x32 MFMAs
@@ -839,14 +846,20 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
         // ================================ producer ================================
         const int p = SIMD3 ? wave >> 2 : wave - NC;
         int pb = 0;
-        for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
-            int logical;
-            {
-                const int xcd = work & 7, idx = work >> 3;
-                const int q = nwg >> 3, r = nwg & 7;
-                logical = xcd * q + (xcd < r ? xcd : r) + idx;
-            }
-            const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+        bool had_tile = false;
+        for (int work = blockIdx.x; work < nseq; work += gridDim.x) {
+            const int pi = problem_of(g, work);
+            const Problem &P = g.p[pi];
+            const int logical = logical_tile(work - g.tile_start[pi], P.tiles_m * P.tiles_n);
+            if (logical < 0) continue;  // padding slot (the consumers skip it as well)
+            const int T = P.T, N = P.N, K = P.K, rows_per_group = P.rows_per_group;
+            const int8_t *__restrict__ Xq = P.Xq;
+            const int32_t *__restrict__ rs_x = P.rs_x, *__restrict__ rs_w = P.rs_w;
+            const uint8_t *__restrict__ packed = P.packed;
+            const float *__restrict__ h = P.h, *__restrict__ bias = P.bias;
+            const OutQ &oq = P.oq;
+            const int nsteps = K / BK, kunits = K >> 6, ncb = (N + 31) >> 5;
+            const int tile_m = logical / P.tiles_n, tile_n = logical - tile_m * P.tiles_n;
             // token rows: lane l of a copy fills physical chunk l%8 of row l/8 of an 8-row block; the
             // chunk holds logical chunk (l%8) ^ ((row/2)%8): the swizzle that makes 16 consecutive
             // rows of one logical chunk land in 16 different 16-byte bank groups
@@ -911,7 +924,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #pragma unroll
             for (int u = 1; u < D; ++u)
                 if (u < nsteps) fetch(u, u);
-            if (OUTQ && work != (int)blockIdx.x) __builtin_amdgcn_s_barrier();  // barrier E of the previous tile
+            if (OUTQ && had_tile) __builtin_amdgcn_s_barrier();  // barrier E of the previous tile
+            had_tile = true;
             // step 0 has landed when only younger copies are outstanding: steps 1..D-1 and, in the wavefront
             // that issued them, the parameter copies (their number depends on bias and per-token scales)
             if (nsteps >= D) {
@@ -936,7 +950,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                 __builtin_amdgcn_s_barrier();
             }
         }
-        if (OUTQ && (int)blockIdx.x < nwg) __builtin_amdgcn_s_barrier();  // barrier E of the last tile
+        if (OUTQ && had_tile) __builtin_amdgcn_s_barrier();  // barrier E of the last tile
         return;
     }
 
@@ -965,27 +979,33 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
     uint8_t *stg = lds + STG_OFF;
     int *rowsum = reinterpret_cast<int *>(lds + STG_OFF + BM * BN);
     Quantizer qo;
-    int prev_t0 = -1;
+    int prev_t0 = -1, prev_T = 0;  // the tile whose row sums still sit in LDS, and its problem's token count and rs_y
+    int32_t *prev_rs_y = nullptr;
     if constexpr (OUTQ) {
-        qo.set(oq.clip_out, 255.0f);
         if (ctid < BM) rowsum[ctid] = 0;
     }
     auto flush_rowsums = [&]() {  // the previous tile's row sums -> rs_y; every LDS add to them is a barrier back
         if (ctid < BM) {
             const int v = rowsum[ctid];
             rowsum[ctid] = 0;
-            if (prev_t0 + ctid < T) atomicAdd(oq.rs_y + prev_t0 + ctid, v);
+            if (prev_t0 + ctid < prev_T) atomicAdd(prev_rs_y + prev_t0 + ctid, v);
         }
     };
 
-    for (int work = blockIdx.x; work < nwg; work += gridDim.x) {
-        int logical;
-        {
-            const int xcd = work & 7, idx = work >> 3;
-            const int q = nwg >> 3, r = nwg & 7;
-            logical = xcd * q + (xcd < r ? xcd : r) + idx;
-        }
-        const int tile_m = logical / tiles_n, tile_n = logical - tile_m * tiles_n;
+    for (int work = blockIdx.x; work < nseq; work += gridDim.x) {
+        const int pi = problem_of(g, work);
+        const Problem &P = g.p[pi];
+        const int logical = logical_tile(work - g.tile_start[pi], P.tiles_m * P.tiles_n);
+        if (logical < 0) continue;  // padding slot (the producers skip it as well)
+        const int T = P.T, N = P.N, K = P.K;
+        const float hx = P.hx;
+        const float *__restrict__ bias = P.bias;
+        float *__restrict__ Y = P.Y;
+        int32_t *__restrict__ A4out = P.A4out;
+        const OutQ &oq = P.oq;
+        const int nsteps = K / BK;
+        const int tile_m = logical / P.tiles_n, tile_n = logical - tile_m * P.tiles_n;
+        if constexpr (OUTQ) qo.set(oq.clip_out, 255.0f);
 
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
@@ -1108,6 +1128,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
                 }
             }
             prev_t0 = t0;
+            prev_T = T;
+            prev_rs_y = oq.rs_y;
         } else {
         const bool fast = (tile_m + 1) * BM <= T && (tile_n + 1) * BN <= N && A4out == nullptr;
 #pragma unroll
@@ -1131,27 +1153,50 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(
 #undef QB_BARRIER
 }
 
+// Adds one problem to a launch list of the role-split kernel with BM x BN tiles; false when the list is full.
+template <int BM, int BN>
+bool group_add(Group &g, const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
+               const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, const OutQ &oq)
+{
+    if (g.n >= kMaxGroup) return false;
+    Problem &P = g.p[g.n];
+    P.Xq = Xq; P.rs_x = rs_x; P.packed = packed; P.h = h; P.rs_w = rs_w; P.bias = bias; P.Y = Y; P.A4out = A4;
+    P.T = T; P.N = N; P.K = K; P.rows_per_group = rpg; P.hx = hx;
+    P.tiles_m = (T + BM - 1) / BM;
+    P.tiles_n = (N + BN - 1) / BN;
+    P.oq = oq;
+    const int nwg = P.tiles_m * P.tiles_n;
+    if (g.n == 0) g.tile_start[0] = 0;
+    // a problem's share of the sequence is padded to a multiple of 8 (the last one needs no padding)
+    g.tile_start[g.n] = (g.tile_start[g.n] + 7) & ~7;
+    g.tile_start[g.n + 1] = g.tile_start[g.n] + nwg;
+    ++g.n;
+    return true;
+}
+
+// One launch for the whole list: a persistent grid of at most grid_cap workgroups (a multiple of 8).
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, int OUT>
+void launch_group(const Group &g, hipStream_t st, int grid_cap)
+{
+    int grid = g.tile_start[g.n];
+    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
+    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, OUT>), dim3(grid),
+                       dim3(64 * (WM * WN + NPROD)), 0, st, g);
+}
+
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3 = false>
 void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
                int grid_cap, const float *hx_rows = nullptr, const float *q0 = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    int grid = tiles_m * tiles_n;
-    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
+    static_assert((BN + 63) / 64 * 64 <= BM, "the asymmetric variant needs room for q0 in the parameter block");
     const OutQ oq{nullptr, nullptr, 1.0f, 0, hx_rows, q0};
-    if constexpr ((BN + 63) / 64 * 64 <= BM) {  // (the asymmetric variant exists for the tile shapes it fits)
-        if (q0) {
-            hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 2>), dim3(grid),
-                               dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg,
-                               hx, tiles_m, tiles_n, oq);
-            return;
-        }
-    }
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 0>), dim3(grid),
-                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx,
-                       tiles_m, tiles_n, oq);
+    Group g;
+    g.n = 0;
+    group_add<BM, BN>(g, Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, oq);
+    if (q0) launch_group<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 2>(g, st, grid_cap);
+    else launch_group<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 0>(g, st, grid_cap);
 }
 
 // the same with the 8-bit output
@@ -1160,12 +1205,10 @@ void launch_ws_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, 
                   const float *bias, const OutQ &oq, int T, int N, int K, int rpg, float hx, hipStream_t st, int grid_cap)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    int grid = tiles_m * tiles_n;
-    if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_ws_kernel<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 1>), dim3(grid),
-                       dim3(64 * (WM * WN + NPROD)), 0, st, Xq, rs_x, packed, h, rs_w, bias, nullptr, nullptr, T, N, K, rpg,
-                       hx, tiles_m, tiles_n, oq);
+    Group g;
+    g.n = 0;
+    group_add<BM, BN>(g, Xq, rs_x, packed, h, rs_w, bias, nullptr, nullptr, T, N, K, rpg, hx, oq);
+    launch_group<BITS, TM, TN, WM, WN, NSTAGE, NPROD, SIMD3, 1>(g, st, grid_cap);
 }
 
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
@@ -1180,7 +1223,7 @@ void launch_cfg(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, co
 }
 
 // grid_cap: upper bound of workgroups (a multiple of 8); 0 = one workgroup per tile
-template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int SKIP = 0>
+template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE>
 void launch_dma(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, const float *h, const int32_t *rs_w,
                 const float *bias, float *Y, int32_t *A4, int T, int N, int K, int rpg, float hx, hipStream_t st,
                 int grid_cap = 0)
@@ -1189,7 +1232,7 @@ void launch_dma(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, co
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     int grid = tiles_m * tiles_n;
     if (grid_cap > 0 && grid > grid_cap) grid = grid_cap;
-    hipLaunchKernelGGL((qgemm_i8_dma_kernel<BITS, TM, TN, WM, WN, NSTAGE, SKIP>), dim3(grid), dim3(64 * WM * WN), 0, st,
+    hipLaunchKernelGGL((qgemm_i8_dma_kernel<BITS, TM, TN, WM, WN, NSTAGE>), dim3(grid), dim3(64 * WM * WN), 0, st,
                        Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, tiles_m, tiles_n);
 }
 
@@ -1254,89 +1297,6 @@ __global__ void fill_zero_i32_kernel(int32_t *p, int n)
     if (i < n) p[i] = 0;
 }
 
-#ifdef QB_TUNE
-}  // namespace
-}  // namespace qb
-// developer hook for tile sweeps (only in builds made with -DQB_TUNE, never in the shipped library)
-extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
-                                   const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N, int64_t K, float *Y,
-                                   void *stream);
-extern "C" int qb_tune_timeline(int stages, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
-                                const int32_t *rs_w, int64_t T, int64_t N, int64_t K, float *Y, long long *dbg, void *stream)
-{
-    using namespace qb;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint8_t *p = static_cast<const uint8_t *>(packed);
-    const int rpg = (int)(N / 128);
-    const float hx = 6.0f / 255.0f;
-    int32_t *d = reinterpret_cast<int32_t *>(dbg);
-    if (stages == 2) launch_dma<4, 2, 2, 2, 2, 2, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
-    else if (stages == 3) launch_dma<4, 2, 2, 2, 2, 3, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
-    else launch_dma<4, 2, 2, 2, 2, 4, 8>(Xq, rs_x, p, h, rs_w, nullptr, Y, d, (int)T, (int)N, (int)K, rpg, hx, st, 0);
-    return hipGetLastError() == hipSuccess ? 0 : 6;
-}
-extern "C" int qb_tune_qlinear_fwd(int cfg, const int8_t *Xq, const int32_t *rs_x, const void *packed, const float *h,
-                                   const int32_t *rs_w, int bits, int groups, int64_t T, int64_t N, int64_t K, float *Y,
-                                   void *stream)
-{
-    using namespace qb;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint8_t *p = static_cast<const uint8_t *>(packed);
-    const int rpg = (int)(N / groups);
-    const float hx = 6.0f / 255.0f;
-    const int cap = (cfg / 100) * 256;  // cfg = variant + 100 * (workgroups per CU of the persistent grid; 0 = one per tile)
-#define QB_T(B, a, b, c, d, e, f) launch_dma<B, a, b, c, d, e, f>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
-#define QB_TB(a, b, c, d, e, f) { if (bits == 2) QB_T(2, a, b, c, d, e, f); else if (bits == 3) QB_T(3, a, b, c, d, e, f); else if (bits == 4) QB_T(4, a, b, c, d, e, f); else QB_T(8, a, b, c, d, e, f); }
-    switch (cfg % 100) {
-        case 0: QB_TB(2, 2, 2, 2, 2, 0) break;   // 128x128 2 stages
-        case 1: QB_TB(2, 2, 2, 2, 3, 0) break;   // 128x128 3 stages
-        case 2: QB_TB(2, 2, 2, 2, 4, 0) break;   // 128x128 4 stages
-        case 3: QB_TB(4, 2, 2, 2, 3, 0) break;   // 256x128 3 stages
-        case 4: QB_TB(2, 4, 2, 2, 3, 0) break;   // 128x256 3 stages
-        case 5: QB_TB(4, 4, 2, 2, 2, 0) break;   // 256x256 2 stages
-        case 6: QB_TB(2, 1, 2, 2, 4, 0) break;   // 128x64 4 stages
-        case 7: QB_TB(1, 2, 4, 2, 3, 0) break;   // 128x128 8 waves 3 stages
-        case 8: QB_TB(2, 2, 4, 2, 3, 0) break;   // 256x128 8 waves 3 stages
-        case 9: QB_TB(4, 2, 2, 4, 2, 0) break;   // 256x256 8 waves 2 stages
-#define QB_W(B, a, b, c, d, e, f) launch_ws<B, a, b, c, d, e, f>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
-#define QB_WB(a, b, c, d, e, f) { if (bits == 2) QB_W(2, a, b, c, d, e, f); else if (bits == 3) QB_W(3, a, b, c, d, e, f); else if (bits == 4) QB_W(4, a, b, c, d, e, f); else QB_W(8, a, b, c, d, e, f); }
-        case 30: QB_WB(2, 2, 2, 2, 2, 1) break;   // ws 128x128 2 stages 1 producer
-        case 31: QB_WB(2, 2, 2, 2, 2, 2) break;   // ws 128x128 2 stages 2 producers
-        case 32: QB_WB(2, 2, 2, 2, 3, 2) break;   // ws 128x128 3 stages 2 producers
-        case 33: QB_WB(2, 2, 2, 2, 3, 4) break;   // ws 128x128 3 stages 4 producers
-        case 34: QB_WB(4, 2, 2, 2, 3, 2) break;   // ws 256x128 3 stages 2 producers
-        case 35: QB_WB(4, 4, 2, 2, 2, 2) break;   // ws 256x256 2 stages 2 producers
-        case 36: QB_WB(4, 4, 2, 2, 2, 4) break;   // ws 256x256 2 stages 4 producers
-        case 37: QB_WB(2, 2, 2, 2, 4, 2) break;   // ws 128x128 4 stages 2 producers
-#define QB_S3(B, e) launch_ws<B, 2, 1, 2, 3, e, 2, true>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
-#define QB_S3B(e) { if (bits == 2) QB_S3(2, e); else if (bits == 3) QB_S3(3, e); else if (bits == 4) QB_S3(4, e); else QB_S3(8, e); }
-        case 40: QB_S3B(3) break;   // 128x96 tiles, MFMAs on three SIMDs, copies on the fourth, 3 stages
-        case 41: QB_S3B(4) break;   // 4 stages
-#define QB_S3B(B, tm, tn) launch_ws<B, tm, tn, 2, 3, 3, 2, true>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st, cap)
-        case 47: { if (bits == 2) QB_S3B(2, 2, 2); else if (bits == 3) QB_S3B(3, 2, 2); else if (bits == 4) QB_S3B(4, 2, 2); else QB_S3B(8, 2, 2); } break;  // 128x192
-#define QB_SM(tm, tn, wm, wn, ku) launch_cfg<4, tm, tn, wm, wn, ku>(Xq, rs_x, p, h, rs_w, nullptr, Y, nullptr, (int)T, (int)N, (int)K, rpg, hx, st)
-        case 70: QB_SM(1, 1, 2, 2, 2); break;  // 64x64
-        case 71: QB_SM(1, 1, 1, 2, 2); break;  // 32x64
-        case 72: QB_SM(1, 1, 1, 1, 2); break;  // 32x32, one wavefront
-        case 73: QB_SM(1, 1, 1, 4, 2); break;  // 32x128
-        case 74: QB_SM(1, 1, 1, 2, 4); break;  // 32x64, 256 features per step
-        case 75: QB_SM(1, 1, 1, 1, 4); break;  // 32x32
-        // dissection of 128x128 2 stages: skip copies (1), LDS fragment reads (2), stores (4)
-        case 10: QB_TB(2, 2, 2, 2, 2, 1) break;
-        case 12: QB_TB(2, 2, 2, 2, 2, 4) break;
-        case 14: QB_TB(2, 2, 2, 2, 2, 7) break;
-        case 11: QB_TB(2, 2, 2, 2, 2, 2) break;
-        case 13: QB_TB(2, 2, 2, 2, 2, 6) break;
-        case 15: QB_TB(2, 2, 2, 2, 2, 5) break;
-        case 16: QB_TB(2, 2, 2, 2, 3, 4) break;
-        case 17: QB_TB(2, 2, 2, 2, 3, 6) break;
-        default: return -1;
-    }
-    return hipGetLastError() == hipSuccess ? 0 : 6;
-}
-namespace qb {
-namespace {
-#endif
 }  // namespace
 }  // namespace qb
 
@@ -1361,6 +1321,77 @@ extern "C" qb_status qb_qlinear_fwd(const int8_t *Xq, const int32_t *rs_x, float
         case 4: launch_bits<4>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st); break;
         default: launch_bits<8>(Xq, rs_x, p, h, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st); break;
     }
+    return launch_status();
+}
+
+namespace {
+qb_status check_fwd_job(const qb_fwd_job &j)
+{
+    if (!j.Xq || !j.rs_x || !j.packed || !j.h || !j.rs_w || !j.Y) return QB_ERR_NULL;
+    if (!bits_ok(j.bits)) return QB_ERR_BITS;
+    if (j.T <= 0 || j.T > (1 << 24) || j.N <= 0 || j.N > (1 << 24) || !k_ok(j.K) || j.groups <= 0 || j.N % j.groups != 0)
+        return QB_ERR_SHAPE;
+    if (!(j.clip > 0.0f) || !(j.clip < 3.0e38f)) return QB_ERR_CLIP;
+    return QB_OK;
+}
+
+template <int BITS>
+void launch_job(const qb_fwd_job &j, hipStream_t st)
+{
+    launch_bits<BITS>(j.Xq, j.rs_x, static_cast<const uint8_t *>(j.packed), j.h, j.rs_w, j.bias, j.Y, nullptr, (int)j.T, (int)j.N,
+                      (int)j.K, (int)(j.N / j.groups), j.clip / 255.0f, st);
+}
+
+// the jobs of one bit-width: those of a size where a launch's fixed cost matters share launches of the
+// role-split kernel (128x96 tiles where 96 divides N, else 128x128), the others go one by one
+template <int BITS>
+void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
+{
+    Group g96, g128;
+    g96.n = g128.n = 0;
+    const OutQ none{nullptr, nullptr, 1.0f, 0, nullptr, nullptr};
+    for (int i = 0; i < n_jobs; ++i) {
+        const qb_fwd_job &j = jobs[i];
+        if (j.bits != BITS) continue;
+        const long tiles128 = (long)((j.T + 127) / 128) * ((j.N + 127) / 128);
+        if (j.K % 128 != 0 || tiles128 <= 160 || tiles128 > 1024) {
+            launch_job<BITS>(j, st);
+            continue;
+        }
+        const uint8_t *p = static_cast<const uint8_t *>(j.packed);
+        const int rpg = (int)(j.N / j.groups);
+        const float hx = j.clip / 255.0f;
+        if (j.N % 96 == 0) {
+            if (g96.n == kMaxGroup) {
+                launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
+                g96.n = 0;
+            }
+            group_add<128, 96>(g96, j.Xq, j.rs_x, p, j.h, j.rs_w, j.bias, j.Y, nullptr, (int)j.T, (int)j.N, (int)j.K, rpg, hx, none);
+        } else {
+            if (g128.n == kMaxGroup) {
+                launch_group<BITS, 2, 2, 2, 2, 3, 4, false, 0>(g128, st, 256);
+                g128.n = 0;
+            }
+            group_add<128, 128>(g128, j.Xq, j.rs_x, p, j.h, j.rs_w, j.bias, j.Y, nullptr, (int)j.T, (int)j.N, (int)j.K, rpg, hx, none);
+        }
+    }
+    if (g96.n) launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
+    if (g128.n) launch_group<BITS, 2, 2, 2, 2, 3, 4, false, 0>(g128, st, 256);
+}
+}  // namespace
+
+extern "C" qb_status qb_qlinear_fwd_batched(const qb_fwd_job *jobs, int n_jobs, void *stream)
+{
+    if (n_jobs < 0 || (n_jobs > 0 && !jobs)) return QB_ERR_NULL;
+    for (int i = 0; i < n_jobs; ++i) {
+        const qb_status s = check_fwd_job(jobs[i]);
+        if (s != QB_OK) return s;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    launch_jobs_of_width<2>(jobs, n_jobs, st);
+    launch_jobs_of_width<3>(jobs, n_jobs, st);
+    launch_jobs_of_width<4>(jobs, n_jobs, st);
+    launch_jobs_of_width<8>(jobs, n_jobs, st);
     return launch_status();
 }
 

@@ -1,0 +1,238 @@
+"""GPU parity at full size: whole-output comparisons of the kernels the benchmark times, the batched forward,
+configuration 4 (12-layer stack at 32 x 384 tokens with per-layer bits) forward and backward, and per-element
+bounds for the STE backward at configuration-3 size.  Everything goes through the C ABI; the reference is the
+CPU oracle (its OpenMP build, the same source)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1909_05840_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+BITS = (2, 3, 4, 8)
+CLIP = 6.0
+DEV = "cuda:0"
+G = 128
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def quantized_inputs(qb, N, K, T, bits, seed, groups=G, uniform=False):
+    W = wl.weight_uniform(N, K, seed=seed, lo=-0.1, hi=0.1) if uniform else wl.weight(N, K, seed=seed)
+    X = wl.activation(T, K, seed=seed + 1)
+    packed, h, m, rs_w = qb.qb_quantize_groupwise(W.to(DEV), bits, groups)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    oc, oh, _, ors = oracle.quantize_groupwise(W.numpy(), bits, groups)
+    oq, orx = oracle.quantize_act(X.numpy(), CLIP)
+    torch.cuda.synchronize()
+    assert (qb.qb_unpack_codes(packed, N, K, bits).cpu().numpy() == oc).all()
+    assert (Xq.cpu().numpy() == oq).all()
+    assert (rs_w.cpu().numpy() == ors).all() and (rs_x.cpu().numpy() == orx).all()
+    return dict(W=W, X=X, packed=packed, h=h, rs_w=rs_w, Xq=Xq, rs_x=rs_x, oc=oc, oh=oh, oq=oq)
+
+
+def assert_rel(Y, Yo, tol=1e-6):
+    err = np.abs(Y.astype(np.float64) - Yo)
+    bad = err > tol * np.abs(Yo)
+    assert not bad.any(), "%d elements outside %g relative, worst %g" % (bad.sum(), tol, (err / np.maximum(np.abs(Yo), 1e-300)).max())
+
+
+# (T, N, K): every kernel the tile dispatch can choose for a large problem, at the benchmark's own sizes and with
+# ragged edges: 128x96 tiles on three SIMDs (N = 768 at 4096 tokens; 4000 x 760 ragged in both directions),
+# role-split 128x128 (4096 x 1024 x 1024; 2049 x 1530 ragged), two plain workgroups per CU (4096 x 3072 x 768;
+# 4090 x 3000 ragged).
+TIMED_KERNEL_SHAPES = [(4096, 768, 3072), (4096, 768, 768), (4096, 2304, 768), (4000, 760, 256), (4096, 1024, 1024),
+                       (2049, 1530, 256), (4096, 3072, 768), (4090, 3000, 256)]
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", TIMED_KERNEL_SHAPES)
+def test_forward_whole_output_of_timed_kernels(qb, bits, shape):
+    """Y of the plain call (the launch bench.py times: streaming-store write-out) and A4 of the checked call, every
+    element against the oracle."""
+    T, N, K = shape
+    groups = G if N % G == 0 else (N // 2 if N % 2 == 0 else 1)
+    say("fwd whole output", shape, "bits", bits)
+    d = quantized_inputs(qb, N, K, T, bits, seed=31 * N + K + bits, groups=groups)
+    bias = wl.activation(1, N, seed=9)[0].contiguous()
+    Y = torch.full((T, N), float("nan"), dtype=torch.float32, device=DEV)
+    qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, groups, N, Y=Y)
+    Yb = torch.full((T, N), float("nan"), dtype=torch.float32, device=DEV)
+    qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, groups, N, bias=bias.to(DEV), Y=Yb)
+    _, A4 = qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, groups, N, want_a4=True)
+    torch.cuda.synchronize()
+    Yo, A4o, _ = oracle.qlinear_fwd(d["oq"], CLIP, d["oc"], d["oh"], bits, openmp=True)
+    assert (A4.cpu().numpy() == A4o).all()
+    Yh = Y.cpu().numpy()
+    assert_rel(Yh, Yo)
+    assert (Yh[A4o == 0] == 0).all()
+    # with bias: (Y + b) - b recovers Y to a rounding of the sum
+    Ybh = Yb.cpu().numpy().astype(np.float64)
+    b = bias.numpy().astype(np.float64)[None, :]
+    assert (np.abs(Ybh - (Yo + b)) <= 1e-6 * np.abs(Yo) + 2.0 ** -23 * np.abs(Yo + b)).all()
+
+
+def test_forward_batched_matches_single_calls(qb):
+    """The benchmark's 16 jobs (4 linears x 4 bit-widths at 4096 tokens) plus jobs that do not share launches (few
+    tiles, K not a multiple of 128, N not a multiple of 96, a very large one) in one call: every Y bit for bit the Y
+    of the single call, and one job of every bit-width element by element against the oracle."""
+    jobs, singles, checks = [], [], []
+    shapes = [(4096, N, K) for (_, N, K) in wl.BERT_BASE_LINEARS]
+    extra = [(128, 768, 3072, 4), (1000, 130, 192, 3), (2049, 1530, 256, 2), (4096, 1024, 1024, 8), (300, 96, 128, 4),
+             (16384, 1024, 1024, 2), (4096, 768, 768, 4)]
+    case = 0
+    for bits in BITS:
+        for (T, N, K) in shapes:
+            d = quantized_inputs(qb, N, K, T, bits, seed=17 * N + K + bits + case)
+            bias = wl.activation(1, N, seed=case)[0].contiguous().to(DEV) if case % 3 == 0 else None
+            jobs.append(dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=bits,
+                             groups=G, N=N, bias=bias))
+            singles.append(qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, G, N, bias=bias))
+            if (N, K) == (768, 3072):
+                checks.append((len(jobs) - 1, d, bits, bias))
+            case += 1
+    for (T, N, K, bits) in extra:
+        groups = G if N % G == 0 else (N // 2 if N % 2 == 0 else 1)
+        d = quantized_inputs(qb, N, K, T, bits, seed=5 * N + K + T, groups=groups)
+        jobs.append(dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=bits,
+                         groups=groups, N=N, bias=None))
+        singles.append(qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, groups, N))
+    for j in jobs:  # outputs pre-filled: every element must be written by the batched call
+        T = j["Xq"].shape[0]
+        j["Y"] = torch.full((T, j["N"]), float("nan"), dtype=torch.float32, device=DEV)
+    say("fwd batched", len(jobs), "jobs")
+    Ys = qb.qb_qlinear_fwd_batched(jobs)
+    torch.cuda.synchronize()
+    for i, (Yb, Y1) in enumerate(zip(Ys, singles)):
+        assert torch.equal(Yb, Y1), "job %d differs from the single call" % i
+    for (i, d, bits, bias) in checks:
+        Yo, _, _ = oracle.qlinear_fwd(d["oq"], CLIP, d["oc"], d["oh"], bits, openmp=True)
+        Yh = Ys[i].cpu().numpy().astype(np.float64)
+        if bias is not None:
+            b = bias.cpu().numpy().astype(np.float64)[None, :]
+            assert (np.abs(Yh - (Yo + b)) <= 1e-6 * np.abs(Yo) + 2.0 ** -23 * np.abs(Yo + b)).all()
+        else:
+            assert_rel(Yh, Yo)
+    # an empty list is a valid call
+    assert qb.qb_qlinear_fwd_batched([]) == []
+
+
+def test_forward_batched_rejects_bad_jobs_before_launching(qb):
+    d = quantized_inputs(qb, 768, 768, 256, 4, seed=3)
+    good = dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=4, groups=G, N=768)
+    Y0 = torch.full((256, 768), 7.0, dtype=torch.float32, device=DEV)
+    bad = dict(good, bits=5)
+    with pytest.raises(qb.QBError) as e:
+        qb.qb_qlinear_fwd_batched([dict(good, Y=Y0), bad])
+    assert e.value.status == 2
+    torch.cuda.synchronize()
+    assert (Y0 == 7.0).all()  # nothing was launched
+
+
+# ---- configuration 4: 12-layer stack, T = 32 x 384 = 12288, per-layer bits ---------------------------------------
+CFG4_T = 12288
+
+
+def cfg4_bit_vectors():
+    vecs = {"seeded": wl.layer_bits(12, seed=wl.config_seed(3, 0)), "table6-SST-2": wl.PAPER_BITS_2_3["SST-2"],
+            "table7-SST-2": wl.PAPER_BITS_2_4["SST-2"]}
+    return vecs
+
+
+def sampled_forward(qb, T, N, K, bits, seed, n_samples=1024):
+    d = quantized_inputs(qb, N, K, T, bits, seed=seed)
+    Y, A4 = qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, G, N, want_a4=True)
+    Yp = torch.full((T, N), float("nan"), dtype=torch.float32, device=DEV)
+    qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, G, N, Y=Yp)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Yp)
+    Y, A4 = Y.cpu().numpy(), A4.cpu().numpy()
+    r = np.random.default_rng(seed)
+    ts = np.concatenate([r.integers(0, T, n_samples), [0, T - 1, 0, T - 1]])
+    ns = np.concatenate([r.integers(0, N, n_samples), [0, N - 1, N - 1, 0]])
+    Ys, A4s = oracle.qlinear_fwd_sampled(d["oq"], CLIP, d["oc"], d["oh"], bits, ts, ns)
+    assert (A4[ts, ns] == A4s).all()
+    assert_rel(Y[ts, ns], Ys)
+    # exact at any size: column sums and row sums of A4 against integer identities
+    L = 2 ** bits - 1
+    colx = (2 * d["oq"].astype(np.int64) + 1).sum(0)
+    assert (A4.astype(np.int64).sum(0) == ((2 * d["oc"].astype(np.int64) - L) * colx[None, :]).sum(1)).all()
+    roww = (2 * d["oc"].astype(np.int64) - L).sum(0)
+    assert (A4.astype(np.int64).sum(1) == ((2 * d["oq"].astype(np.int64) + 1) * roww[None, :]).sum(1)).all()
+    return d
+
+
+@pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
+def test_config4_forward_all_linears(qb, lin):
+    """Every linear of the layer at 12288 tokens, at every bit-width the seeded vector and the paper's Table 6 / 7
+    rows assign to some layer: sampled outputs, and the exact column- and row-sum identities over the whole A4."""
+    name, N, K = lin
+    widths = sorted(set(b for v in cfg4_bit_vectors().values() for b in v))
+    assert set(widths) <= set(BITS)
+    for bits in widths:
+        say("cfg4 fwd", lin, "bits", bits)
+        sampled_forward(qb, CFG4_T, N, K, bits, seed=wl.config_seed(3, N + K + bits))
+
+
+@pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
+def test_config4_backward_all_linears(qb, lin):
+    """STE backward at 12288 tokens with the bit-widths of the seeded per-layer vector: sampled entries of dX and dW
+    against the oracle (relative Frobenius over the sample, and a bound per sampled element)."""
+    name, N, K = lin
+    T = CFG4_T
+    for bits in sorted(set(cfg4_bit_vectors()["seeded"])):
+        say("cfg4 bwd", lin, "bits", bits)
+        d = quantized_inputs(qb, N, K, T, bits, seed=wl.config_seed(3, 100 + N + K + bits))
+        dY = wl.grad_output_bf16(T, N, seed=wl.config_seed(3, 200 + N + bits))
+        dX, dW = qb.qb_qlinear_bwd_ste(dY.to(DEV), d["Xq"], CLIP, d["packed"], d["h"], bits, G)
+        torch.cuda.synchronize()
+        r = np.random.default_rng(N + K + bits)
+        n_s = 4096
+        ts, js, ns = r.integers(0, T, n_s), r.integers(0, K, n_s), r.integers(0, N, n_s)
+        b16 = wl.bf16_bits(dY)
+        sdx = oracle.bwd_dx_sampled(b16, d["oc"], d["oh"], bits, ts, js)
+        sdw = oracle.bwd_dw_sampled(b16, d["oq"], CLIP, ns, js)
+        gdx = dX.float().cpu().numpy()[ts, js].astype(np.float64)
+        gdw = dW.cpu().numpy()[ns, js].astype(np.float64)
+        assert np.linalg.norm(gdx - sdx) / np.linalg.norm(sdx) <= 2e-2
+        assert np.linalg.norm(gdw - sdw) / np.linalg.norm(sdw) <= 1e-4
+        # per element: magnitude sums of the products bound the rounding of operands and accumulation
+        dYf = dY.float().numpy().astype(np.float64)
+        What = oracle.dequantize_groupwise(d["oc"], d["oh"], bits).astype(np.float64)
+        sabs_x = np.einsum("sn,ns->s", np.abs(dYf[ts, :]), np.abs(What[:, js]))
+        assert (np.abs(gdx - sdx) <= 2.0 ** -8 * np.abs(sdx) + 2.0 ** -8 * sabs_x).all()
+        Xhat = oracle.dequantize_act(d["oq"], CLIP).astype(np.float64)
+        sabs_w = np.einsum("ts,ts->s", np.abs(dYf[:, ns]), np.abs(Xhat[:, js]))
+        assert (np.abs(gdw - sdw) <= 2.0 ** -10 * sabs_w).all()
+
+
+# ---- configuration 3 at full size: whole matrices ------------------------------------------------------------------
+@pytest.mark.parametrize("lin", wl.BERT_BASE_LINEARS, ids=[l[0] for l in wl.BERT_BASE_LINEARS])
+def test_backward_config3_whole_matrices(qb, lin):
+    """T = 4096, 3-bit weights: dX and dW complete against the oracle's binary64 products: relative Frobenius norm
+    over the whole matrix and a bound for every element.  Error model: What is rounded to bf16 (2^-9 relative per
+    operand element), products are accumulated in fp32 (at most N * 2^-24 of the magnitude sum), dX is rounded to
+    bf16 on the way out (2^-9 of its value); dW has exact operands (dY and 2x'+1 are bf16 values) and differs by
+    the fp32 summation order only (at most T * 2^-24 of the magnitude sum)."""
+    name, N, K = lin
+    T, bits = 4096, 3
+    say("bwd cfg3 whole", lin)
+    d = quantized_inputs(qb, N, K, T, bits, seed=wl.config_seed(2, N + K))
+    dY = wl.grad_output_bf16(T, N, seed=wl.config_seed(2, 2))
+    dX, dW = qb.qb_qlinear_bwd_ste(dY.to(DEV), d["Xq"], CLIP, d["packed"], d["h"], bits, G)
+    torch.cuda.synchronize()
+    odX, odW = oracle.qlinear_bwd_ste(wl.bf16_bits(dY), d["oq"], CLIP, d["oc"], d["oh"], bits, openmp=True)
+    gdx = dX.float().cpu().numpy().astype(np.float64)
+    gdw = dW.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(gdx - odX) / np.linalg.norm(odX) <= 2e-2
+    assert np.linalg.norm(gdw - odW) / np.linalg.norm(odW) <= 1e-4
+    dYa = np.abs(dY.float().numpy().astype(np.float64))
+    sabs_x = dYa @ np.abs(oracle.dequantize_groupwise(d["oc"], d["oh"], bits).astype(np.float64))
+    bad = np.abs(gdx - odX) > 2.0 ** -8 * np.abs(odX) + 2.0 ** -8 * sabs_x
+    assert not bad.any(), "dX: %d elements outside the bound" % bad.sum()
+    sabs_w = dYa.T @ np.abs(oracle.dequantize_act(d["oq"], CLIP).astype(np.float64))
+    bad = np.abs(gdw - odW) > 2.0 ** -12 * sabs_w
+    assert not bad.any(), "dW: %d elements outside the bound" % bad.sum()
