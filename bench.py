@@ -6,19 +6,24 @@ Workload (benchmark configs[1]): the four linears of one BERT-base encoder l
 matrix, weight bit-widths {2,3,4,8}, forward only, synthetic seeded data.
 
 One step = one pass of the forward hot path over that batch for every bit-width of the sweep:
-  16 x quantize/pack of the fp32 master weights (one batched launch), 4 x 8-bit activation quantize,
-  16 x int8 MFMA GEMM with the scale epilogue.
+  16 x quantize/pack of fp32 master weights (16 distinct matrices, one batched launch), 4 x 8-bit activation
+  quantize, 16 x int8 MFMA GEMM with the scale epilogue (one batched call: the 16 independent linears share
+  one persistent launch per bit-width, 4 launches).
 All inputs are resident in HBM before the timed region.  `value` = int8 GEMM operations of the
 step (2*T*N*K summed) divided by the wall time of the whole step, in TOPS.
 
-The timed region replays ONE captured HIP graph per step (it holds the 21 kernels of the step and
-nothing else); --no-graph launches every kernel eagerly instead.  The per-kernel averages in
-`roofline` and `kernels` come from a second pass in the same run, on the same stream: the 16 GEMMs (and
-the 4 activation quantizers, four times over) as one graph of 16 kernels, replayed ten times between two
+The timed region replays ONE captured HIP graph per step (it holds the 9 kernels of the step and
+nothing else); --no-graph launches every kernel eagerly instead.  Before the warm-up steps the step is
+replayed for at least 60 ms so that the clocks have settled whatever --warmup says.  The per-kernel
+averages in `roofline` and `kernels` come from a second pass in the same run, on the same stream: the GEMM
+launches (and the 4 activation quantizers, four times over) as one graph, replayed ten times between two
 HIP events; the single quantize/pack kernel behind a cache-emptying fill, as the difference to the fill alone.
 
-Also printed on the same JSON line: the STE backward (configs[2]) and the embedding path
-(configs[4]) timed outside the K steps, and the CPU oracle timed on a bounded sample.
+Also printed on the same JSON line: every GEMM shape on its own (one launch, and four independent problems of
+the shape in one batched call), the STE backward (configs[2]), one iteration of the 12-layer stack
+(configs[3]: quantize/pack + act-quant + forward + backward at 12288 tokens with per-layer bits), BERT-large
+(configs[4]: GEMMs at 32768 tokens, the 24-layer quantize/pack aggregate over 1.2 GB of distinct weights, the
+embedding path), all timed outside the K steps, and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
@@ -46,7 +51,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--gemm-streams", type=int, default=1, help="streams the step's independent GEMMs are spread over")
+    ap.add_argument("--single-launches", action="store_true",
+                    help="one launch per GEMM (16 qb_qlinear_fwd calls) instead of the batched call")
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference dispatch for HBM byte counters)")
@@ -72,7 +78,10 @@ def main():
         return
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
-    Ws = [wl.weight(N, K, seed=wl.config_seed(1, i)).to(dev) for i, (_, N, K) in enumerate(linears)]
+    # one fp32 master matrix per (bit-width, linear): 16 distinct matrices, 113 MB, so that no quantize/pack
+    # job finds its input in a cache because another job of the launch has just read it
+    Ws = {(b, i): wl.weight(N, K, seed=wl.config_seed(1, 100 * b + i)).to(dev)
+          for b in BITS_SWEEP for i, (_, N, K) in enumerate(linears)}
     Xs = [wl.activation(T, K, seed=wl.config_seed(1, 10 + i)).to(dev) for i, (_, N, K) in enumerate(linears)]
     # ---- outputs, allocated once -----------------------------------------------------------------
     q = {}
@@ -84,9 +93,14 @@ def main():
                              rs_w=torch.empty(N, dtype=torch.int32, device=dev))
     acts = [dict(Xq=torch.empty((T, K), dtype=torch.int8, device=dev),
                  rs_x=torch.empty(T, dtype=torch.int32, device=dev)) for (_, N, K) in linears]
-    Ys = [torch.empty((T, N), dtype=torch.float32, device=dev) for (_, N, K) in linears]
+    # the 16 GEMMs of a step are independent jobs of one batched call: each has its own output
+    Ys = {(b, i): torch.empty((T, N), dtype=torch.float32, device=dev)
+          for b in BITS_SWEEP for i, (_, N, K) in enumerate(linears)}
 
-    quant_jobs = [dict(W=Ws[i], bits=b, groups=GROUPS, **q[(b, i)]) for b in BITS_SWEEP for i in range(len(linears))]
+    quant_jobs = [dict(W=Ws[(b, i)], bits=b, groups=GROUPS, **q[(b, i)]) for b in BITS_SWEEP for i in range(len(linears))]
+    gemm_jobs = [dict(Xq=acts[i]["Xq"], rs_x=acts[i]["rs_x"], clip=CLIP, packed=q[(b, i)]["packed"], h=q[(b, i)]["h"],
+                      rs_w=q[(b, i)]["rs_w"], bits=b, groups=GROUPS, N=N, Y=Ys[(b, i)])
+                 for b in BITS_SWEEP for i, (_, N, K) in enumerate(linears)]
 
     def stage_quantize():
         qb.qb_quantize_groupwise_batched(quant_jobs)   # all 16 matrices of the step, one launch
@@ -95,30 +109,12 @@ def main():
         for i in range(len(linears)):
             qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
 
-    side_all = [torch.cuda.Stream(device=dev) for _ in range(3)]   # default priority
-
-    def stage_gemm(nstreams=None):
-        side = side_all[:max(0, (args.gemm_streams if nstreams is None else nstreams) - 1)]
-        if not side:
-            for b in BITS_SWEEP:
-                for i, (_, N, K) in enumerate(linears):
-                    o = q[(b, i)]
-                    qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
-                                      Y=Ys[i])
-            return
-        # the GEMMs of different linears are independent: linear i goes to stream i % n (fork / join on events)
-        cur = torch.cuda.current_stream()
-        lanes = [cur] + side
-        for s_ in side:
-            s_.wait_stream(cur)
-        for i, (_, N, K) in enumerate(linears):
-            with torch.cuda.stream(lanes[i % len(lanes)]):
-                for b in BITS_SWEEP:
-                    o = q[(b, i)]
-                    qb.qb_qlinear_fwd(acts[i]["Xq"], acts[i]["rs_x"], CLIP, o["packed"], o["h"], o["rs_w"], b, GROUPS, N,
-                                      Y=Ys[i])
-        for s_ in side:
-            cur.wait_stream(s_)
+    def stage_gemm():
+        if args.single_launches:   # one launch per linear, as separate qb_qlinear_fwd calls
+            for j in gemm_jobs:
+                qb.qb_qlinear_fwd(j["Xq"], j["rs_x"], CLIP, j["packed"], j["h"], j["rs_w"], j["bits"], GROUPS, j["N"], Y=j["Y"])
+        else:
+            qb.qb_qlinear_fwd_batched(gemm_jobs)   # one persistent launch per bit-width
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
@@ -128,7 +124,8 @@ def main():
         torch.cuda.synchronize()
 
     stages = [stage_quantize, stage_act, stage_gemm]
-    n_quant, n_act, n_gemm = 1, 4, 16      # kernels per stage
+    n_quant, n_act = 1, 4                  # kernels per stage
+    n_gemm = 16 if args.single_launches else len(BITS_SWEEP)
     stream = torch.cuda.Stream(device=dev)   # default priority
     use_graph = not args.no_graph
 
@@ -146,6 +143,12 @@ def main():
         whole_step()
         stream.synchronize()
         one_step = capture(whole_step) if use_graph else whole_step
+        # settle the clocks: the first tens of milliseconds after idle run at other clocks than the steady state
+        t_w = time.perf_counter()
+        while time.perf_counter() - t_w < 0.06:
+            for _ in range(20):
+                one_step()
+            stream.synchronize()
         for _ in range(args.warmup):
             one_step()
         stream.synchronize()
@@ -156,27 +159,6 @@ def main():
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-
-        # ---- the same step with the GEMMs of different linears on two streams (they are independent of each
-        # other; in a network they would belong to two micro-batches): reported beside `value`, not as `value`
-        overlapped = None
-        if use_graph and not args.no_extras and args.gemm_streams == 1:
-            def step2():
-                stage_quantize()
-                stage_act()
-                stage_gemm(2)
-            step2()
-            stream.synchronize()
-            run2 = capture(step2)
-            for _ in range(args.warmup):
-                run2()
-            stream.synchronize()
-            t2 = time.perf_counter()
-            for k in range(args.steps):
-                run2()
-            stream.synchronize()
-            torch.cuda.synchronize()
-            overlapped = (time.perf_counter() - t2) * 1e3 / args.steps
 
         # ---- per-kernel pass: each stage on its own, 16 kernels per graph, ten replays between two events.
         # The quantize/pack stage is one kernel reading 113 MB of weights that would stay in the 256 MB
@@ -208,7 +190,7 @@ def main():
             seg_ms.append(timed(fill_quant) - timed(fill_only))
         del flush
         for fn, nk in zip(stages[1:], (n_act, n_gemm)):
-            reps = 16 // nk
+            reps = max(1, 16 // nk)
 
             def many(fn=fn, reps=reps):
                 for _ in range(reps):
@@ -236,11 +218,11 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "configs[1]: BERT-base encoder layer, 4 linears (QKV 768->2304, out 768->768, "
                                "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
-                               "step = 16 quantize/pack + 4 act-quant + 16 int8 GEMM+epilogue",
+                               "step = 16 quantize/pack (16 distinct fp32 matrices) + 4 act-quant + 16 int8 GEMM+epilogue",
                    "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph,
-                   "gemm_streams": args.gemm_streams},
-        "roofline": {"kernel": "qgemm_i8_ws_kernel / qgemm_i8_dma_kernel (int8 MFMA GEMM + scale epilogue), "
-                               "16 launches per step",
+                   "gemm_launches_per_step": n_gemm},
+        "roofline": {"kernel": "qgemm_i8_ws_kernel (int8 MFMA GEMM + scale epilogue; one persistent launch per bit-width "
+                               "walks the tiles of that width's four linears), %d launches per step" % n_gemm,
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
                      "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
@@ -260,17 +242,16 @@ def main():
         },
     }
 
-    if overlapped is not None:
-        out["overlapped"] = {"gemm_streams": 2, "ms_per_step": round(overlapped, 4),
-                             "value": round(gemm_ops / (overlapped * 1e-3) / 1e12, 3),
-                             "note": "same step, the GEMMs of different linears on two streams inside the graph"}
     if not args.no_extras:
         out["shapes"] = per_shape(torch, qb, wl, dev)
         out["q8_output"] = q8_output_leg(torch, qb, wl, dev)
         out["dynamic_range"] = dynamic_range_leg(torch, qb, wl, dev)
         out["asymmetric_ranges"] = asymmetric_leg(torch, qb, wl, dev)
         out["backward"] = backward_leg(torch, qb, wl, dev)
+        out["stack_12_layers"] = stack_leg(torch, qb, wl, dev)
+        out["bert_large"] = bert_large_leg(torch, qb, wl, dev)
         out["embedding"] = embedding_leg(torch, qb, wl, dev)
+        out["copy_gbs_measured"] = copy_ceiling(torch, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
@@ -305,11 +286,10 @@ def measured_mfma_peak(torch, qb, dev):
     return best
 
 
-def time_launches(torch, fn, iters=100, warm=30):
-    """Seconds per call of fn: ten calls captured in a HIP graph (the Python binding costs more per call than a
+def time_launches(torch, fn, iters=100, warm=30, per=10):
+    """Seconds per call of fn: `per` calls captured in a HIP graph (the Python binding costs more per call than a
     small kernel runs), the graph replayed between two events on its stream."""
     s = torch.cuda.Stream()   # default priority
-    per = 10
     with torch.cuda.stream(s):
         for _ in range(warm):
             fn()
@@ -331,28 +311,42 @@ def time_launches(torch, fn, iters=100, warm=30):
 
 
 def per_shape(torch, qb, wl, dev):
-    """Each GEMM shape on its own (back-to-back launches between two events), against
-    min(int8 MFMA peak, HBM peak x intensity) for its algorithmic bytes; BERT-base at T = 4096
-    and, as the asymptotic case, BERT-large FFN-down at T = 32768."""
+    """Each GEMM shape on its own, against min(int8 MFMA peak, HBM peak x intensity) for its algorithmic bytes:
+    `us` / `tops` = back-to-back single launches (qb_qlinear_fwd) between two events; `us_batched4` / `tops_batched4`
+    = four independent problems of the shape (own weights, activations and outputs) in one qb_qlinear_fwd_batched
+    call, per problem.  BERT-base at T = 4096 and, as the asymptotic case, BERT-large FFN at T = 32768."""
     res = []
     cases = [(T_TOKENS, N, K, 4) for (_, N, K) in wl.BERT_BASE_LINEARS] + [(T_TOKENS, 768, 3072, b) for b in (2, 3, 8)]
     cases += [(32768, 1024, 4096, 2), (32768, 4096, 1024, 3)]
     cases += [(1024, 768, 768, 4), (128, 768, 3072, 4)]  # configs[0]; a 128-token inference batch (launch-bound)
     for (T, N, K, b) in cases:
-        W = wl.weight(N, K, seed=N + K).to(dev)
-        X = wl.activation(T, K, seed=T + K).to(dev)
-        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
-        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
-        Y = torch.empty((T, N), dtype=torch.float32, device=dev)
-        sec = time_launches(torch, lambda: qb.qb_qlinear_fwd(Xq, rs_x, CLIP, packed, h, rs_w, b, GROUPS, N, Y=Y))
+        nprob = 4 if T <= 4096 else 1
+        jobs = []
+        for c in range(nprob):
+            W = wl.weight(N, K, seed=N + K + c).to(dev)
+            X = wl.activation(T, K, seed=T + K + c).to(dev)
+            packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+            Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+            jobs.append(dict(Xq=Xq, rs_x=rs_x, clip=CLIP, packed=packed, h=h, rs_w=rs_w, bits=b, groups=GROUPS, N=N,
+                             Y=torch.empty((T, N), dtype=torch.float32, device=dev)))
+            del W, X
+        j0 = jobs[0]
+        sec = time_launches(torch, lambda: qb.qb_qlinear_fwd(j0["Xq"], j0["rs_x"], CLIP, j0["packed"], j0["h"], j0["rs_w"], b,
+                                                             GROUPS, N, Y=j0["Y"]))
         ops = 2.0 * T * N * K
         byts = T * K + N * K * b / 8.0 + 4.0 * T * N + 4 * T + 4 * N
         roof = min(PEAK_INT8_TOPS, PEAK_HBM_GBS * 1e9 * (ops / byts) / 1e12)
-        res.append({"T": T, "N": N, "K": K, "bits": b, "us": round(sec * 1e6, 2), "tops": round(ops / sec / 1e12, 1),
-                    "frac_int8_peak": round(ops / sec / 1e12 / PEAK_INT8_TOPS, 4),
-                    "roofline_tops": round(roof, 1), "frac_roofline": round(ops / sec / 1e12 / roof, 4),
-                    "gbs": round(byts / sec / 1e9, 1)})
-        del W, X, Y, Xq
+        row = {"T": T, "N": N, "K": K, "bits": b, "us": round(sec * 1e6, 2), "tops": round(ops / sec / 1e12, 1),
+               "frac_int8_peak": round(ops / sec / 1e12 / PEAK_INT8_TOPS, 4),
+               "roofline_tops": round(roof, 1), "frac_roofline": round(ops / sec / 1e12 / roof, 4),
+               "gbs": round(byts / sec / 1e9, 1)}
+        if nprob > 1:
+            secb = time_launches(torch, lambda: qb.qb_qlinear_fwd_batched(jobs)) / nprob
+            row.update({"us_batched4": round(secb * 1e6, 2), "tops_batched4": round(ops / secb / 1e12, 1),
+                        "frac_int8_peak_batched4": round(ops / secb / 1e12 / PEAK_INT8_TOPS, 4),
+                        "frac_roofline_batched4": round(ops / secb / 1e12 / roof, 4)})
+        res.append(row)
+        del jobs, j0
     return res
 
 
@@ -488,40 +482,156 @@ def embedding_leg(torch, qb, wl, dev):
                     "max over all rows, then codes); 1 read + 4 written per gathered element"}
 
 
+def stack_leg(torch, qb, wl, dev):
+    """configs[3]: one iteration of the 12-layer BERT-base linear stack at 32 x 384 = 12288 tokens, per-layer weight
+    bits drawn by seed: 48 quantize/pack (batched, 48 distinct master matrices), per layer 4 activation quantizers,
+    4 forward GEMMs (one batched call) and 4 STE backwards (dX and dW)."""
+    T = 12288
+    bits = wl.layer_bits(12, seed=wl.config_seed(3, 0))
+    lin = wl.BERT_BASE_LINEARS
+    Ws = [[wl.weight(N, K, seed=wl.config_seed(3, 10 * l + i)).to(dev) for i, (_, N, K) in enumerate(lin)] for l in range(12)]
+    Xs = [wl.activation(T, K, seed=wl.config_seed(3, 500 + i)).to(dev) for i, (_, N, K) in enumerate(lin)]
+    dYs = [wl.grad_output_bf16(T, N, seed=wl.config_seed(3, 600 + i)).to(dev) for i, (_, N, K) in enumerate(lin)]
+    qs = [[dict(packed=torch.empty(qb.qb_packed_nbytes(N, K, bits[l]), dtype=torch.uint8, device=dev),
+                h=torch.empty(GROUPS, dtype=torch.float32, device=dev), m=torch.empty(GROUPS, dtype=torch.float32, device=dev),
+                rs_w=torch.empty(N, dtype=torch.int32, device=dev)) for (_, N, K) in lin] for l in range(12)]
+    acts = [dict(Xq=torch.empty((T, K), dtype=torch.int8, device=dev), rs_x=torch.empty(T, dtype=torch.int32, device=dev))
+            for (_, N, K) in lin]
+    Ys = [torch.empty((T, N), dtype=torch.float32, device=dev) for (_, N, K) in lin]
+    dXs = [torch.empty((T, K), dtype=torch.bfloat16, device=dev) for (_, N, K) in lin]
+    dWs = [torch.empty((N, K), dtype=torch.float32, device=dev) for (_, N, K) in lin]
+    ws = torch.empty(max(qb.qb_bwd_workspace_nbytes(T, N, K) for (_, N, K) in lin), dtype=torch.uint8, device=dev)
+    qjobs = [dict(W=Ws[l][i], bits=bits[l], groups=GROUPS, **qs[l][i]) for l in range(12) for i in range(4)]
+
+    def quant():
+        qb.qb_quantize_groupwise_batched(qjobs)
+
+    def fwd():
+        for l in range(12):
+            for i in range(4):
+                qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
+            qb.qb_qlinear_fwd_batched([dict(Xq=acts[i]["Xq"], rs_x=acts[i]["rs_x"], clip=CLIP, packed=qs[l][i]["packed"],
+                                            h=qs[l][i]["h"], rs_w=qs[l][i]["rs_w"], bits=bits[l], groups=GROUPS, N=lin[i][1],
+                                            Y=Ys[i]) for i in range(4)])
+
+    def bwd():
+        for l in range(12):
+            for i in range(4):
+                qb.qb_qlinear_bwd_ste(dYs[i], acts[i]["Xq"], CLIP, qs[l][i]["packed"], qs[l][i]["h"], bits[l], GROUPS,
+                                      dX=dXs[i], dW=dWs[i], workspace=ws)
+
+    tq, tf, tb = (time_launches(torch, f, iters=5, warm=2, per=1) for f in (quant, fwd, bwd))
+    ops = 12 * sum(2.0 * T * N * K for (_, N, K) in lin)
+    qbytes = sum(N * K * (4.0 + bits[l] / 8.0) + GROUPS * 8 + N * 4 for l in range(12) for (_, N, K) in lin)
+    return {"workload": "configs[3]: 12 layers x 4 linears, T=12288, bits per layer " + str(list(bits)) +
+                        ", per iteration: 48 quantize/pack + 48 act-quant + 48 fwd GEMM + 48 STE bwd",
+            "ms_per_iteration": round((tq + tf + tb) * 1e3, 3), "quantize_pack_ms": round(tq * 1e3, 3),
+            "quantize_pack_gbs": round(qbytes / tq / 1e9, 1), "fwd_ms": round(tf * 1e3, 3),
+            "fwd_tops_incl_act_quant": round(ops / tf / 1e12, 1), "bwd_ms": round(tb * 1e3, 3),
+            "bwd_tflops": round(2.0 * ops / tb / 1e12, 1)}
+
+
+def bert_large_leg(torch, qb, wl, dev):
+    """configs[4], the linear layers: the four GEMMs of a BERT-large layer at 64 x 512 = 32768 tokens at 2 and 3 bits,
+    and quantize/pack of all 24 layers (96 matrices, 1.2 GB of distinct fp32 master weights: nothing fits a cache)."""
+    T = 32768
+    lin = wl.BERT_LARGE_LINEARS
+    rows = []
+    for b in (2, 3):
+        jobs = []
+        for i, (name, N, K) in enumerate(lin):
+            W = wl.weight(N, K, seed=wl.config_seed(4, 10 + i)).to(dev)
+            X = wl.activation(T, K, seed=wl.config_seed(4, 20 + i)).to(dev)
+            packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+            Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+            jobs.append(dict(Xq=Xq, rs_x=rs_x, clip=CLIP, packed=packed, h=h, rs_w=rs_w, bits=b, groups=GROUPS, N=N,
+                             Y=torch.empty((T, N), dtype=torch.float32, device=dev)))
+            del W, X
+        sec = time_launches(torch, lambda: qb.qb_qlinear_fwd_batched(jobs), iters=20, warm=5)
+        ops = sum(2.0 * T * N * K for (_, N, K) in lin)
+        rows.append({"bits": b, "us_per_layer": round(sec * 1e6, 1), "tops": round(ops / sec / 1e12, 1),
+                     "frac_int8_peak": round(ops / sec / 1e12 / PEAK_INT8_TOPS, 4)})
+        del jobs
+    masters = [wl.weight(N, K, seed=wl.config_seed(4, 30 + i)).to(dev) for i, (_, N, K) in enumerate(lin)]
+    res = {"gemm_per_layer": rows}
+    for b in (2, 3):
+        qjobs = []
+        for l in range(24):
+            for i, (_, N, K) in enumerate(lin):
+                qjobs.append(dict(W=masters[i].clone(), bits=b, groups=GROUPS,
+                                  packed=torch.empty(qb.qb_packed_nbytes(N, K, b), dtype=torch.uint8, device=dev),
+                                  h=torch.empty(GROUPS, dtype=torch.float32, device=dev),
+                                  m=torch.empty(GROUPS, dtype=torch.float32, device=dev),
+                                  rs_w=torch.empty(N, dtype=torch.int32, device=dev)))
+        sec = time_launches(torch, lambda: qb.qb_quantize_groupwise_batched(qjobs), iters=10, warm=2)
+        byts = 24 * sum(N * K * (4.0 + b / 8.0) + GROUPS * 8 + N * 4 for (_, N, K) in lin)
+        res["quantize_pack_24_layers_%dbit" % b] = {"ms": round(sec * 1e3, 3), "gbs": round(byts / sec / 1e9, 1),
+                                                     "frac_hbm_peak": round(byts / sec / 1e9 / PEAK_HBM_GBS, 4),
+                                                     "bytes": byts, "launches": (len(qjobs) + 15) // 16}
+        del qjobs
+    return res
+
+
+def copy_ceiling(torch, dev):
+    """GB/s (read + written) of a plain 1 GiB device-to-device copy on this machine: what HBM sustains for a kernel
+    that only moves bytes, to set beside the published 8 TB/s."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    sec = time_launches(torch, lambda: dst.copy_(src), iters=20, warm=5)
+    return round(2.0 * (1 << 30) / sec / 1e9, 1)
+
+
 def cpu_baseline(wl):
-    """The CPU oracle (OpenMP build of the same source, untuned) on a bounded sample of the step:
-    the whole step (all 4096 token rows, four linears, four bit-widths): about eight seconds on the box's sixteen
-    cores."""
+    """The CPU oracle (the same source, untuned) on a bounded sample of the step.  All threads (its OpenMP build): the
+    whole step, all 4096 token rows, four linears, four bit-widths, including the quantize steps.  One thread (the
+    serial build): the same step on the first 256 token rows."""
     import numpy as np
     import oracle
     Ts = T_TOKENS
     linears = wl.BERT_BASE_LINEARS
-    Ws = [wl.weight(N, K, seed=wl.config_seed(1, i)).numpy() for i, (_, N, K) in enumerate(linears)]
+    Ws = {(b, i): wl.weight(N, K, seed=wl.config_seed(1, 100 * b + i)).numpy()
+          for b in BITS_SWEEP for i, (_, N, K) in enumerate(linears)}
     Xs = [wl.activation(Ts, K, seed=wl.config_seed(1, 10 + i)).numpy() for i, (_, N, K) in enumerate(linears)]
+
+    def run(rows, omp):
+        t0 = time.perf_counter()
+        acts = [oracle.quantize_act(X[:rows], CLIP) for X in Xs]
+        ops = 0.0
+        for b in BITS_SWEEP:
+            for i, (_, N, K) in enumerate(linears):
+                codes, h, m, rs_w = oracle.quantize_groupwise(Ws[(b, i)], b, GROUPS)
+                oracle.qlinear_fwd(acts[i][0], CLIP, codes, h, b, openmp=omp)
+                ops += 2.0 * rows * N * K
+        return ops, time.perf_counter() - t0
     threads = oracle.num_threads(True)
-    t0 = time.perf_counter()
-    acts = [oracle.quantize_act(X, CLIP) for X in Xs]
-    ops = 0.0
-    for b in BITS_SWEEP:
-        for i, (_, N, K) in enumerate(linears):
-            codes, h, m, rs_w = oracle.quantize_groupwise(Ws[i], b, GROUPS)
-            oracle.qlinear_fwd(acts[i][0], CLIP, codes, h, b, openmp=True)
-            ops += 2.0 * Ts * N * K
-    sec = time.perf_counter() - t0
+    ops, sec = run(Ts, True)
+    ops1, sec1 = run(256, False)
     return {"value": round(ops / sec / 1e12, 5), "unit": "TOPS", "cores": threads, "kind": "oracle",
             "sample": "one whole step: 4096 token rows, 4 linears x 4 bit-widths, incl. the quantize steps; %.1f s" % sec,
+            "single_thread": {"value": round(ops1 / sec1 / 1e12, 6), "unit": "TOPS", "cores": 1,
+                              "sample": "the same step on the first 256 token rows (weights quantized in full); %.1f s" % sec1},
             "host_cpus": os.cpu_count(), "cpu_model": cpu_model()}
 
 
 def cpu_model():
+    """Model string of the host CPU with what /proc/cpuinfo tells about it (family / model / stepping, logical CPUs)."""
+    info = {}
+    n = 0
     try:
         with open("/proc/cpuinfo") as f:
             for line in f:
-                if line.startswith("model name"):
-                    return line.split(":", 1)[1].strip()
+                if ":" not in line:
+                    continue
+                k, v = [x.strip() for x in line.split(":", 1)]
+                if k == "processor":
+                    n += 1
+                elif k in ("model name", "vendor_id", "cpu family", "model", "stepping") and k not in info:
+                    info[k] = v
     except OSError:
-        pass
-    return "unknown"
+        return "unknown"
+    return "%s (%s, family %s model %s stepping %s, %d logical CPUs visible)" % (
+        info.get("model name", "unknown"), info.get("vendor_id", "?"), info.get("cpu family", "?"), info.get("model", "?"),
+        info.get("stepping", "?"), n)
 
 
 if __name__ == "__main__":
