@@ -222,6 +222,24 @@ qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
                              uint16_t *dX, float *dW, void *workspace, void *stream);
 
 /*
+ * qb_qlinear_bwd_ste for callers that cannot allocate device memory or carry a workspace around (code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc): the same kernels and
+ * results, with the staging area taken from a fixed array inside the library instead of a `workspace`
+ * argument.  The call allocates and frees nothing.  The array has QB_BWD_STATIC_BYTES bytes on every GPU the
+ * library runs on, for as long as the process lives; shapes that need more (qb_bwd_workspace_nbytes(T,N,K) >
+ * QB_BWD_STATIC_BYTES; the limit covers every linear of a BERT-base layer at up to 4096 tokens) are refused with
+ * QB_ERR_WORKSPACE before anything is enqueued.  All calls on one GPU share that GPU's array: calls that overlap
+ * in time on one GPU (different streams, different threads) race on it and must be serialised by the caller;
+ * successive calls on one stream are safe, whatever their shapes.  Other arguments and errors as
+ * qb_qlinear_bwd_ste.
+ */
+#define QB_BWD_STATIC_BYTES (36u << 20)
+qb_status qb_qlinear_bwd_ste_static(const uint16_t *dY, const int8_t *Xq, float clip,
+                                    const void *packed, const float *h, int bits, int groups,
+                                    int64_t T, int64_t N, int64_t K,
+                                    uint16_t *dX, float *dW, void *stream);
+
+/*
  * The same backward with the clamp's own derivative kept (App.: X' = Clamp(X, q0, q_{2^k-1}) precedes the
  * rounding; only the rounding is passed straight through): the gradient of a value that lay outside its
  * range is zero, that of a value inside (ends included) is unchanged.

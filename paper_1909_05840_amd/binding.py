@@ -19,7 +19,7 @@ QB_K_ALIGN = 64
 QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
-           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_unpack_codes",
+           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
            "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
@@ -80,6 +80,8 @@ def load_library():
     lib.qb_qlinear_fwd_q8.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, ci, cf, vp, vp, vp]
     lib.qb_qlinear_bwd_ste.restype = ci
     lib.qb_qlinear_bwd_ste.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_bwd_ste_static.restype = ci
+    lib.qb_qlinear_bwd_ste_static.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp]
     lib.qb_quantize_groupwise_asym.restype = ci
     lib.qb_quantize_groupwise_asym.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_asym.restype = ci
@@ -276,6 +278,19 @@ def qb_qlinear_bwd_ste(dY, Xq, clip, packed, h, bits, groups, want_dx=True, want
         workspace = torch.empty(max(qb_bwd_workspace_nbytes(T, N, K), 256), dtype=torch.uint8, device=dev)
     _check(lib.qb_qlinear_bwd_ste(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
                                   _p(dX), _p(dW), _p(workspace), _stream()))
+    return dX, dW
+
+
+def qb_qlinear_bwd_ste_static(dY, Xq, clip, packed, h, bits, groups, dX=None, dW=None):
+    """qb_qlinear_bwd_ste without a workspace (the library's fixed staging area); dX and dW are the caller's, or null
+    to skip one of them.  The call itself allocates nothing."""
+    lib = load_library()
+    _dev(dY, torch.bfloat16, "dY")
+    _dev(Xq, torch.int8, "Xq")
+    T, N = dY.shape
+    K = Xq.shape[1]
+    _check(lib.qb_qlinear_bwd_ste_static(_p(dY), _p(Xq), float(clip), _p(packed), _p(h), bits, groups, T, N, K,
+                                         _p(dX), _p(dW), _stream()))
     return dX, dW
 
 

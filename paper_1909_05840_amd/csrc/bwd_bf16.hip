@@ -13,6 +13,7 @@
 // dW splits the long contraction over T across workgroups; partial sums are written to the
 // workspace and added in a fixed order, so results do not change from run to run.
 #include "qb_common.hpp"
+#include <mutex>
 
 namespace qb {
 namespace {
@@ -606,6 +607,48 @@ extern "C" qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, fl
                                         uint16_t *dX, float *dW, void *workspace, void *stream)
 {
     return bwd_ste(dY, Xq, clip, packed, h, bits, groups, T, N, K, nullptr, nullptr, nullptr, dX, dW, workspace, stream);
+}
+
+// ---- the backward for callers that cannot allocate: its staging area is a fixed array of the library -------------
+// One array per GPU (every device the code object is loaded on holds its own copy until the process ends).  In host
+// code the array's name is not a device address; the address on the current device is asked for once per device
+// and kept.
+static __device__ __align__(256) unsigned char scratch[QB_BWD_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// the current device's copy of `scratch`, or null if the runtime does not give it
+void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" qb_status qb_qlinear_bwd_ste_static(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
+                                               const float *h, int bits, int groups, int64_t T, int64_t N, int64_t K,
+                                               uint16_t *dX, float *dW, void *stream)
+{
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K)) return QB_ERR_SHAPE;
+    if (make_plan(T, N, K).total > (size_t)QB_BWD_STATIC_BYTES) return QB_ERR_WORKSPACE;  // larger than the fixed staging area
+    void *ws = scratch_of_current_device();
+    if (!ws) return QB_ERR_HIP;
+    // every byte of the staging area that the GEMMs read is written by this call's own staging launch first
+    // (padding included), so the contents a previous call left behind never matter
+    return bwd_ste(dY, Xq, clip, packed, h, bits, groups, T, N, K, nullptr, nullptr, nullptr, dX, dW, ws, stream);
 }
 
 extern "C" qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float clip, const void *packed,
