@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the backward and embedding timings")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (reference dispatch for HBM byte counters)")
+    ap.add_argument("--gemm-only", type=str, default=None, metavar="T,N,K,BITS",
+                    help="run only this GEMM shape (30 single launches of qb_qlinear_fwd, then 10 batched calls of four "
+                         "independent problems) and print its timing: the command profiled for per-shape counters")
     ap.add_argument("--backward-only", action="store_true",
                     help="run only the STE-backward leg (configs[2]) and print its result: the command profiled for "
                          "the backward kernels")
@@ -75,6 +78,9 @@ def main():
     T = T_TOKENS
     if args.backward_only:
         print(json.dumps({"backward": backward_leg(torch, qb, wl, dev)}))
+        return
+    if args.gemm_only:
+        print(json.dumps({"gemm": gemm_only_leg(torch, qb, wl, dev, [int(v) for v in args.gemm_only.split(",")])}))
         return
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
@@ -348,6 +354,33 @@ def per_shape(torch, qb, wl, dev):
         res.append(row)
         del jobs, j0
     return res
+
+
+def gemm_only_leg(torch, qb, wl, dev, shape):
+    """One GEMM shape, eagerly launched (every launch is its own dispatch for the profiler): 30 single launches, then 10
+    batched calls of four independent problems."""
+    T, N, K, b = shape
+    jobs = []
+    for c in range(4):
+        W = wl.weight(N, K, seed=N + K + c).to(dev)
+        X = wl.activation(T, K, seed=T + K + c).to(dev)
+        packed, h, m, rs_w = qb.qb_quantize_groupwise(W, b, GROUPS)
+        Xq, rs_x = qb.qb_quantize_act(X, CLIP)
+        jobs.append(dict(Xq=Xq, rs_x=rs_x, clip=CLIP, packed=packed, h=h, rs_w=rs_w, bits=b, groups=GROUPS, N=N,
+                         Y=torch.empty((T, N), dtype=torch.float32, device=dev)))
+    j0 = jobs[0]
+    torch.cuda.synchronize()
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    e[0].record()
+    for _ in range(30):
+        qb.qb_qlinear_fwd(j0["Xq"], j0["rs_x"], CLIP, j0["packed"], j0["h"], j0["rs_w"], b, GROUPS, N, Y=j0["Y"])
+    e[1].record()
+    for _ in range(10):
+        qb.qb_qlinear_fwd_batched(jobs)
+    e[2].record()
+    torch.cuda.synchronize()
+    return {"T": T, "N": N, "K": K, "bits": b, "single_us_eager": round(e[0].elapsed_time(e[1]) * 1e3 / 30, 2),
+            "batched4_us_per_problem_eager": round(e[1].elapsed_time(e[2]) * 1e3 / 40, 2)}
 
 
 def q8_output_leg(torch, qb, wl, dev):
