@@ -7,12 +7,12 @@ matrix, weight bit-widths {2,3,4,8}, forward only, synthetic seeded data.
 
 One step = one pass of the forward hot path over that batch for every bit-width of the sweep:
   16 x quantize/pack of fp32 master weights (16 distinct matrices, one batched launch), 4 x 8-bit activation
-  quantize, 16 x int8 MFMA GEMM with the scale epilogue (one batched call: the 16 independent linears share
-  one persistent launch per bit-width, 4 launches).
+  quantize (one batched launch), 16 x int8 MFMA GEMM with the scale epilogue (one batched call: per bit-width
+  QKV, attention-out and FFN-down share one persistent launch, FFN-up with its many tiles goes alone: 8 launches).
 All inputs are resident in HBM before the timed region.  `value` = int8 GEMM operations of the
 step (2*T*N*K summed) divided by the wall time of the whole step, in TOPS.
 
-The timed region replays ONE captured HIP graph per step (it holds the 9 kernels of the step and
+The timed region replays ONE captured HIP graph per step (it holds the 10 kernels of the step and
 nothing else); --no-graph launches every kernel eagerly instead.  Before the warm-up steps the step is
 replayed for at least 60 ms so that the clocks have settled whatever --warmup says.  The per-kernel
 averages in `roofline` and `kernels` come from a second pass in the same run, on the same stream: the GEMM
@@ -111,9 +111,14 @@ def main():
     def stage_quantize():
         qb.qb_quantize_groupwise_batched(quant_jobs)   # all 16 matrices of the step, one launch
 
+    act_jobs = [dict(X=Xs[i], clip=CLIP, Xq=acts[i]["Xq"], rs_x=acts[i]["rs_x"]) for i in range(len(linears))]
+
     def stage_act():
-        for i in range(len(linears)):
-            qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
+        if args.single_launches:
+            for i in range(len(linears)):
+                qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
+        else:
+            qb.qb_quantize_act_batched(act_jobs)   # the layer's four input tensors, one launch
 
     def stage_gemm():
         if args.single_launches:   # one launch per linear, as separate qb_qlinear_fwd calls
@@ -130,8 +135,9 @@ def main():
         torch.cuda.synchronize()
 
     stages = [stage_quantize, stage_act, stage_gemm]
-    n_quant, n_act = 1, 4                  # kernels per stage
-    n_gemm = 16 if args.single_launches else len(BITS_SWEEP)
+    n_quant = 1                            # kernels per stage
+    n_act = 4 if args.single_launches else 1
+    n_gemm = 16 if args.single_launches else len(BITS_SWEEP) + 4   # (FFN-up goes one launch per bit-width: many tiles)
     stream = torch.cuda.Stream(device=dev)   # default priority
     use_graph = not args.no_graph
 
@@ -196,7 +202,7 @@ def main():
             seg_ms.append(timed(fill_quant) - timed(fill_only))
         del flush
         for fn, nk in zip(stages[1:], (n_act, n_gemm)):
-            reps = max(1, 16 // nk)
+            reps = max(1, 16 // nk) if nk <= 4 else 1
 
             def many(fn=fn, reps=reps):
                 for _ in range(reps):
@@ -224,11 +230,12 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "configs[1]: BERT-base encoder layer, 4 linears (QKV 768->2304, out 768->768, "
                                "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
-                               "step = 16 quantize/pack (16 distinct fp32 matrices) + 4 act-quant + 16 int8 GEMM+epilogue",
+                               "step = 16 quantize/pack (16 distinct fp32 matrices, 1 launch) + 4 act-quant (1 launch) + 16 int8 GEMM+epilogue",
                    "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph,
                    "gemm_launches_per_step": n_gemm},
-        "roofline": {"kernel": "qgemm_i8_ws_kernel (int8 MFMA GEMM + scale epilogue; one persistent launch per bit-width "
-                               "walks the tiles of that width's four linears), %d launches per step" % n_gemm,
+        "roofline": {"kernel": "qgemm_i8_ws_kernel / qgemm_i8_dma_kernel (int8 MFMA GEMM + scale epilogue; per bit-width one "
+                               "persistent launch walks the tiles of QKV, attention-out and FFN-down, FFN-up goes alone), "
+                               "%d launches per step" % n_gemm,
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
                      "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
@@ -541,8 +548,7 @@ def stack_leg(torch, qb, wl, dev):
 
     def fwd():
         for l in range(12):
-            for i in range(4):
-                qb.qb_quantize_act(Xs[i], CLIP, acts[i]["Xq"], acts[i]["rs_x"])
+            qb.qb_quantize_act_batched([dict(X=Xs[i], clip=CLIP, Xq=acts[i]["Xq"], rs_x=acts[i]["rs_x"]) for i in range(4)])
             qb.qb_qlinear_fwd_batched([dict(Xq=acts[i]["Xq"], rs_x=acts[i]["rs_x"], clip=CLIP, packed=qs[l][i]["packed"],
                                             h=qs[l][i]["h"], rs_w=qs[l][i]["rs_w"], bits=bits[l], groups=GROUPS, N=lin[i][1],
                                             Y=Ys[i]) for i in range(4)])

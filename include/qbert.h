@@ -117,6 +117,22 @@ qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float clip,
                           int8_t *Xq, int32_t *rs_x, void *stream);
 
 /*
+ * qb_quantize_act for several tensors in one launch (the inputs of a layer's linears; Table 1 caption: every
+ * matrix product takes 8-bit activations).  `jobs` is a HOST array of n_jobs descriptors whose pointer fields are
+ * DEVICE pointers with the meaning of the arguments of qb_quantize_act; it is read during the call only.  Jobs
+ * must not overlap in their outputs.  All jobs are validated before anything is launched; the sum of the T must
+ * not exceed 2^30.
+ */
+typedef struct {
+    const float *X;
+    int64_t T, K;
+    float clip;
+    int8_t *Xq;
+    int32_t *rs_x;
+} qb_act_job;
+qb_status qb_quantize_act_batched(const qb_act_job *jobs, int n_jobs, void *stream);
+
+/*
  * Forward of the quantized linear layer (App., last paragraph: integer matrix product on the
  * codes followed by one de-quantization).  With x' = Xq and c' = u - 2^(k-1),
  *   acc[t,n] = sum_j x'[t,j] * c'[n,j]                       (int8 x int8 -> int32)

@@ -5,7 +5,7 @@ The work is done by hand-written HIP kernels behind the C ABI in include/qbert.h
 workloads.  Nothing is imported from, or falls back to, any CPU implementation.
 """
 from .binding import (QBError, load_library, qb_status_string, qb_packed_nbytes, qb_bwd_workspace_nbytes,
-                      qb_quantize_groupwise, qb_quantize_groupwise_batched, qb_quantize_act, qb_qlinear_fwd, qb_qlinear_fwd_batched, qb_qlinear_fwd_q8, qb_qlinear_bwd_ste, qb_qlinear_bwd_ste_static,
+                      qb_quantize_groupwise, qb_quantize_groupwise_batched, qb_quantize_act, qb_quantize_act_batched, qb_qlinear_fwd, qb_qlinear_fwd_batched, qb_qlinear_fwd_q8, qb_qlinear_bwd_ste, qb_qlinear_bwd_ste_static,
                       qb_unpack_codes, qb_embedding_quantize, qb_embedding_gather, qb_embedding_quantize_bits,
                       qb_embedding_gather_bits, qb_quantize_act_dyn, qb_qlinear_fwd_dyn, qb_quantize_groupwise_clip, qb_quantize_act_dyn_tensor, qb_qlinear_bwd_ste_masked,
                       qb_quantize_groupwise_asym, qb_qlinear_fwd_asym, qb_qlinear_bwd_ste_asym,
@@ -14,7 +14,7 @@ from .binding import (QBError, load_library, qb_status_string, qb_packed_nbytes,
 from . import workloads
 
 __all__ = ["QBError", "load_library", "qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes",
-           "qb_quantize_groupwise", "qb_quantize_groupwise_batched", "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static",
+           "qb_quantize_groupwise", "qb_quantize_groupwise_batched", "qb_quantize_act", "qb_quantize_act_batched", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static",
            "qb_unpack_codes", "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits",
            "qb_embedding_gather_bits", "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked", "qb_quantize_groupwise_asym",
            "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym", "qb_power_iteration", "qb_sensitivity_omega",

@@ -19,7 +19,7 @@ QB_K_ALIGN = 64
 QB_N_BLOCK = 32
 EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
-           "qb_quantize_act", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
+           "qb_quantize_act", "qb_quantize_act_batched", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
            "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
@@ -35,6 +35,11 @@ class _QuantJob(ctypes.Structure):
     _fields_ = [("W", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("bits", ctypes.c_int),
                 ("groups", ctypes.c_int), ("packed", ctypes.c_void_p), ("h", ctypes.c_void_p), ("m", ctypes.c_void_p),
                 ("rs_w", ctypes.c_void_p)]
+
+
+class _ActJob(ctypes.Structure):
+    _fields_ = [("X", ctypes.c_void_p), ("T", ctypes.c_int64), ("K", ctypes.c_int64), ("clip", ctypes.c_float),
+                ("Xq", ctypes.c_void_p), ("rs_x", ctypes.c_void_p)]
 
 
 class _FwdJob(ctypes.Structure):
@@ -72,6 +77,8 @@ def load_library():
     lib.qb_quantize_groupwise_batched.argtypes = [ctypes.POINTER(_QuantJob), ci, vp]
     lib.qb_quantize_act.restype = ci
     lib.qb_quantize_act.argtypes = [vp, i64, i64, cf, vp, vp, vp]
+    lib.qb_quantize_act_batched.restype = ci
+    lib.qb_quantize_act_batched.argtypes = [ctypes.POINTER(_ActJob), ci, vp]
     lib.qb_qlinear_fwd.restype = ci
     lib.qb_qlinear_fwd.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_batched.restype = ci
@@ -205,6 +212,24 @@ def qb_quantize_act(X, clip, Xq=None, rs_x=None):
         rs_x = torch.empty(T, dtype=torch.int32, device=X.device)
     _check(lib.qb_quantize_act(_p(X), T, K, float(clip), _p(Xq), _p(rs_x), _stream()))
     return Xq, rs_x
+
+
+def qb_quantize_act_batched(jobs):
+    """jobs: list of dicts with X, clip and optionally Xq, rs_x (allocated here if absent): several tensors, one launch.
+    Returns the list of (Xq, rs_x) tuples."""
+    lib = load_library()
+    arr = (_ActJob * max(len(jobs), 1))()
+    outs = []
+    for i, j in enumerate(jobs):
+        X = _dev(j["X"], torch.float32, "X")
+        T, K = X.shape
+        Xq = j.get("Xq") if j.get("Xq") is not None else torch.empty((T, K), dtype=torch.int8, device=X.device)
+        rs = j.get("rs_x") if j.get("rs_x") is not None else torch.empty(T, dtype=torch.int32, device=X.device)
+        arr[i] = _ActJob(X.data_ptr(), T, K, float(j["clip"]), _dev(Xq, torch.int8, "Xq").data_ptr(),
+                         _dev(rs, torch.int32, "rs_x").data_ptr())
+        outs.append((Xq, rs))
+    _check(lib.qb_quantize_act_batched(arr, len(jobs), _stream()))
+    return outs
 
 
 def qb_qlinear_fwd(Xq, rs_x, clip, packed, h, rs_w, bits, groups, N, bias=None, Y=None, A4_debug=None,

@@ -1342,8 +1342,8 @@ void launch_job(const qb_fwd_job &j, hipStream_t st)
                       (int)j.K, (int)(j.N / j.groups), j.clip / 255.0f, st);
 }
 
-// the jobs of one bit-width: those of a size where a launch's fixed cost matters share launches of the
-// role-split kernel (128x96 tiles where 96 divides N, else 128x128), the others go one by one
+// the jobs of one bit-width: those that the single call would give to a role-split kernel share launches of it
+// (one list per tile shape), the others go one by one
 template <int BITS>
 void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
 {
@@ -1353,15 +1353,21 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
     for (int i = 0; i < n_jobs; ++i) {
         const qb_fwd_job &j = jobs[i];
         if (j.bits != BITS) continue;
+        // the tile choice of the single call (launch_bits): problems it gives to a role-split kernel share launches,
+        // the others (few tiles, K not a multiple of 128, many tiles: two plain workgroups per CU) go one by one
         const long tiles128 = (long)((j.T + 127) / 128) * ((j.N + 127) / 128);
-        if (j.K % 128 != 0 || tiles128 <= 160 || tiles128 > 1024) {
+        const long tiles96 = (long)((j.T + 127) / 128) * ((j.N + 95) / 96);
+        const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
+        const bool use96 = 86 * rounds96 < 100 * rounds128;
+        const bool use128 = !use96 && (tiles128 <= 640 || (j.K >= 2048 && tiles128 <= 1024));
+        if (j.K % 128 != 0 || tiles128 <= 160 || !(use96 || use128)) {
             launch_job<BITS>(j, st);
             continue;
         }
         const uint8_t *p = static_cast<const uint8_t *>(j.packed);
         const int rpg = (int)(j.N / j.groups);
         const float hx = j.clip / 255.0f;
-        if (j.N % 96 == 0) {
+        if (use96) {
             if (g96.n == kMaxGroup) {
                 launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
                 g96.n = 0;

@@ -367,6 +367,96 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restri
     }
 }
 
+// Several activation tensors in one launch (the inputs of a layer's linears): the rows of all tensors form one
+// sequence that the wavefronts walk through as quantize_act_kernel walks through the rows of one tensor, the next
+// chunk (possibly of another tensor) in flight while the current one is quantized.
+struct ActBatch {
+    int n;
+    int row_start[QB_MAX_BATCH + 1];  // first row of tensor i in the sequence; [n] = number of rows
+    const float *X[QB_MAX_BATCH];
+    int8_t *Xq[QB_MAX_BATCH];
+    int32_t *rs_x[QB_MAX_BATCH];
+    int K[QB_MAX_BATCH];
+    float clip[QB_MAX_BATCH];
+};
+
+__global__ __launch_bounds__(256) void quantize_act_batched_kernel(const ActBatch b)
+{
+    const int lane = threadIdx.x & 63;
+    const int nwaves = gridDim.x * 4;
+    const int total = b.row_start[b.n];
+    int vrow = blockIdx.x * 4 + (threadIdx.x >> 6);  // position in the sequence of rows (uniform over the wavefront)
+    if (vrow >= total) return;
+    auto job_of = [&](int r) {
+        int j = 0;
+        while (j + 1 < b.n && r >= b.row_start[j + 1]) ++j;
+        return j;
+    };
+    int j = job_of(vrow);
+    int K = b.K[j], k4 = K >> 2, chunks = (k4 + 255) >> 8;
+    float clip = b.clip[j];
+    Quantizer qz;
+    qz.set(clip, 255.0f);
+
+    float4 cur[4], nxt[4];
+    auto load = [&](float4 (&v)[4], int jj, int r, int c) {
+        const int kk4 = b.K[jj] >> 2;
+        const float4 *src = reinterpret_cast<const float4 *>(b.X[jj] + (size_t)(r - b.row_start[jj]) * b.K[jj]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = (c << 8) + u * 64 + lane;
+            if (idx < kk4) v[u] = src[idx];
+        }
+    };
+    load(cur, j, vrow, 0);
+    uint32_t sum = 0;
+    int c = 0;
+    while (true) {
+        int nrow = vrow, nc = c + 1, nj = j;
+        if (nc == chunks) {
+            nc = 0;
+            nrow = vrow + nwaves;
+            if (nrow < total) nj = job_of(nrow);
+        }
+        const bool more = nrow < total;
+        if (more) load(nxt, nj, nrow, nc);
+        const int row = vrow - b.row_start[j];
+        uint32_t *dst = reinterpret_cast<uint32_t *>(b.Xq[j] + (size_t)row * K);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = (c << 8) + u * 64 + lane;
+            if (idx < k4) {
+                float4 v = cur[u];
+                v.x = __builtin_amdgcn_fmed3f(v.x, -clip, clip);
+                v.y = __builtin_amdgcn_fmed3f(v.y, -clip, clip);
+                v.z = __builtin_amdgcn_fmed3f(v.z, -clip, clip);
+                v.w = __builtin_amdgcn_fmed3f(v.w, -clip, clip);
+                const uint32_t q = qz.code4(v);
+                sum = __builtin_amdgcn_sad_u8(q, 0u, sum);
+                dst[idx] = q ^ 0x80808080u;  // u - 128 as int8
+            }
+        }
+        if (nc == 0) {  // row finished
+            const int tot = wave_sum((int)sum);
+            if (lane == 0) b.rs_x[j][row] = tot - 128 * K;
+            sum = 0;
+        }
+        if (!more) break;
+        if (nj != j) {  // the next row belongs to another tensor
+            j = nj;
+            K = b.K[j];
+            k4 = K >> 2;
+            chunks = (k4 + 255) >> 8;
+            clip = b.clip[j];
+            qz.set(clip, 255.0f);
+        }
+        vrow = nrow;
+        c = nc;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+    }
+}
+
 // ---- activations with one range for the whole tensor, c = max |X|: pass 1 reduces into a device float
 // (zero-filled before; non-negative floats order like their bit patterns, so an integer atomic max serves),
 // pass 2 is quantize_act_kernel reading its clip from that float.
@@ -825,6 +915,37 @@ extern "C" qb_status qb_quantize_act(const float *X, int64_t T, int64_t K, float
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(quantize_act_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), X, (int)T,
                        (int)K, clip, static_cast<const float *>(nullptr), Xq, rs_x, static_cast<float *>(nullptr));
+    return launch_status();
+}
+
+extern "C" qb_status qb_quantize_act_batched(const qb_act_job *jobs, int n_jobs, void *stream)
+{
+    if (n_jobs < 0) return QB_ERR_SHAPE;
+    if (n_jobs == 0) return QB_OK;
+    if (!jobs) return QB_ERR_NULL;
+    int64_t rows = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const qb_act_job &j = jobs[i];
+        if (!j.X || !j.Xq || !j.rs_x) return QB_ERR_NULL;
+        if (j.T <= 0 || j.T > (1 << 30) || !k_ok(j.K)) return QB_ERR_SHAPE;
+        if (!(j.clip > 0.0f) || !(j.clip < 3.0e38f)) return QB_ERR_CLIP;
+        rows += j.T;
+    }
+    if (rows > (1 << 30)) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int i0 = 0; i0 < n_jobs; i0 += QB_MAX_BATCH) {
+        ActBatch b;
+        b.n = n_jobs - i0 < QB_MAX_BATCH ? n_jobs - i0 : QB_MAX_BATCH;
+        b.row_start[0] = 0;
+        for (int k = 0; k < b.n; ++k) {
+            const qb_act_job &j = jobs[i0 + k];
+            b.X[k] = j.X; b.Xq[k] = j.Xq; b.rs_x[k] = j.rs_x; b.K[k] = (int)j.K; b.clip[k] = j.clip;
+            b.row_start[k + 1] = b.row_start[k] + (int)j.T;
+        }
+        unsigned blocks = (unsigned)((b.row_start[b.n] + 3) / 4);
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(quantize_act_batched_kernel, dim3(blocks), dim3(256), 0, st, b);
+    }
     return launch_status();
 }
 

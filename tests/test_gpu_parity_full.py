@@ -236,3 +236,55 @@ def test_backward_config3_whole_matrices(qb, lin):
     sabs_w = dYa.T @ np.abs(oracle.dequantize_act(d["oq"], CLIP).astype(np.float64))
     bad = np.abs(gdw - odW) > 2.0 ** -12 * sabs_w
     assert not bad.any(), "dW: %d elements outside the bound" % bad.sum()
+
+
+# ---- batched activation quantizer ---------------------------------------------------------------------------------
+def test_quantize_act_batched(qb):
+    """The four inputs of a BERT-base layer at 4096 tokens plus ragged and tiny tensors (and two clips) in one call:
+    codes and row sums bit for bit the oracle's, every output element written."""
+    shapes = [(4096, 768, 6.0), (4096, 768, 6.0), (4096, 768, 3.0), (4096, 3072, 6.0), (1, 64, 6.0), (1023, 768, 2.5),
+              (7, 1024, 6.0), (130, 4096, 1.0)]
+    jobs, Xs = [], []
+    for i, (T, K, clip) in enumerate(shapes):
+        X = wl.activation(T, K, seed=900 + i)
+        X[0, 0], X[-1, -1] = float("inf"), -float("inf")
+        Xs.append(X)
+        jobs.append(dict(X=X.to(DEV), clip=clip, Xq=torch.full((T, K), 77, dtype=torch.int8, device=DEV),
+                         rs_x=torch.full((T,), -1, dtype=torch.int32, device=DEV)))
+    say("act batched", len(jobs), "tensors")
+    outs = qb.qb_quantize_act_batched(jobs)
+    torch.cuda.synchronize()
+    for (Xq, rs), X, (T, K, clip) in zip(outs, Xs, shapes):
+        oq, orx = oracle.quantize_act(X.numpy(), clip)
+        assert (Xq.cpu().numpy() == oq).all()
+        assert (rs.cpu().numpy() == orx).all()
+    assert qb.qb_quantize_act_batched([]) == []
+    with pytest.raises(qb.QBError) as e:
+        qb.qb_quantize_act_batched([jobs[0], dict(jobs[1], clip=-1.0)])
+    assert e.value.status == 4
+
+
+# ---- few tokens: the inference regime (batch x sequence of 1 ... 128 tokens) ---------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("T", (1, 8, 64, 128))
+def test_forward_few_tokens_bert_shapes(qb, bits, T):
+    """BERT-base linears with 1 ... 128 tokens, alone and as one batched call of the layer's four linears: A4 bit for
+    bit, Y within 1e-6, over the whole output."""
+    jobs, refs = [], []
+    for (name, N, K) in wl.BERT_BASE_LINEARS:
+        say("fwd few tokens", (T, N, K), "bits", bits)
+        d = quantized_inputs(qb, N, K, T, bits, seed=7 * N + K + T + bits)
+        Y, A4 = qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, G, N, want_a4=True)
+        Yp = qb.qb_qlinear_fwd(d["Xq"], d["rs_x"], CLIP, d["packed"], d["h"], d["rs_w"], bits, G, N)
+        torch.cuda.synchronize()
+        Yo, A4o, _ = oracle.qlinear_fwd(d["oq"], CLIP, d["oc"], d["oh"], bits)
+        assert (A4.cpu().numpy() == A4o).all()
+        assert_rel(Y.cpu().numpy(), Yo)
+        assert torch.equal(Y, Yp)
+        jobs.append(dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=bits,
+                         groups=G, N=N))
+        refs.append(Y)
+    Ys = qb.qb_qlinear_fwd_batched(jobs)
+    torch.cuda.synchronize()
+    for Yb, Y in zip(Ys, refs):
+        assert torch.equal(Yb, Y)
