@@ -11,8 +11,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue
  *     kernels on it: they never synchronise, never use another stream, and may be captured
  *     into a HIP graph.
- *   - Arguments are validated on the host before anything is launched.  On any status other
- *     than QB_OK nothing has been enqueued and no output has been written.
+ *   - Arguments are validated on the host before anything is launched: on QB_ERR_NULL, _BITS, _SHAPE,
+ *     _CLIP and _WORKSPACE nothing has been enqueued and no output has been written.  QB_ERR_HIP is the
+ *     one status that can come after work was enqueued: it reports that the runtime refused a launch of
+ *     the call (earlier launches of the same call may already be in the stream; the outputs are then
+ *     undefined), or, for qb_power_iteration, that the caller's callback failed (see there).
  *   - Inputs must be finite (activations may be +-inf, which the clamp removes; NaN is not
  *     allowed).  Faults on the device are not detected.
  *   - Matrices are dense row-major.  K must be a multiple of QB_K_ALIGN.
@@ -55,6 +58,21 @@ size_t qb_packed_nbytes(int64_t N, int64_t K, int bits);
  * the given shape (of the other calls only qb_power_iteration takes scratch, sized by
  * qb_power_iteration_scratch_floats).  Returns 0 for invalid arguments. */
 size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K);
+
+/* Host, pure.  The same question for any entry point: bytes of caller-provided scratch that operation `op`
+ * needs for the given shape and bit-width (arguments an operation does not depend on are ignored).  Only the
+ * backward calls (qb_qlinear_bwd_ste and its _masked / _asym variants: qb_bwd_workspace_nbytes) and
+ * qb_power_iteration (qb_power_iteration_scratch_floats() floats) take scratch; every other operation
+ * returns 0, as do invalid arguments. */
+enum {
+    QB_OP_QUANTIZE_GROUPWISE = 0,
+    QB_OP_QUANTIZE_ACT = 1,
+    QB_OP_QLINEAR_FWD = 2,
+    QB_OP_QLINEAR_BWD_STE = 3,
+    QB_OP_EMBEDDING = 4,
+    QB_OP_POWER_ITERATION = 5
+};
+size_t qb_workspace_nbytes(int op, int64_t T, int64_t N, int64_t K, int bits);
 
 /*
  * Group-wise symmetric uniform weight quantization and packing.
@@ -315,6 +333,9 @@ qb_status qb_qlinear_bwd_ste_asym(const uint16_t *dY, const int8_t *Xq, float cl
  *   estimates  out [iters] fp32 device: v.Hv of every step, the last one being the top eigenvalue's estimate
  * Nothing is copied to the host and nothing waits: 3 + 3*iters small launches around the caller's own.  The
  * reductions run in a fixed order (the result does not depend on scheduling).
+ * If the callback returns non-zero in step i, the call returns QB_ERR_HIP at once: the normalisation of v and the
+ * steps 0 .. i-1 are already in the stream (they stay valid work: v holds the normalised vector of step i,
+ * estimates[0 .. i-1] are defined, estimates[i ..] are not written), and nothing further is enqueued.
  *
  * qb_sensitivity_omega -- Eq. 2, host only: omega[i] = |mean_r lambdas[i][r]| + std_r lambdas[i][r] (population
  * standard deviation over the `runs` estimates of layer i; arithmetic in binary64).

@@ -326,6 +326,24 @@ def quantize_groupwise_asym(W, bits, groups):
     return codes, delta, q0, rs
 
 
+def quantize_groupwise_asym_range(W, bits, lo, hi):
+    """Caller-given group ranges [lo[g], hi[g]] (App.: a sub-interval of the data's range; weights outside are clamped).
+    Returns (codes[N,K] u8, delta[G] f32, q0[G] f32, rs_w[N] i32)."""
+    W = _c(W, np.float32)
+    lo = _c(lo, np.float32)
+    hi = _c(hi, np.float32)
+    N, K = W.shape
+    G = lo.shape[0]
+    codes = np.empty((N, K), np.uint8)
+    delta = np.empty(G, np.float32)
+    q0 = np.empty(G, np.float32)
+    rs_w = np.empty(N, np.int32)
+    _check(_lib().qbo_quantize_groupwise_asym_range(_ptr(W), _I64(N), _I64(K), int(bits), _I64(G), _ptr(lo), _ptr(hi),
+                                                    _ptr(codes), _ptr(delta), _ptr(q0), _ptr(rs_w)),
+           "quantize_groupwise_asym_range")
+    return codes, delta, q0, rs_w
+
+
 def dequantize_groupwise_asym(codes, delta, q0):
     codes = _c(codes, np.uint8)
     delta = _c(delta, np.float32)

@@ -702,6 +702,56 @@ int qbo_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, 
     return QBO_OK;
 }
 
+/* The same quantizer with the range of every group given by the caller (App.: the range [q0, q_{2^k-1}] may be a
+ * sub-interval of the data's [min, max]; X' = Clamp(X, q0, q_{2^k-1})): group g uses [lo[g], hi[g]], lo <= hi.
+ * Weights outside are clamped first and so get the end codes.  Delta = fl(fl(hi - lo)/L), q0 = lo.
+ * With lo = min and hi = max of the group this is qbo_quantize_groupwise_asym. */
+int qbo_quantize_groupwise_asym_range(const float *W, int64_t N, int64_t K, int bits, int64_t G, const float *lo_in,
+                                      const float *hi_in, uint8_t *codes, float *delta, float *q0, int32_t *rs_w)
+{
+    int64_t g, rows;
+    int L, half;
+    if (!W || !lo_in || !hi_in || !codes || !delta || !q0 || !rs_w || !bits_ok(bits)) return QBO_ERR_ARG;
+    if (N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    L = (1 << bits) - 1;
+    half = 1 << (bits - 1);
+    rows = N / G;
+    for (g = 0; g < G; ++g) {
+        const float *Wg = W + g * rows * K;
+        uint8_t *cg = codes + g * rows * K;
+        const float lo = lo_in[g], hi = hi_in[g];
+        float d;
+        int64_t r, j;
+        if (!isfinite(lo) || !isfinite(hi) || lo > hi) return QBO_ERR_ARG;
+        d = hi - lo;
+        d = d / (float)L;
+        delta[g] = d;
+        q0[g] = lo;
+        for (r = 0; r < rows; ++r) {
+            int32_t acc = 0;
+            for (j = 0; j < K; ++j) {
+                int u = 0;
+                float w = Wg[r * K + j];
+                if (!isfinite(w)) return QBO_ERR_NONFINITE;
+                if (d != 0.0f) {
+                    float sft, t;
+                    if (w < lo) w = lo;               /* X' = Clamp(X, q0, q_{2^k-1}) */
+                    if (w > hi) w = hi;
+                    sft = w - lo;                     /* X' - q0 */
+                    t = sft / d;
+                    u = (int)rintf(t);
+                    if (u < 0) u = 0;
+                    if (u > L) u = L;
+                }
+                cg[r * K + j] = (uint8_t)u;
+                acc += u - half;
+            }
+            rs_w[g * rows + r] = acc;
+        }
+    }
+    return QBO_OK;
+}
+
 /* Q(w) = Delta*u + q0 in binary64 from the binary32 Delta and q0. */
 int qbo_dequantize_groupwise_asym(const uint8_t *codes, const float *delta, const float *q0, int64_t N, int64_t K,
                                   int64_t G, double *Wq)

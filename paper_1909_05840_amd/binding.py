@@ -17,7 +17,7 @@ _lib = None
 
 QB_K_ALIGN = 64
 QB_N_BLOCK = 32
-EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_quantize_groupwise",
+EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "qb_workspace_nbytes", "qb_quantize_groupwise",
            "qb_quantize_groupwise_batched",
            "qb_quantize_act", "qb_quantize_act_batched", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
@@ -69,6 +69,8 @@ def load_library():
     lib.qb_status_string.argtypes = [ci]
     lib.qb_packed_nbytes.restype = ctypes.c_size_t
     lib.qb_packed_nbytes.argtypes = [i64, i64, ci]
+    lib.qb_workspace_nbytes.restype = ctypes.c_size_t
+    lib.qb_workspace_nbytes.argtypes = [ci, i64, i64, i64, ci]
     lib.qb_bwd_workspace_nbytes.restype = ctypes.c_size_t
     lib.qb_bwd_workspace_nbytes.argtypes = [i64, i64, i64]
     lib.qb_quantize_groupwise.restype = ci
@@ -154,6 +156,13 @@ def qb_status_string(status):
 
 def qb_packed_nbytes(N, K, bits):
     return int(load_library().qb_packed_nbytes(N, K, bits))
+
+
+QB_OP_QUANTIZE_GROUPWISE, QB_OP_QUANTIZE_ACT, QB_OP_QLINEAR_FWD, QB_OP_QLINEAR_BWD_STE, QB_OP_EMBEDDING, QB_OP_POWER_ITERATION = range(6)
+
+
+def qb_workspace_nbytes(op, T, N, K, bits):
+    return int(load_library().qb_workspace_nbytes(int(op), T, N, K, bits))
 
 
 def qb_bwd_workspace_nbytes(T, N, K):

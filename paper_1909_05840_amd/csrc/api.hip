@@ -22,3 +22,19 @@ extern "C" size_t qb_packed_nbytes(int64_t N, int64_t K, int bits)
     if (!bits_ok(bits) || N <= 0 || N > (1 << 24) || !k_ok(K)) return 0;
     return (size_t)padded_rows(N) * (size_t)K * (size_t)bits / 8;
 }
+
+// declared in bwd_bf16.hip and hessian.hip
+extern "C" size_t qb_bwd_workspace_nbytes(int64_t T, int64_t N, int64_t K);
+extern "C" size_t qb_power_iteration_scratch_floats(void);
+
+extern "C" size_t qb_workspace_nbytes(int op, int64_t T, int64_t N, int64_t K, int bits)
+{
+    switch (op) {
+        case QB_OP_QLINEAR_BWD_STE:
+            return bits_ok(bits) ? qb_bwd_workspace_nbytes(T, N, K) : 0;
+        case QB_OP_POWER_ITERATION:
+            return qb_power_iteration_scratch_floats() * sizeof(float);
+        default:  // the quantizers, the forward calls and the embedding calls work in their inputs and outputs only
+            return 0;
+    }
+}

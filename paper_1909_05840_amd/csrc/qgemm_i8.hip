@@ -1389,6 +1389,7 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
 extern "C" qb_status qb_qlinear_fwd_batched(const qb_fwd_job *jobs, int n_jobs, void *stream)
 {
     if (n_jobs < 0 || (n_jobs > 0 && !jobs)) return QB_ERR_NULL;
+    if (n_jobs == 0) return QB_OK;
     for (int i = 0; i < n_jobs; ++i) {
         const qb_status s = check_fwd_job(jobs[i]);
         if (s != QB_OK) return s;

@@ -1004,6 +1004,8 @@ extern "C" qb_status qb_embedding_quantize_bits(const float *E, int64_t V, int64
     if (!E || !codes || !h || !m) return QB_ERR_NULL;
     if (bits != 4 && bits != 8) return QB_ERR_BITS;
     if (V <= 0 || V > (1 << 30) || !k_ok(d) || groups <= 0 || d % groups != 0) return QB_ERR_SHAPE;
+    // one workgroup row per EMB_ROWS table rows: the grid's second dimension holds at most 65535 of them
+    if ((V + EMB_ROWS - 1) / EMB_ROWS > 65535) return QB_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int cpg = (int)(d / groups);
     const dim3 grid((unsigned)((d / 4 + 255) / 256), (unsigned)((V + EMB_ROWS - 1) / EMB_ROWS));

@@ -47,6 +47,46 @@ def test_workspace_size(lib):
     assert qb.qb_bwd_workspace_nbytes(0, 768, 768) == 0
 
 
+def test_general_workspace_query(lib):
+    bwd = qb.qb_bwd_workspace_nbytes(4096, 768, 3072)
+    assert qb.qb_workspace_nbytes(qb.binding.QB_OP_QLINEAR_BWD_STE, 4096, 768, 3072, 3) == bwd
+    assert qb.qb_workspace_nbytes(qb.binding.QB_OP_QLINEAR_BWD_STE, 4096, 768, 3072, 5) == 0
+    assert qb.qb_workspace_nbytes(qb.binding.QB_OP_POWER_ITERATION, 0, 0, 0, 0) == 4 * lib.qb_power_iteration_scratch_floats()
+    for op in (qb.binding.QB_OP_QUANTIZE_GROUPWISE, qb.binding.QB_OP_QUANTIZE_ACT, qb.binding.QB_OP_QLINEAR_FWD,
+               qb.binding.QB_OP_EMBEDDING, 99):
+        assert qb.qb_workspace_nbytes(op, 4096, 768, 3072, 4) == 0
+
+
+def test_batched_calls_and_the_static_backward_refuse_bad_arguments_on_the_host(lib):
+    P = 0x1000
+    fj = qb.binding._FwdJob(P, P, 6.0, P, P, P, 4, 128, 4096, 768, 768, None, P)
+    arr = (qb.binding._FwdJob * 2)(fj, fj)
+    assert lib.qb_qlinear_fwd_batched(arr, 0, None) == 0
+    assert lib.qb_qlinear_fwd_batched(None, 2, None) == 1
+    arr[1].bits = 7
+    assert lib.qb_qlinear_fwd_batched(arr, 2, None) == 2
+    arr[1].bits = 4
+    arr[1].K = 100
+    assert lib.qb_qlinear_fwd_batched(arr, 2, None) == 3
+    arr[1].K = 768
+    arr[1].clip = 0.0
+    assert lib.qb_qlinear_fwd_batched(arr, 2, None) == 4
+    aj = qb.binding._ActJob(P, 16, 64, 6.0, P, P)
+    aarr = (qb.binding._ActJob * 2)(aj, aj)
+    assert lib.qb_quantize_act_batched(aarr, 0, None) == 0
+    aarr[1].K = 65
+    assert lib.qb_quantize_act_batched(aarr, 2, None) == 3
+    aarr[1].K = 64
+    aarr[1].Xq = None
+    assert lib.qb_quantize_act_batched(aarr, 2, None) == 1
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    # the static backward: shape and size checks come before the device is touched
+    assert lib.qb_qlinear_bwd_ste_static(vp(P), vp(P), cf(6.0), vp(P), vp(P), 4, 128, 12288, 3072, 768, vp(P), None, None) == 5
+    assert lib.qb_qlinear_bwd_ste_static(vp(P), vp(P), cf(6.0), vp(P), vp(P), 4, 128, 4096, 768, 100, vp(P), None, None) == 3
+    # embedding tables whose row count exceeds the grid's second dimension
+    assert lib.qb_embedding_quantize_bits(vp(P), 3000000, 64, 8, 8, vp(P), vp(P), vp(P), None) == 3
+
+
 def test_status_strings(lib):
     seen = {qb.qb_status_string(i) for i in range(7)}
     assert len(seen) == 7 and "unknown" not in " ".join(seen)

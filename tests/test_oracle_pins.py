@@ -770,3 +770,54 @@ def test_sensitivity_omega_and_power_iteration():
     assert err[30] < err[10] * (0.6 ** 2) ** 15                             # (3/5)^2 per step, with slack
     lam0, _ = oracle.power_iteration(lambda x: 0.0 * x, r.standard_normal(n), 3)
     assert (lam0 == 0).all()
+
+
+# ---- asymmetric group ranges given by the caller (App.: the range may be a sub-interval of [min, max]) ---------------
+@pytest.mark.parametrize("bits", BITS)
+def test_given_asymmetric_range_pins(bits):
+    from fractions import Fraction
+    L = 2 ** bits - 1
+    rng = np.random.default_rng(70 + bits)
+    # (a) lo = min, hi = max of every group reproduces the data-range quantizer bit for bit
+    W = rng.normal(0.01, 0.05, (12, 64)).astype(np.float32)
+    G = 3
+    lo = W.reshape(G, -1).min(1)
+    hi = W.reshape(G, -1).max(1)
+    c0, d0, q0, r0 = oracle.quantize_groupwise_asym(W, bits, G)
+    c1, d1, q1, r1 = oracle.quantize_groupwise_asym_range(W, bits, lo, hi)
+    assert (c0 == c1).all() and (d0.view(np.uint32) == d1.view(np.uint32)).all() and (q0 == q1).all() and (r0 == r1).all()
+    # (b) a lattice with exact arithmetic: lo = -3/8, Delta = 2^-4: codes = index, values below / above get 0 / L
+    dlt = 2.0 ** -4
+    lo1 = np.array([-0.375], np.float32)
+    hi1 = np.array([-0.375 + L * dlt], np.float32)
+    idx = rng.integers(0, L + 1, (4, 64))
+    Wl = (-0.375 + dlt * idx).astype(np.float32)
+    Wl[0, :4] = [-10.0, -0.376, hi1[0] + 1e-3, 99.0]
+    c, d, q, r = oracle.quantize_groupwise_asym_range(Wl, bits, lo1, hi1)
+    exp = idx.copy()
+    exp[0, :4] = [0, 0, L, L]
+    assert (c == exp).all() and d[0] == np.float32(dlt) and q[0] == np.float32(-0.375)
+    assert (r == (exp - 2 ** (bits - 1)).sum(1)).all()
+    # (c) nearest level of the clamped weight in exact rational arithmetic (away from ties by more than float error)
+    lo2 = np.array([-0.11, 0.02], np.float32)
+    hi2 = np.array([0.07, 0.09], np.float32)
+    W2 = rng.normal(0.0, 0.08, (2, 256)).astype(np.float32)
+    c, d, q, _ = oracle.quantize_groupwise_asym_range(W2, bits, lo2, hi2)
+    for g in range(2):
+        D, Q0, HI = Fraction(float(d[g])), Fraction(float(lo2[g])), Fraction(float(hi2[g]))
+        for j in range(256):
+            w = min(max(Fraction(float(W2[g, j])), Q0), HI)
+            t = (w - Q0) / D
+            near = min(max(int(round(t)), 0), L)
+            if abs(t - near) < Fraction(4999, 10000):
+                assert c[g, j] == near
+            assert abs(int(c[g, j]) - t) <= Fraction(1, 2) + Fraction(1, 1000)
+    # (d) a degenerate range lo == hi: Delta = 0, codes 0, Q = lo
+    c, d, q, r = oracle.quantize_groupwise_asym_range(W2[:1], bits, np.array([0.05], np.float32), np.array([0.05], np.float32))
+    assert (c == 0).all() and d[0] == 0.0 and (oracle.dequantize_groupwise_asym(c, d, q) == float(np.float32(0.05))).all()
+    # (e) monotone in w, and a narrower range clips more weights to the end codes
+    order = np.argsort(W2[0], kind="stable")
+    cc, _, _, _ = oracle.quantize_groupwise_asym_range(W2[:1], bits, lo2[:1], hi2[:1])
+    assert (np.diff(cc[0][order].astype(int)) >= 0).all()
+    cn, _, _, _ = oracle.quantize_groupwise_asym_range(W2[:1], bits, lo2[:1] / 2, hi2[:1] / 2)
+    assert ((cn == 0) | (cn == L)).sum() >= ((cc == 0) | (cc == L)).sum()
