@@ -310,6 +310,17 @@ qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float 
  */
 qb_status qb_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, int groups,
                                      void *packed, float *delta, float *q0, int32_t *rs_w, void *stream);
+/*
+ * qb_quantize_groupwise_asym with the range of every group given by the caller (App.: the range [q0, q_{2^k-1}] may be
+ * a sub-interval of the data's [min, max], X' = Clamp(X, q0, q_{2^k-1})): group g uses [lo[g], hi[g]]; weights outside
+ * are clamped first and get the end codes; Delta_g = fl(fl(hi - lo)/L), q0_g = lo.  lo = min and hi = max of the group
+ * give the codes of qb_quantize_groupwise_asym.
+ *   lo, hi  in  [G] fp32, finite, lo <= hi (not checked on the device; lo == hi gives Delta = 0 and codes 0)
+ * The result feeds qb_qlinear_fwd_asym and qb_qlinear_bwd_ste_asym unchanged.
+ */
+qb_status qb_quantize_groupwise_asym_range(const float *W, int64_t N, int64_t K, int bits, int groups,
+                                           const float *lo, const float *hi,
+                                           void *packed, float *delta, float *q0, int32_t *rs_w, void *stream);
 qb_status qb_qlinear_fwd_asym(const int8_t *Xq, const int32_t *rs_x, float clip,
                               const void *packed, const float *delta, const float *q0, const int32_t *rs_w,
                               int bits, int groups, int64_t T, int64_t N, int64_t K,

@@ -22,7 +22,7 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_act", "qb_quantize_act_batched", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
-           "qb_quantize_groupwise_asym", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
+           "qb_quantize_groupwise_asym", "qb_quantize_groupwise_asym_range", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
            "qb_power_iteration_scratch_floats", "qb_power_iteration", "qb_sensitivity_omega", "qb_rank_by_sensitivity",
            "qb_probe_mfma_i8")
 
@@ -93,6 +93,8 @@ def load_library():
     lib.qb_qlinear_bwd_ste_static.argtypes = [vp, vp, cf, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp]
     lib.qb_quantize_groupwise_asym.restype = ci
     lib.qb_quantize_groupwise_asym.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp]
+    lib.qb_quantize_groupwise_asym_range.restype = ci
+    lib.qb_quantize_groupwise_asym_range.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_asym.restype = ci
     lib.qb_qlinear_fwd_asym.argtypes = [vp, vp, cf, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_bwd_ste_asym.restype = ci
@@ -376,6 +378,25 @@ def qb_quantize_groupwise_asym(W, bits, groups, packed=None, delta=None, q0=None
     if rs_w is None:
         rs_w = torch.empty(N, dtype=torch.int32, device=dev)
     _check(lib.qb_quantize_groupwise_asym(_p(W), N, K, bits, groups, _p(packed), _p(delta), _p(q0), _p(rs_w), _stream()))
+    return packed, delta, q0, rs_w
+
+
+def qb_quantize_groupwise_asym_range(W, bits, lo, hi, packed=None, delta=None, q0=None, rs_w=None):
+    """Asymmetric group ranges [lo[g], hi[g]] given by the caller. Returns (packed, delta[G], q0[G], rs_w[N])."""
+    lib = load_library()
+    _dev(W, torch.float32, "W")
+    _dev(lo, torch.float32, "lo")
+    _dev(hi, torch.float32, "hi")
+    N, K = W.shape
+    groups = lo.numel()
+    dev = W.device
+    if packed is None:
+        packed = torch.empty(max(qb_packed_nbytes(N, K, bits), 1), dtype=torch.uint8, device=dev)
+    delta = delta if delta is not None else torch.empty(groups, dtype=torch.float32, device=dev)
+    q0 = q0 if q0 is not None else torch.empty(groups, dtype=torch.float32, device=dev)
+    rs_w = rs_w if rs_w is not None else torch.empty(N, dtype=torch.int32, device=dev)
+    _check(lib.qb_quantize_groupwise_asym_range(_p(W), N, K, bits, groups, _p(lo), _p(hi), _p(packed), _p(delta), _p(q0),
+                                                _p(rs_w), _stream()))
     return packed, delta, q0, rs_w
 
 

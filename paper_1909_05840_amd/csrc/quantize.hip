@@ -38,8 +38,9 @@ template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
 __device__ __forceinline__ void quantize_panel_body(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
     uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
-    int panel, uint8_t *smem)
+    int panel, uint8_t *smem, const float *__restrict__ clamp_hi = nullptr)
 {
+    // clamp_hi (ASYM, !FUSED): the range was given by the caller as [m[g], clamp_hi[g]]; weights outside are clamped
     const int tid = threadIdx.x;
     const int stride = K + 16;
     int *rowsum = reinterpret_cast<int *>(smem + (size_t)prow * stride);
@@ -108,6 +109,18 @@ __device__ __forceinline__ void quantize_panel_body(
             if (FUSED) m[g] = mg;
         }
     }
+    if constexpr (!FUSED && ASYM) {
+        if (clamp_hi) {  // a given range [lo, hi]: X' = Clamp(X, lo, hi)
+            const float hi = clamp_hi[g];
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                v[i].x = __builtin_amdgcn_fmed3f(v[i].x, mg, hi);
+                v[i].y = __builtin_amdgcn_fmed3f(v[i].y, mg, hi);
+                v[i].z = __builtin_amdgcn_fmed3f(v[i].z, mg, hi);
+                v[i].w = __builtin_amdgcn_fmed3f(v[i].w, mg, hi);
+            }
+        }
+    }
     if (!FUSED && !ASYM) {  // the range was given: it may be smaller than the group's max-abs (clipped range)
 #pragma unroll
         for (int i = 0; i < V; ++i) {
@@ -166,11 +179,12 @@ __device__ __forceinline__ void quantize_panel_body(
 template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
 __global__ __launch_bounds__(THREADS) void quantize_panel_kernel(
     const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
-    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w)
+    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
+    const float *__restrict__ clamp_hi)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     quantize_panel_body<BITS, THREADS, V, FUSED, ASYM>(W, K, rows_per_group, prow, inv_K, inv_prow, packed, h, m, rs_w,
-                                                       blockIdx.x, smem);
+                                                       blockIdx.x, smem, clamp_hi);
 }
 
 // ---- asymmetric ranges: min and max of every group.  Floats are mapped to unsigned keys that order like the
@@ -232,6 +246,17 @@ __global__ void range_finish_kernel(float *delta, float *q0, int n, float L)
         const float lo = key_float(reinterpret_cast<const uint32_t *>(q0)[i]);
         delta[i] = __fdiv_rn(__fsub_rn(hi, lo), L);
         q0[i] = lo;
+    }
+}
+
+// given ranges [lo, hi] -> q0 = lo and Delta = fl(fl(hi - lo)/L)
+__global__ void range_given_kernel(const float *__restrict__ lo, const float *__restrict__ hi, float *delta, float *q0, int n,
+                                   float L)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        delta[i] = __fdiv_rn(__fsub_rn(hi[i], lo[i]), L);
+        q0[i] = lo[i];
     }
 }
 
@@ -705,11 +730,11 @@ __global__ __launch_bounds__(256) void embedding_gather_kernel(const uint8_t *__
 
 template <int BITS, int THREADS, bool ASYM = false>
 void launch_panel(const float *W, int K, int rows_per_group, int prow, int panels, uint8_t *packed, float *h, float *m,
-                  int32_t *rs_w, hipStream_t st)
+                  int32_t *rs_w, hipStream_t st, const float *clamp_hi = nullptr)
 {
     const size_t lds = (size_t)prow * (K + 16) + (size_t)prow * 4 + 128;
     hipLaunchKernelGGL((quantize_panel_kernel<BITS, THREADS, 8, false, ASYM>), dim3(panels), dim3(THREADS), lds, st, W, K,
-                       rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w);
+                       rows_per_group, prow, 1.0f / (float)K, 1.0f / (float)prow, packed, h, m, rs_w, clamp_hi);
 }
 
 // groups too large for one workgroup's registers: max-abs by slices, then panels of whole rows
@@ -762,13 +787,13 @@ qb_status quantize_asym(const float *W, int64_t N, int64_t K, int groups, uint8_
         const dim3 grid(groups);
         if (gelems <= 256 * 4 * 8)
             hipLaunchKernelGGL((quantize_panel_kernel<BITS, 256, 8, true, true>), grid, dim3(256), lds, st, W, (int)K, rpg, rpg,
-                               inv_K, inv_rows, packed, delta, q0, rs_w);
+                               inv_K, inv_rows, packed, delta, q0, rs_w, static_cast<const float *>(nullptr));
         else if (gelems <= 512 * 4 * 10)
             hipLaunchKernelGGL((quantize_panel_kernel<BITS, 512, 10, true, true>), grid, dim3(512), lds, st, W, (int)K, rpg, rpg,
-                               inv_K, inv_rows, packed, delta, q0, rs_w);
+                               inv_K, inv_rows, packed, delta, q0, rs_w, static_cast<const float *>(nullptr));
         else
             hipLaunchKernelGGL((quantize_panel_kernel<BITS, 1024, 8, true, true>), grid, dim3(1024), lds, st, W, (int)K, rpg,
-                               rpg, inv_K, inv_rows, packed, delta, q0, rs_w);
+                               rpg, inv_K, inv_rows, packed, delta, q0, rs_w, static_cast<const float *>(nullptr));
         return launch_status();
     }
     int prow = 1;
@@ -788,12 +813,47 @@ qb_status quantize_asym(const float *W, int64_t N, int64_t K, int groups, uint8_
     return launch_status();
 }
 
+// asymmetric ranges given by the caller: Delta and q0 from [lo, hi], then panels that clamp to the range
+template <int BITS>
+qb_status quantize_asym_given(const float *W, int64_t N, int64_t K, int groups, const float *lo, const float *hi,
+                              uint8_t *packed, float *delta, float *q0, int32_t *rs_w, hipStream_t st)
+{
+    const int rpg = (int)(N / groups);
+    int prow = 1;
+    for (int p = rpg; p >= 1; --p)
+        if (rpg % p == 0 && (int64_t)p * K <= kMaxFusedElems) { prow = p; break; }
+    hipLaunchKernelGGL(range_given_kernel, dim3((groups + 255) / 256), dim3(256), 0, st, lo, hi, delta, q0, groups,
+                       (float)((1 << BITS) - 1));
+    const int64_t pelems = (int64_t)prow * K;
+    if (pelems <= 8192) launch_panel<BITS, 256, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st, hi);
+    else if (pelems <= 16384) launch_panel<BITS, 512, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st, hi);
+    else launch_panel<BITS, 1024, true>(W, (int)K, rpg, prow, (int)(N / prow), packed, delta, q0, rs_w, st, hi);
+    return launch_status();
+}
+
 }  // namespace
 }  // namespace qb
 
 using namespace qb;
 
 extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream);
+
+extern "C" qb_status qb_quantize_groupwise_asym_range(const float *W, int64_t N, int64_t K, int bits, int groups,
+                                                      const float *lo, const float *hi, void *packed, float *delta,
+                                                      float *q0, int32_t *rs_w, void *stream)
+{
+    if (!W || !lo || !hi || !packed || !delta || !q0 || !rs_w) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0) return QB_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *p = static_cast<uint8_t *>(packed);
+    switch (bits) {
+        case 2: return quantize_asym_given<2>(W, N, K, groups, lo, hi, p, delta, q0, rs_w, st);
+        case 3: return quantize_asym_given<3>(W, N, K, groups, lo, hi, p, delta, q0, rs_w, st);
+        case 4: return quantize_asym_given<4>(W, N, K, groups, lo, hi, p, delta, q0, rs_w, st);
+        default: return quantize_asym_given<8>(W, N, K, groups, lo, hi, p, delta, q0, rs_w, st);
+    }
+}
 
 extern "C" qb_status qb_quantize_groupwise_asym(const float *W, int64_t N, int64_t K, int bits, int groups, void *packed,
                                                 float *delta, float *q0, int32_t *rs_w, void *stream)

@@ -288,3 +288,43 @@ def test_forward_few_tokens_bert_shapes(qb, bits, T):
     torch.cuda.synchronize()
     for Yb, Y in zip(Ys, refs):
         assert torch.equal(Yb, Y)
+
+
+# ---- asymmetric ranges given by the caller -------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("shape", [(768, 768, 128), (2304, 768, 12), (768, 3072, 128), (6, 64, 6), (40, 192, 8), (1030, 64, 1)])
+def test_quantize_given_asymmetric_ranges(qb, bits, shape):
+    """Group ranges [lo, hi] from the caller (a 1 % / 99 % percentile band, the data's own [min, max] for one group and
+    a degenerate range for another): codes, Delta, q0 and row sums bit for bit, then the forward through
+    qb_qlinear_fwd_asym against the oracle."""
+    N, K, groups = shape
+    say("given asym ranges", shape, "bits", bits)
+    W = wl.weight(N, K, seed=3 * N + K + bits) + 0.01
+    Wg = W.reshape(groups, -1)
+    lo = torch.quantile(Wg.double(), 0.01, dim=1).float()
+    hi = torch.quantile(Wg.double(), 0.99, dim=1).float()
+    lo[0], hi[0] = Wg[0].min(), Wg[0].max()
+    if groups > 1:
+        lo[-1] = hi[-1] = 0.02
+    packed, delta, q0, rs_w = qb.qb_quantize_groupwise_asym_range(W.to(DEV), bits, lo.to(DEV), hi.to(DEV))
+    codes = qb.qb_unpack_codes(packed, N, K, bits)
+    torch.cuda.synchronize()
+    oc, od, oq0, ors = oracle.quantize_groupwise_asym_range(W.numpy(), bits, lo.numpy(), hi.numpy())
+    assert (codes.cpu().numpy() == oc).all()
+    assert (delta.cpu().numpy().view(np.uint32) == od.view(np.uint32)).all()
+    assert (q0.cpu().numpy().view(np.uint32) == oq0.view(np.uint32)).all()
+    assert (rs_w.cpu().numpy() == ors).all()
+    L = 2 ** bits - 1
+    assert ((oc == 0) | (oc == L)).sum() > 0   # something was clamped
+    T = 70
+    X = wl.activation(T, K, seed=N + bits)
+    Xq, rs_x = qb.qb_quantize_act(X.to(DEV), CLIP)
+    Y, A4 = qb.qb_qlinear_fwd_asym(Xq, rs_x, CLIP, packed, delta, q0, rs_w, bits, groups, N, want_a4=True)
+    torch.cuda.synchronize()
+    oxq, _ = oracle.quantize_act(X.numpy(), CLIP)
+    Yo, S = oracle.qlinear_fwd_asym(oxq, CLIP, oc, od, oq0, want_s=True)
+    R = (2 * oxq.astype(np.int64) + 1).sum(1)
+    hx = float(np.float32(CLIP) / np.float32(255.0))
+    rows = N // groups
+    mag = hx * (np.abs(od.astype(np.float64)).repeat(rows)[None, :] * np.abs(S) + np.abs(oq0.astype(np.float64)).repeat(rows)[None, :] * np.abs(R)[:, None])
+    assert (np.abs(Y.cpu().numpy().astype(np.float64) - Yo) <= 1e-6 * mag).all()
