@@ -149,15 +149,36 @@ struct Quantizer {
     }
     __device__ __forceinline__ uint32_t code(float w) const { return (uint32_t)code_f(w); }
     // four codes, one per byte (v_cvt_pk_u8_f32 converts and inserts in one instruction; its input is
-    // an integer-valued float here, so its rounding never comes into play)
-    __device__ __forceinline__ uint32_t code4(const float4 v) const
+    // an integer-valued float here, so its rounding never comes into play).  FAST (the caller has tested `fast`
+    // once for the range): the reciprocal route for all four and one test for the lot: if any of the four products
+    // came within 1e-4 of a rounding boundary, all four are redone with the division (for the other three it gives
+    // the same code, by the bound above).  One branch per four weights instead of one per weight.
+    template <bool FAST>
+    __device__ __forceinline__ uint32_t code4t(const float4 v) const
     {
-        uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.x), 0, 0u);
-        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.y), 1, q);
-        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.z), 2, q);
-        q = __builtin_amdgcn_cvt_pk_u8_f32(code_f(v.w), 3, q);
+        if constexpr (FAST) {
+            // one weight at a time, so that few values are alive at once (the callers hold whole groups in registers)
+            float t = __fmul_rn(__fadd_rn(v.x, m), rinv), r = rintf(t);
+            float far = fabsf(t - r);
+            uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(r, 0, 0u);
+            t = __fmul_rn(__fadd_rn(v.y, m), rinv); r = rintf(t);
+            far = fmaxf(far, fabsf(t - r));
+            q = __builtin_amdgcn_cvt_pk_u8_f32(r, 1, q);
+            t = __fmul_rn(__fadd_rn(v.z, m), rinv); r = rintf(t);
+            far = fmaxf(far, fabsf(t - r));
+            q = __builtin_amdgcn_cvt_pk_u8_f32(r, 2, q);
+            t = __fmul_rn(__fadd_rn(v.w, m), rinv); r = rintf(t);
+            far = fmaxf(far, fabsf(t - r));
+            q = __builtin_amdgcn_cvt_pk_u8_f32(r, 3, q);
+            if (far <= 0.4999f) return q;  // (false also for NaN)
+        }
+        uint32_t q = __builtin_amdgcn_cvt_pk_u8_f32(rintf(__fdiv_rn(__fadd_rn(v.x, m), delta)), 0, 0u);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(rintf(__fdiv_rn(__fadd_rn(v.y, m), delta)), 1, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(rintf(__fdiv_rn(__fadd_rn(v.z, m), delta)), 2, q);
+        q = __builtin_amdgcn_cvt_pk_u8_f32(rintf(__fdiv_rn(__fadd_rn(v.w, m), delta)), 3, q);
         return q;
     }
+    __device__ __forceinline__ uint32_t code4(const float4 v) const { return fast ? code4t<true>(v) : code4t<false>(v); }
 };
 
 // ---- host-side argument checks ------------------------------------------------------------------

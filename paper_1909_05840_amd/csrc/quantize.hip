@@ -10,6 +10,7 @@
 // operation (add, divide, round-half-even), in the order the paper's appendix gives them
 // (X' - q0, / Delta, round), so the codes do not depend on how the work is split over lanes.
 #include "qb_common.hpp"
+#include <type_traits>
 
 namespace qb {
 namespace {
@@ -28,72 +29,67 @@ __device__ __forceinline__ int fast_div(int e, int d, float inv)
     return q;
 }
 
-// One workgroup quantizes and packs a panel of `prow` consecutive rows that lie inside one
-// group.  FUSED: the panel is the whole group, max-abs is found here and m/h are written.
-// Otherwise m was found by absmax_slices_kernel and only the panel starting a group writes h.
-// LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then THREADS/64 floats.
+// Barrier between the phases of a panel.  BARE: for the streaming kernel, whose copies of the next group into LDS
+// (issued as inline assembly, unknown to the compiler) must stay in flight across the phases: only this wavefront's
+// LDS operations are awaited (lgkmcnt 0), then a bare s_barrier; __syncthreads() would also wait for the copies.
+template <bool BARE>
+__device__ __forceinline__ void panel_sync()
+{
+    if constexpr (BARE) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else __syncthreads();
+}
+
+// A team of `threads` threads (a whole workgroup, or a 64-multiple part of one: `tid` is the thread's number in
+// the team and `smem` the team's own LDS) quantizes and packs a panel of `prow` consecutive rows that lie inside
+// one group, from the panel's weights in registers: float4 number tid + i*threads of the panel in v[i]; mx (and mn
+// if ASYM) the thread's share of the range.  Every team of a workgroup must come here (the barriers are the
+// workgroup's).  FUSED: the panel is the whole group, the range is found here and m/h are written.  Otherwise m was
+// found before and only the panel starting a group writes h.
+// LDS: prow rows of (K + 16) code bytes, then prow int32 row sums, then 2*threads/64 floats.
 // ASYM: the group's range is [q0, q0 + L*Delta] with q0 in m[g] and Delta in h[g]: read (found before) if !FUSED,
 // found here as the group's minimum and fl(fl(max - min)/L) and written if FUSED.
-template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
-__device__ __forceinline__ void quantize_panel_body(
-    const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
-    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
-    int panel, uint8_t *smem, const float *__restrict__ clamp_hi = nullptr)
+// PARK: the thread's float4 numbers V .. V+PARK-1 wait in LDS (park[p * park_stride]) instead of registers.
+template <int BITS, int V, bool FUSED, bool ASYM, bool BARE, int PARK = 0>
+__device__ __forceinline__ void panel_finish(
+    float4 (&v)[V], float mx, float mn, const int tid, const int threads, int K, int rows_per_group, int prow, float inv_K,
+    float inv_prow, uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m,
+    int32_t *__restrict__ rs_w, int panel, uint8_t *smem, const float *__restrict__ clamp_hi,
+    const float4 *park = nullptr, int park_stride = 0)
 {
+    static_assert(PARK == 0 || (FUSED && !ASYM), "parked weights: the symmetric one-pass form only");
     // clamp_hi (ASYM, !FUSED): the range was given by the caller as [m[g], clamp_hi[g]]; weights outside are clamped
-    const int tid = threadIdx.x;
     const int stride = K + 16;
     int *rowsum = reinterpret_cast<int *>(smem + (size_t)prow * stride);
     float *red = reinterpret_cast<float *>(rowsum + prow);
-
     const int row0 = panel * prow;  // first row of the panel
     const int g = row0 / rows_per_group;
-    const float4 *src = reinterpret_cast<const float4 *>(W + (size_t)row0 * K);
     const int n4 = prow * (K >> 2);
     constexpr float Lf = (float)((1 << BITS) - 1);
 
-    float4 v[V];
-    float mx = 0.0f, mn = 0.0f;
-    if constexpr (FUSED && ASYM) mx = mn = W[(size_t)row0 * K];  // any element of the group
-#pragma unroll
-    for (int i = 0; i < V; ++i) {
-        const int idx = tid + i * THREADS;
-        if (idx < n4) {
-            v[i] = src[idx];
-            if constexpr (FUSED && ASYM) {
-                mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
-                mn = fminf(fminf(mn, fminf(v[i].x, v[i].y)), fminf(v[i].z, v[i].w));
-            } else if (FUSED) {
-                mx = absmax4(v[i], mx);
-            }
-        }
-    }
-    for (int r = tid; r < prow; r += THREADS) rowsum[r] = 0;
+    for (int r = tid; r < prow; r += threads) rowsum[r] = 0;
 
     float mg, dg = 0.0f;
     if (FUSED) {
-        constexpr int NW = THREADS / 64;
+        const int nw = threads >> 6;
         mx = wave_max(mx);
         if constexpr (ASYM) mn = -wave_max(-mn);
         if ((tid & 63) == 0) {
             red[tid >> 6] = mx;
-            if constexpr (ASYM) red[NW + (tid >> 6)] = mn;
+            if constexpr (ASYM) red[nw + (tid >> 6)] = mn;
         }
-        __syncthreads();
+        panel_sync<BARE>();
         mg = red[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) mg = fmaxf(mg, red[w]);
+        for (int w = 1; w < nw; ++w) mg = fmaxf(mg, red[w]);
         if constexpr (ASYM) {
-            float lo = red[NW];
-#pragma unroll
-            for (int w = 1; w < NW; ++w) lo = fminf(lo, red[NW + w]);
+            float lo = red[nw];
+            for (int w = 1; w < nw; ++w) lo = fminf(lo, red[nw + w]);
             dg = __fdiv_rn(__fsub_rn(mg, lo), Lf);
             mg = lo;
         }
     } else {
         mg = m[g];
         if constexpr (ASYM) dg = h[g];
-        __syncthreads();
+        panel_sync<BARE>();
     }
     Quantizer qz;
     if constexpr (ASYM) qz.set_range(mg, dg);
@@ -131,22 +127,48 @@ __device__ __forceinline__ void quantize_panel_body(
         }
     }
 
-    // codes, four per dword, into the LDS image of the panel
+    // codes, four per dword, into the LDS image of the panel.  Row and column of a thread's float4 advance by a fixed
+    // step from one to the next (no division per float4), and the test `fast` is taken once for the group.
+    {
+        const int step = 4 * threads;
+        const int dr = fast_div(step, K, inv_K), dc = step - dr * K;  // uniform
+        int r = fast_div(tid << 2, K, inv_K);
+        int c = (tid << 2) - r * K;
+        auto walk = [&](auto fast_tag) {
 #pragma unroll
-    for (int i = 0; i < V; ++i) {
-        const int idx = tid + i * THREADS;
-        if (idx < n4) {
-            const int e = idx << 2;
-            const int r = fast_div(e, K, inv_K);
-            const int c = e - r * K;
-            *reinterpret_cast<uint32_t *>(smem + (size_t)r * stride + c) = qz.code4(v[i]);
-        }
+            for (int i = 0; i < V; ++i) {
+                const int idx = tid + i * threads;
+                if (idx < n4)
+                    *reinterpret_cast<uint32_t *>(smem + (size_t)(r * stride + c)) = qz.template code4t<decltype(fast_tag)::value>(v[i]);
+                r += dr;
+                c += dc;
+                if (c >= K) {
+                    c -= K;
+                    ++r;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PARK; ++p) {
+                const int idx = tid + (V + p) * threads;
+                if (idx < n4)
+                    *reinterpret_cast<uint32_t *>(smem + (size_t)(r * stride + c)) =
+                        qz.template code4t<decltype(fast_tag)::value>(park[p * park_stride]);
+                r += dr;
+                c += dc;
+                if (c >= K) {
+                    c -= K;
+                    ++r;
+                }
+            }
+        };
+        if (qz.fast) walk(std::true_type{});
+        else walk(std::false_type{});
     }
-    __syncthreads();
+    panel_sync<BARE>();
 
     // regroup into 32-code slots; consecutive threads take consecutive rows of one column run
     const int nruns = prow * (K >> 5);
-    for (int id = tid; id < nruns; id += THREADS) {
+    for (int id = tid; id < nruns; id += threads) {
         const int rc = fast_div(id, prow, inv_prow);
         const int r = id - rc * prow;
         const uint4 lo = *reinterpret_cast<const uint4 *>(smem + (size_t)r * stride + rc * 32);
@@ -172,8 +194,39 @@ __device__ __forceinline__ void quantize_panel_body(
             dst[2] = out[2];
         }
     }
-    __syncthreads();
-    for (int r = tid; r < prow; r += THREADS) rs_w[row0 + r] = rowsum[r] - K * (1 << (BITS - 1));
+    panel_sync<BARE>();
+    for (int r = tid; r < prow; r += threads) rs_w[row0 + r] = rowsum[r] - K * (1 << (BITS - 1));
+}
+
+// One workgroup, one panel: the panel's weights are read from global memory into registers, then panel_finish.
+template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
+__device__ __forceinline__ void quantize_panel_body(
+    const float *__restrict__ W, int K, int rows_per_group, int prow, float inv_K, float inv_prow,
+    uint8_t *__restrict__ packed, float *__restrict__ h, float *__restrict__ m, int32_t *__restrict__ rs_w,
+    int panel, uint8_t *smem, const float *__restrict__ clamp_hi = nullptr)
+{
+    const int tid = threadIdx.x;
+    const int row0 = panel * prow;
+    const float4 *src = reinterpret_cast<const float4 *>(W + (size_t)row0 * K);
+    const int n4 = prow * (K >> 2);
+    float4 v[V];
+    float mx = 0.0f, mn = 0.0f;
+    if constexpr (FUSED && ASYM) mx = mn = W[(size_t)row0 * K];  // any element of the group
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const int idx = tid + i * THREADS;
+        if (idx < n4) {
+            v[i] = src[idx];
+            if constexpr (FUSED && ASYM) {
+                mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+                mn = fminf(fminf(mn, fminf(v[i].x, v[i].y)), fminf(v[i].z, v[i].w));
+            } else if (FUSED) {
+                mx = absmax4(v[i], mx);
+            }
+        }
+    }
+    panel_finish<BITS, V, FUSED, ASYM, false>(v, mx, mn, tid, THREADS, K, rows_per_group, prow, inv_K, inv_prow, packed, h, m,
+                                              rs_w, panel, smem, clamp_hi);
 }
 
 template <int BITS, int THREADS, int V, bool FUSED, bool ASYM = false>
@@ -264,34 +317,76 @@ constexpr int kMaxFusedElems = 1024 * 4 * 8;  // one group in the registers of 1
 
 // Several matrices in one launch (a fine-tuning step re-quantizes every matrix of the model):
 // workgroup w serves group w - first_wg[j] of job j.  Passed by value as the kernel argument.
+constexpr int kQuantBatch = 48;  // jobs of one launch: the descriptor below is the kernel argument (under 4 KB)
 struct QuantBatch {
     int n;
-    int first_wg[QB_MAX_BATCH + 1];
-    const float *W[QB_MAX_BATCH];
-    uint8_t *packed[QB_MAX_BATCH];
-    float *h[QB_MAX_BATCH];
-    float *m[QB_MAX_BATCH];
-    int32_t *rs_w[QB_MAX_BATCH];
-    int K[QB_MAX_BATCH];
-    int rows_per_group[QB_MAX_BATCH];
-    int bits[QB_MAX_BATCH];
-    float inv_K[QB_MAX_BATCH];
-    float inv_rows[QB_MAX_BATCH];
+    int first_wg[kQuantBatch + 1];
+    const float *W[kQuantBatch];
+    uint8_t *packed[kQuantBatch];
+    float *h[kQuantBatch];
+    float *m[kQuantBatch];
+    int32_t *rs_w[kQuantBatch];
+    int K[kQuantBatch];
+    int rows_per_group[kQuantBatch];
+    int bits[kQuantBatch];
+    float inv_K[kQuantBatch];
+    float inv_rows[kQuantBatch];
+    int per_item[kQuantBatch];    // groups per work item (first_wg counts items)
+    uint32_t team_bytes[kQuantBatch];  // LDS of one team of the job
 };
 
-template <int THREADS, int V>
-__global__ __launch_bounds__(THREADS) void quantize_batched_kernel(const QuantBatch b)
+// Resident workgroups walk over work items: item w is `per_item` (1, 2 or 4) consecutive groups of one matrix, one
+// group per team of THREADS/per_item threads, so that small groups do not leave most of a workgroup idle.
+// Why resident: a workgroup has no loads in flight while it computes, and workgroups that start together share the
+// memory bandwidth evenly and so finish loading together: launched one per group they stay in step through their two
+// or three rounds and the memory system idles for about a third of the time (measured with timestamps per phase).
+// Walking over many items, the workgroups of a CU drift apart and loads of some run under the arithmetic of others.
+template <int THREADS, int V, int PARK, int MIN_WAVES>
+__global__ __launch_bounds__(THREADS, MIN_WAVES) void quantize_batched_kernel(const QuantBatch b, uint32_t park_off)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    int j = 0;
-    while (j + 1 < b.n && (int)blockIdx.x >= b.first_wg[j + 1]) ++j;
-    const int g = blockIdx.x - b.first_wg[j];
-    const int rpg = b.rows_per_group[j];
-    switch (b.bits[j]) {
-        case 2: quantize_panel_body<2, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 3: quantize_panel_body<3, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        case 4: quantize_panel_body<4, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
-        default: quantize_panel_body<8, THREADS, V, true>(b.W[j], b.K[j], rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, smem); break;
+    constexpr int LOG_THREADS = THREADS == 1024 ? 10 : THREADS == 512 ? 9 : 8;
+    static_assert(THREADS == 1 << LOG_THREADS, "256, 512 or 1024 threads");
+    const int total = b.first_wg[b.n];
+    int j = 0;  // the job of the item: items come in rising order, so the search goes on from the last one
+    for (int item = blockIdx.x; item < total; item += gridDim.x) {
+        while (j + 1 < b.n && item >= b.first_wg[j + 1]) ++j;
+        const int per = b.per_item[j];
+        const int sh = LOG_THREADS - (per >> 1), threads = 1 << sh;  // per is 1, 2 or 4: teams of whole wavefronts
+        const int team = threadIdx.x >> sh, tid = threadIdx.x & (threads - 1);
+        const int rpg = b.rows_per_group[j], K = b.K[j];
+        const int n4 = rpg * (K >> 2);                                // float4 of a group
+        const int g = (item - b.first_wg[j]) * per + team;
+        const float4 *src = reinterpret_cast<const float4 *>(b.W[j]) + (size_t)g * n4;
+        float4 v[V];
+        float mx = 0.0f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int idx = tid + i * threads;
+            if (idx < n4) {
+                v[i] = src[idx];
+                mx = absmax4(v[i], mx);
+            }
+        }
+        // V float4 stay in registers, PARK more wait in LDS (behind every team's area), so that 64 registers a thread do
+        float4 *park = reinterpret_cast<float4 *>(smem + park_off) + threadIdx.x;
+#pragma unroll
+        for (int p = 0; p < PARK; ++p) {
+            const int idx = tid + (V + p) * threads;
+            if (idx < n4) {
+                const float4 x = src[idx];
+                mx = absmax4(x, mx);
+                park[p * THREADS] = x;
+            }
+        }
+        uint8_t *lds = smem + (size_t)team * b.team_bytes[j];
+        switch (b.bits[j]) {
+            case 2: panel_finish<2, V, true, false, false, PARK>(v, mx, 0.0f, tid, threads, K, rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, lds, nullptr, park, THREADS); break;
+            case 3: panel_finish<3, V, true, false, false, PARK>(v, mx, 0.0f, tid, threads, K, rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, lds, nullptr, park, THREADS); break;
+            case 4: panel_finish<4, V, true, false, false, PARK>(v, mx, 0.0f, tid, threads, K, rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, lds, nullptr, park, THREADS); break;
+            default: panel_finish<8, V, true, false, false, PARK>(v, mx, 0.0f, tid, threads, K, rpg, rpg, b.inv_K[j], b.inv_rows[j], b.packed[j], b.h[j], b.m[j], b.rs_w[j], g, lds, nullptr, park, THREADS); break;
+        }
+        __syncthreads();  // the row sums were read to the end before the next item clears them
     }
 }
 
@@ -915,6 +1010,18 @@ static qb_status check_quant_job(const qb_quant_job &j)
     return QB_OK;
 }
 
+// How many consecutive groups of a job one work item takes (one team of threads/per threads each): at most per_cap,
+// as many as the teams' registers (cap float4 a thread) and a modest LDS hold.
+static int groups_per_item(const qb_quant_job &j, int threads, int cap, int per_cap)
+{
+    const int rpg = (int)(j.N / j.groups);
+    const int64_t gelems = (int64_t)rpg * j.K;
+    const size_t team = (size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 80;
+    int per = per_cap;
+    while (per > 1 && (j.groups % per != 0 || gelems > (int64_t)(threads / per) * 4 * cap || per * team > 48 * 1024)) per >>= 1;
+    return per;
+}
+
 extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int n_jobs, void *stream)
 {
     if (n_jobs < 0) return QB_ERR_SHAPE;
@@ -925,21 +1032,39 @@ extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int
         if (s != QB_OK) return s;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // A launch has one workgroup size, chosen for its largest group; a group is held in registers.  Measured on
+    // BERT-base groups (18432 weights): 512 threads with up to ten float4 each beat 1024 threads with eight (more
+    // workgroups per CU in different phases, cheaper barriers).
+    int64_t max_elems = 0;
+    for (int i = 0; i < n_jobs; ++i) {
+        const int64_t gelems = jobs[i].N / jobs[i].groups * jobs[i].K;
+        if (gelems <= kMaxFusedElems && gelems > max_elems) max_elems = gelems;
+    }
+    const int threads = max_elems <= 256 * 4 * 8 ? 256 : max_elems <= 512 * 4 * 10 ? 512 : 1024;
+    const int cap = threads == 512 ? 10 : 8;  // float4 per thread
+    // groups per work item: 4 if that still leaves every resident workgroup an item, else 2, else 1
+    const int resident = 2048 / threads * 256;  // workgroups that fit the 256 CUs at 64 registers a thread
+    int per_cap = 4;
+    for (; per_cap > 1; per_cap >>= 1) {
+        int64_t items = 0;
+        for (int i = 0; i < n_jobs; ++i)
+            if (jobs[i].N / jobs[i].groups * jobs[i].K <= kMaxFusedElems)
+                items += jobs[i].groups / groups_per_item(jobs[i], threads, cap, per_cap);
+        if (items >= resident) break;
+    }
     QuantBatch b;
-    auto flush = [&](int max_elems, size_t lds) {
-        if (b.n == 0) return;
-        // a group is held in registers.  Measured on BERT-base groups (18432 weights): 512 threads with up
-        // to ten float4 each beat 1024 threads with eight (more workgroups per CU in different phases,
-        // cheaper barriers): 33.5 us instead of 42 us for the sixteen matrices of an encoder layer.
-        const dim3 grid(b.first_wg[b.n]);
-        if (max_elems <= 256 * 4 * 8) hipLaunchKernelGGL((quantize_batched_kernel<256, 8>), grid, dim3(256), lds, st, b);
-        else if (max_elems <= 512 * 4 * 10) hipLaunchKernelGGL((quantize_batched_kernel<512, 10>), grid, dim3(512), lds, st, b);
-        else hipLaunchKernelGGL((quantize_batched_kernel<1024, 8>), grid, dim3(1024), lds, st, b);
-        b.n = 0;
-    };
     b.n = 0;
-    int max_elems = 0;
     size_t lds = 0;
+    auto flush = [&]() {
+        if (b.n == 0) return;
+        const int items = b.first_wg[b.n];
+        const dim3 grid(items < resident ? items : resident);
+        const uint32_t park_off = (uint32_t)lds;
+        if (threads == 256) hipLaunchKernelGGL((quantize_batched_kernel<256, 8, 0, 8>), grid, dim3(256), lds, st, b, park_off);
+        else if (threads == 512) hipLaunchKernelGGL((quantize_batched_kernel<512, 8, 2, 8>), grid, dim3(512), lds + 2 * 512 * 16, st, b, park_off);
+        else hipLaunchKernelGGL((quantize_batched_kernel<1024, 8, 0, 8>), grid, dim3(1024), lds, st, b, park_off);
+        b.n = 0; lds = 0;
+    };
     for (int i = 0; i < n_jobs; ++i) {
         const qb_quant_job &j = jobs[i];
         const int rpg = (int)(j.N / j.groups);
@@ -949,18 +1074,20 @@ extern "C" qb_status qb_quantize_groupwise_batched(const qb_quant_job *jobs, int
             if (s != QB_OK) return s;
             continue;
         }
-        if (b.n == 0) { max_elems = 0; lds = 0; b.first_wg[0] = 0; }
+        const size_t team = ((size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 64 + 15) & ~(size_t)15;  // at most 34 KB
+        const int per = groups_per_item(j, threads, cap, per_cap);
+        if (b.n == 0) b.first_wg[0] = 0;
         const int k = b.n++;
         b.W[k] = j.W; b.packed[k] = static_cast<uint8_t *>(j.packed); b.h[k] = j.h; b.m[k] = j.m; b.rs_w[k] = j.rs_w;
         b.K[k] = (int)j.K; b.rows_per_group[k] = rpg; b.bits[k] = j.bits;
         b.inv_K[k] = 1.0f / (float)j.K; b.inv_rows[k] = 1.0f / (float)rpg;
-        b.first_wg[k + 1] = b.first_wg[k] + j.groups;
-        if ((int)gelems > max_elems) max_elems = (int)gelems;
-        const size_t need_lds = (size_t)rpg * (j.K + 16) + (size_t)rpg * 4 + 64;
-        if (need_lds > lds) lds = need_lds;
-        if (b.n == QB_MAX_BATCH) flush(max_elems, lds);
+        b.per_item[k] = per;
+        b.team_bytes[k] = (uint32_t)team;
+        b.first_wg[k + 1] = b.first_wg[k] + j.groups / per;
+        if (per * team > lds) lds = per * team;
+        if (b.n == kQuantBatch) flush();
     }
-    flush(max_elems, lds);
+    flush();
     return launch_status();
 }
 

@@ -328,3 +328,50 @@ def test_quantize_given_asymmetric_ranges(qb, bits, shape):
     rows = N // groups
     mag = hx * (np.abs(od.astype(np.float64)).repeat(rows)[None, :] * np.abs(S) + np.abs(oq0.astype(np.float64)).repeat(rows)[None, :] * np.abs(R)[:, None])
     assert (np.abs(Y.cpu().numpy().astype(np.float64) - Yo) <= 1e-6 * mag).all()
+
+
+def _check_quant_job(qb, job, out):
+    packed, h, m, rs = out
+    W = job["W"]
+    N, K = W.shape
+    oc, oh, om, ors = oracle.quantize_groupwise(W.cpu().numpy(), job["bits"], job["groups"])
+    codes = qb.qb_unpack_codes(packed, N, K, job["bits"]).cpu().numpy()
+    assert (codes == oc).all(), (N, K, job["bits"], job["groups"])
+    assert (h.cpu().numpy().view(np.uint32) == oh.view(np.uint32)).all()
+    assert (m.cpu().numpy().view(np.uint32) == om.view(np.uint32)).all()
+    assert (rs.cpu().numpy() == ors).all()
+
+
+def test_quantize_batched_work_items(qb):
+    """The batched quantizer's work items: one, two or four groups per workgroup (teams of threads), groups whose
+    size is no multiple of a team, group counts not divisible by four or two, weights parked in LDS (groups of more
+    than 16384 weights in the 512-thread kernel), all three workgroup sizes, more jobs than one launch takes, and
+    more items than resident workgroups (several items per workgroup).  Every output against the oracle, bit for bit."""
+    mixes = {
+        "256 threads": [(96, 64, 6), (64, 128, 64), (128, 64, 1), (70, 64, 10), (512, 192, 128)],
+        "512 threads": [(768, 768, 128), (3072, 768, 128), (768, 3072, 128), (96, 192, 6), (2304, 768, 128),
+                        (260, 640, 13), (640, 1024, 32)],
+        "1024 threads": [(1024, 1024, 128), (4096, 1024, 128), (1024, 4096, 128), (62, 960, 2), (96, 64, 3)],
+    }
+    for name, shapes in mixes.items():
+        jobs = []
+        for rep in range(3):
+            for i, (N, K, groups) in enumerate(shapes):
+                bits = (2, 3, 4, 8)[(i + rep) % 4]
+                gen = wl.weight_uniform if (i + rep) % 3 == 0 else wl.weight
+                jobs.append({"W": gen(N, K, seed=1000 * rep + i).to(DEV), "bits": bits, "groups": groups})
+        say("batched quantize work items,", name, len(jobs), "jobs")
+        outs = qb.qb_quantize_groupwise_batched(jobs)
+        torch.cuda.synchronize()
+        for job, out in zip(jobs, outs):
+            _check_quant_job(qb, job, out)
+    # more jobs than one launch takes, many small groups: several items per resident workgroup
+    jobs = [{"W": wl.weight(768, 768, seed=50 + i).to(DEV), "bits": (2, 3, 4, 8)[i % 4], "groups": 128} for i in range(70)]
+    say("batched quantize work items, 70 small matrices")
+    outs = qb.qb_quantize_groupwise_batched(jobs)
+    torch.cuda.synchronize()
+    for i in (0, 1, 2, 3, 47, 48, 69):
+        _check_quant_job(qb, jobs[i], outs[i])
+    # and a single small matrix (few items: one group per item)
+    job = {"W": wl.weight(768, 768, seed=7).to(DEV), "bits": 3, "groups": 128}
+    _check_quant_job(qb, job, qb.qb_quantize_groupwise_batched([job])[0])
