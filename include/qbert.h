@@ -99,7 +99,8 @@ qb_status qb_quantize_groupwise(const float *W, int64_t N, int64_t K, int bits, 
  * of qb_quantize_groupwise; the array is read during the call only.  Jobs must not overlap in
  * their outputs.  All jobs are validated before anything is launched.
  */
-#define QB_MAX_BATCH 16        /* jobs per launch; longer lists are split */
+#define QB_MAX_BATCH 16        /* jobs per launch of the activation and forward batches (the weight quantizer
+                                  takes 48); longer lists are split into several launches */
 typedef struct {
     const float *W;
     int64_t N, K;
@@ -369,12 +370,12 @@ qb_status qb_rank_by_sensitivity(const float *omega, int layers, int32_t *order)
 qb_status qb_probe_mfma_i8(int workgroups, int iters, int32_t *sink, void *stream);
 
 /* Test hook: packed buffer -> codes[N,K] uint8 in row-major order (inverse of the packing,
- * paper Sec. 4 "load 3-bit values and cast them to a wider type"). */
+ * Sec. 4: low-bit codes are loaded as stored and widened before the arithmetic). */
 qb_status qb_unpack_codes(const void *packed, int64_t N, int64_t K, int bits,
                           uint8_t *codes, void *stream);
 
 /*
- * 8-bit group-wise embedding table (Sec. 3 "embedding ... 8 bits"; App. "Mixed Precision
+ * 8-bit group-wise embedding table (Sec. 3: the embedding layer is kept at 8 bits; App. "Mixed Precision
  * Quantization for Embedding": the d output neurons of the embedding are bucketed into
  * groups).  Group g = columns [g*d/G, (g+1)*d/G) over all V rows; same quantizer, k = 8.
  *   E      in   [V,d] fp32       codes  out  [V,d] uint8 (u in 0..255)

@@ -5,8 +5,8 @@
 //   Y[t,n]   = (h_x*h_g(n)) * float(A4) (+ bias[n])
 //
 // b is the int8 the matrix core sees: the unsigned code u itself for 2/3/4 bits (e = -L) and
-// u - 128 for 8 bits (e = +1); either way A4 equals sum_j (2x'+1)(2u-L), the integer the
-// paper's "integer matmul followed by de-quantization" has to produce.
+// u - 128 for 8 bits (e = +1); either way A4 equals sum_j (2x'+1)(2u-L), the integer that the
+// integer product of the codes, de-quantized once afterwards (App., last paragraph), has to produce.
 //
 // Three kernels, chosen by shape (launch_bits):
 //   qgemm_i8_kernel     register-staged: the token tile goes global -> registers -> LDS, the packed weights never
