@@ -7,12 +7,12 @@ matrix, weight bit-widths {2,3,4,8}, forward only, synthetic seeded data.
 
 One step = one pass of the forward hot path over that batch for every bit-width of the sweep:
   16 x quantize/pack of fp32 master weights (16 distinct matrices, one batched launch), 4 x 8-bit activation
-  quantize (one batched launch), 16 x int8 MFMA GEMM with the scale epilogue (one batched call: per bit-width
-  QKV, attention-out and FFN-down share one persistent launch, FFN-up with its many tiles goes alone: 8 launches).
+  quantize (one batched launch), 16 x int8 MFMA GEMM with the scale epilogue (one batched call: per bit-width one
+  persistent launch walks the 2304 tiles of QKV, attention-out, FFN-up and FFN-down: 4 launches).
 All inputs are resident in HBM before the timed region.  `value` = int8 GEMM operations of the
 step (2*T*N*K summed) divided by the wall time of the whole step, in TOPS.
 
-The timed region replays ONE captured HIP graph per step (it holds the 10 kernels of the step and
+The timed region replays ONE captured HIP graph per step (it holds the 6 kernels of the step and
 nothing else); --no-graph launches every kernel eagerly instead.  Before the warm-up steps the step is
 replayed for at least 60 ms so that the clocks have settled whatever --warmup says.  The per-kernel
 averages in `roofline` and `kernels` come from a second pass in the same run, on the same stream: the GEMM
@@ -138,7 +138,7 @@ def main():
     stages = [stage_quantize, stage_act, stage_gemm]
     n_quant = 1                            # kernels per stage
     n_act = 4 if args.single_launches else 1
-    n_gemm = 16 if args.single_launches else len(BITS_SWEEP) + 4   # (FFN-up goes one launch per bit-width: many tiles)
+    n_gemm = 16 if args.single_launches else len(BITS_SWEEP)   # one persistent launch per bit-width walks all four linears
     stream = torch.cuda.Stream(device=dev)   # default priority
     use_graph = not args.no_graph
 
@@ -215,7 +215,7 @@ def main():
             quant_after_fill_ms = timed(fill_quant) - timed(fill_only)
         del flush, big_jobs
         for fn, nk in zip(stages[1:], (n_act, n_gemm)):
-            reps = max(1, 16 // nk) if nk <= 4 else 1
+            reps = max(1, 16 // nk) if fn is stage_act else 1   # the short activation stage is repeated inside its graph
 
             def many(fn=fn, reps=reps):
                 for _ in range(reps):
@@ -246,8 +246,8 @@ def main():
                                "step = 16 quantize/pack (16 distinct fp32 matrices, 1 launch) + 4 act-quant (1 launch) + 16 int8 GEMM+epilogue",
                    "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph,
                    "gemm_launches_per_step": n_gemm},
-        "roofline": {"kernel": "qgemm_i8_ws_kernel / qgemm_i8_dma_kernel (int8 MFMA GEMM + scale epilogue; per bit-width one "
-                               "persistent launch walks the tiles of QKV, attention-out and FFN-down, FFN-up goes alone), "
+        "roofline": {"kernel": "qgemm_i8_ws_kernel (int8 MFMA GEMM + scale epilogue; per bit-width one persistent launch "
+                               "walks the 128x96 tiles of QKV, attention-out, FFN-up and FFN-down), "
                                "%d launches per step" % n_gemm,
                      "bound": "mfma", "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
