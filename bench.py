@@ -230,6 +230,7 @@ def main():
     gemm_ops = sum(2.0 * T * N * K for (_, N, K) in linears) * len(BITS_SWEEP)
     quant_bytes = sum(N * K * (4.0 + b / 8.0) + GROUPS * 8 + N * 4 for b in BITS_SWEEP for (_, N, K) in linears)
     act_bytes = sum(T * K * 5.0 + T * 4 for (_, N, K) in linears)
+    gemm_bytes = sum(T * K + N * K * b / 8.0 + 4.0 * T * N + 4 * T + 4 * N for b in BITS_SWEEP for (_, N, K) in linears)
     gemm_tops = gemm_ops / (seg_ms[2] * 1e-3) / 1e12
     mfma_peak = measured_mfma_peak(torch, qb, dev)
     quant_gbs = quant_bytes / (seg_ms[0] * 1e-3) / 1e9
@@ -253,6 +254,13 @@ def main():
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": measured_traffic("qgemm_i8"),
                      "avg_launch_us": round(seg_ms[2] * 1e3 / n_gemm, 3),
                      "ops_per_launch": gemm_ops / n_gemm,
+                     # with fp32 outputs the step's GEMMs sit below the machine balance (625 op/B): by the roofline
+                     # model their bound is HBM; both fractions are given
+                     "hbm_side": {"bytes_per_launch": gemm_bytes / n_gemm,
+                                  "achieved_gbs": round(gemm_bytes / (seg_ms[2] * 1e-3) / 1e9, 1),
+                                  "frac_hbm_peak": round(gemm_bytes / (seg_ms[2] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                  "intensity_op_per_byte": round(gemm_ops / gemm_bytes, 1),
+                                  "machine_balance_op_per_byte": PEAK_INT8_TOPS * 1e3 / PEAK_HBM_GBS},
                      "peak_measured": round(mfma_peak, 1), "frac_of_measured": round(gemm_tops / mfma_peak, 4),
                      "peak_measured_note": "issue rate of v_mfma_i32_32x32x32_i8 alone (registers only, 2 wavefronts "
                                            "per SIMD), measured in this run at the clock the chip holds under it"},

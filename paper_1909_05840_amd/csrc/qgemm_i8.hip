@@ -1359,10 +1359,12 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
         const long tiles96 = (long)((j.T + 127) / 128) * ((j.N + 95) / 96);
         const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
         const bool few128 = tiles128 <= 640 || (j.K >= 2048 && tiles128 <= 1024);
-        // ... except that a problem with many tiles, which alone would run as two plain workgroups per CU, joins the
-        // 128x96 list when 96 divides its N: inside a shared launch it pays no start-up of its own and its tiles fill
-        // the rounds the other problems leave ragged (BERT-base FFN-up: the step's GEMM stage 212 -> 197 us)
-        const bool use96 = 86 * rounds96 < 100 * rounds128 || (!few128 && j.N % 96 == 0);
+        // ... except that a problem which alone would run as two plain workgroups per CU joins the 128x96 list when 96
+        // divides its N and it has no more than five rounds of tiles: inside a shared launch it pays no start-up of its
+        // own and its tiles fill the rounds the other problems leave ragged (BERT-base FFN-up at 4096 tokens: the
+        // step's GEMM stage 212 -> 197 us; with twelve and more rounds, at 12288 tokens or BERT-large's 32768, the two
+        // workgroups per CU stay 3-5 % ahead)
+        const bool use96 = 86 * rounds96 < 100 * rounds128 || (!few128 && j.N % 96 == 0 && tiles96 <= 1280);
         const bool use128 = !use96 && few128;
         if (j.K % 128 != 0 || tiles128 <= 160 || !(use96 || use128)) {
             launch_job<BITS>(j, st);
