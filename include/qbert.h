@@ -304,7 +304,10 @@ qb_status qb_qlinear_bwd_ste_masked(const uint16_t *dY, const int8_t *Xq, float 
  *
  * qb_qlinear_fwd_asym: Y[t,n] = h_x * (Delta_g * S[t,n] + q0_g * R[t]) (+ bias[n]) with the integer sums
  * S = sum_j (2x'+1) u[n,j] and R = sum_j (2x'+1) = 2 rs_x[t] + K, both taken from the same int8 matrix-core
- * product as qb_qlinear_fwd (S = (A4 + (2^k-1) R)/2, exact).  A4_debug as there.  Fixed activation clip only.
+ * product as qb_qlinear_fwd (S = (A4 + (2^k-1) R)/2, exact).  A4_debug as there.  Fixed activation clip.
+ *
+ * qb_qlinear_fwd_asym_dyn: the same with one activation scale per token, Y[t,n] = hx_rows[t] * (Delta_g * S[t,n] +
+ * q0_g * R[t]) (+ bias[n]); hx_rows [T] fp32 as written by qb_quantize_act_dyn or qb_quantize_act_dyn_tensor.
  *
  * qb_qlinear_bwd_ste_asym: qb_qlinear_bwd_ste with Q(w) = Delta*u + q0 in dX; dW does not involve the weights.
  * Errors as the symmetric calls.
@@ -326,6 +329,10 @@ qb_status qb_qlinear_fwd_asym(const int8_t *Xq, const int32_t *rs_x, float clip,
                               const void *packed, const float *delta, const float *q0, const int32_t *rs_w,
                               int bits, int groups, int64_t T, int64_t N, int64_t K,
                               const float *bias, float *Y, int32_t *A4_debug, void *stream);
+qb_status qb_qlinear_fwd_asym_dyn(const int8_t *Xq, const int32_t *rs_x, const float *hx_rows,
+                                  const void *packed, const float *delta, const float *q0, const int32_t *rs_w,
+                                  int bits, int groups, int64_t T, int64_t N, int64_t K,
+                                  const float *bias, float *Y, int32_t *A4_debug, void *stream);
 qb_status qb_qlinear_bwd_ste_asym(const uint16_t *dY, const int8_t *Xq, float clip,
                                   const void *packed, const float *delta, const float *q0, int bits, int groups,
                                   int64_t T, int64_t N, int64_t K,

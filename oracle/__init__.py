@@ -373,6 +373,24 @@ def qlinear_fwd_asym(xq, clip, codes, delta, q0, bias=None, want_s=False, openmp
     return (Y, S) if want_s else Y
 
 
+def qlinear_fwd_asym_dyn(xq, hx, codes, delta, q0, bias=None, openmp=False):
+    """Forward with asymmetric weights and one activation scale per token. Returns Y[T,N] f32."""
+    xq = _c(xq, np.int8)
+    hx = _c(hx, np.float32)
+    codes = _c(codes, np.uint8)
+    delta = _c(delta, np.float32)
+    q0 = _c(q0, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    T, K = xq.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == K and hx.shape == (T,)
+    Y = np.empty((T, N), np.float32)
+    _check(_lib(openmp).qbo_qlinear_fwd_asym_dyn(_ptr(xq), _ptr(hx), _ptr(codes), _ptr(delta), _ptr(q0),
+                                                 _I64(delta.shape[0]), _I64(T), _I64(N), _I64(K), _ptr(bias), _ptr(Y)),
+           "qlinear_fwd_asym_dyn")
+    return Y
+
+
 def qlinear_bwd_dx_asym(dY_bf16, codes, delta, q0, openmp=False):
     dY = _c(dY_bf16, np.uint16)
     codes = _c(codes, np.uint8)

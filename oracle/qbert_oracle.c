@@ -798,6 +798,33 @@ int qbo_qlinear_fwd_asym(const int8_t *xq, float clip, const uint8_t *codes, con
     return QBO_OK;
 }
 
+/* The same with one activation scale per token (the dynamic range of qbo_quantize_act_dyn applied to the general
+ * quantizer of the appendix): Y[t,n] = hx[t]*(Delta_g*S + q0_g*R) (+ bias[n]). */
+int qbo_qlinear_fwd_asym_dyn(const int8_t *xq, const float *hx, const uint8_t *codes, const float *delta, const float *q0,
+                             int64_t G, int64_t T, int64_t N, int64_t K, const float *bias, float *Y)
+{
+    int64_t t, rows;
+    if (!xq || !hx || !codes || !delta || !q0 || !Y) return QBO_ERR_ARG;
+    if (T <= 0 || N <= 0 || K <= 0 || G <= 0 || N % G) return QBO_ERR_ARG;
+    rows = N / G;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (t = 0; t < T; ++t) {
+        int64_t n, j, R = 0;
+        for (j = 0; j < K; ++j) R += 2 * (int)xq[t * K + j] + 1;
+        for (n = 0; n < N; ++n) {
+            int64_t S = 0;
+            double y;
+            for (j = 0; j < K; ++j) S += (int64_t)(2 * (int)xq[t * K + j] + 1) * (int64_t)codes[n * K + j];
+            y = (double)hx[t] * ((double)delta[n / rows] * (double)S + (double)q0[n / rows] * (double)R);
+            if (bias) y += (double)bias[n];
+            Y[t * N + n] = (float)y;
+        }
+    }
+    return QBO_OK;
+}
+
 /* Straight-through backward with asymmetric weights: dX = dY * Q(W), dW as in qbo_qlinear_bwd_ste (it does
  * not involve the weights). */
 int qbo_qlinear_bwd_dx_asym(const uint16_t *dY, const uint8_t *codes, const float *delta, const float *q0,

@@ -22,7 +22,7 @@ EXPORTS = ("qb_status_string", "qb_packed_nbytes", "qb_bwd_workspace_nbytes", "q
            "qb_quantize_act", "qb_quantize_act_batched", "qb_qlinear_fwd", "qb_qlinear_fwd_batched", "qb_qlinear_fwd_q8", "qb_qlinear_bwd_ste", "qb_qlinear_bwd_ste_static", "qb_unpack_codes",
            "qb_embedding_quantize", "qb_embedding_gather", "qb_embedding_quantize_bits", "qb_embedding_gather_bits",
            "qb_quantize_act_dyn", "qb_qlinear_fwd_dyn", "qb_quantize_groupwise_clip", "qb_quantize_act_dyn_tensor", "qb_qlinear_bwd_ste_masked",
-           "qb_quantize_groupwise_asym", "qb_quantize_groupwise_asym_range", "qb_qlinear_fwd_asym", "qb_qlinear_bwd_ste_asym",
+           "qb_quantize_groupwise_asym", "qb_quantize_groupwise_asym_range", "qb_qlinear_fwd_asym", "qb_qlinear_fwd_asym_dyn", "qb_qlinear_bwd_ste_asym",
            "qb_power_iteration_scratch_floats", "qb_power_iteration", "qb_sensitivity_omega", "qb_rank_by_sensitivity",
            "qb_probe_mfma_i8")
 
@@ -97,6 +97,8 @@ def load_library():
     lib.qb_quantize_groupwise_asym_range.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.qb_qlinear_fwd_asym.restype = ci
     lib.qb_qlinear_fwd_asym.argtypes = [vp, vp, cf, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
+    lib.qb_qlinear_fwd_asym_dyn.restype = ci
+    lib.qb_qlinear_fwd_asym_dyn.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_qlinear_bwd_ste_asym.restype = ci
     lib.qb_qlinear_bwd_ste_asym.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, i64, i64, i64, vp, vp, vp, vp]
     lib.qb_power_iteration_scratch_floats.restype = ctypes.c_size_t
@@ -412,6 +414,22 @@ def qb_qlinear_fwd_asym(Xq, rs_x, clip, packed, delta, q0, rs_w, bits, groups, N
     A4 = torch.empty((T, N), dtype=torch.int32, device=Xq.device) if want_a4 else None
     _check(lib.qb_qlinear_fwd_asym(_p(Xq), _p(rs_x), float(clip), _p(packed), _p(delta), _p(q0), _p(rs_w), bits, groups,
                                    T, N, K, _p(bias), _p(Y), _p(A4), _stream()))
+    return (Y, A4) if want_a4 else Y
+
+
+def qb_qlinear_fwd_asym_dyn(Xq, rs_x, hx_rows, packed, delta, q0, rs_w, bits, groups, N, bias=None, Y=None, want_a4=False):
+    """Forward with asymmetric group ranges and one activation scale per token. Returns Y (and A4 if asked)."""
+    lib = load_library()
+    _dev(Xq, torch.int8, "Xq")
+    _dev(hx_rows, torch.float32, "hx_rows")
+    _dev(delta, torch.float32, "delta")
+    _dev(q0, torch.float32, "q0")
+    T, K = Xq.shape
+    if Y is None:
+        Y = torch.empty((T, N), dtype=torch.float32, device=Xq.device)
+    A4 = torch.empty((T, N), dtype=torch.int32, device=Xq.device) if want_a4 else None
+    _check(lib.qb_qlinear_fwd_asym_dyn(_p(Xq), _p(rs_x), _p(hx_rows), _p(packed), _p(delta), _p(q0), _p(rs_w), bits, groups,
+                                       T, N, K, _p(bias), _p(Y), _p(A4), _stream()))
     return (Y, A4) if want_a4 else Y
 
 

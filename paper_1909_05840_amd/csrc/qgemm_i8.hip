@@ -211,7 +211,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
                     if (t < T && n_ok) {
                         const int a4 = qb_a4(acc[tm][tn][i], E2 * rs_x[t] + coln);
                         const size_t at = (size_t)t * N + n;
-                        Y[at] = asym_value(a4, rs_x[t] + (K >> 1), L, hx, hg, zn) + bv;
+                        Y[at] = asym_value(a4, rs_x[t] + (K >> 1), L, hx_rows ? hx_rows[t] : hx, hg, zn) + bv;
                         if (A4out) A4out[at] = a4;
                     }
                 }
@@ -570,8 +570,8 @@ __device__ __forceinline__ void copy4_to_lds(const void *g, uint32_t lds_addr)
 
 // Epilogue of the role-split kernel.  Its per-token and per-neuron parameters do not come from global
 // memory but from a block in LDS that a producer wavefront filled for the tile (BM ints rs_x, then BN
-// each of rs_w, h of the neuron's group, bias, and last either BM per-token scales or BN values of q0 of the
-// neuron's group; indices past the end of the matrix were clamped).  The
+// each of rs_w, h of the neuron's group, bias, then BM per-token scales and, with asymmetric ranges, BN values of q0 of
+// the neuron's group; indices past the end of the matrix were clamped).  The
 // consumer wavefronts thus issue no global loads at all: their memory counter holds stores only and is
 // never waited on, so the stores of one tile need not have completed before the next tile's go out.
 // acc[tm][tn][r]: token tl + 32*tm + 8*(r/4) + (r%4) of the tile (tl contains 4*hf), neuron nl + 32*tn
@@ -617,8 +617,20 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
         rx[4 * q + 2] = qb_mad24(e2, v.z, coln);
         rx[4 * q + 3] = qb_mad24(e2, v.w, coln);
     }
-    if (asym_L) {  // asymmetric group ranges: Delta in the place of h, q0 in the place of the per-token scales
-        const float dn = p_h[nl], zn = (p_b + BN)[nl];
+    if (asym_L) {  // asymmetric group ranges: Delta in the place of h, q0 behind the per-token scales
+        const float dn = p_h[nl], zn = (p_b + BN + BM)[nl];
+        float hr[16];  // the activation scale of every row: the call's, or the token's own
+        if (dyn) {
+            const float *p_hx = p_b + BN;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4 *>(p_hx + tl + 8 * q);
+                hr[4 * q + 0] = v.x; hr[4 * q + 1] = v.y; hr[4 * q + 2] = v.z; hr[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hr[r] = hx;
+        }
         int rh[16];  // R/2 = rs_x + K/2 per row
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -633,7 +645,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int a4 = qb_a4(acc[r], rx[r]);
-                __builtin_nontemporal_store(asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv,
+                __builtin_nontemporal_store(asym_value(a4, rh[r], asym_L, hr[r], dn, zn) + bv,
                                             reinterpret_cast<float *>(y_blk + (size_t)(8 * (r >> 2) + (r & 3)) * N * 4));
             }
         } else if (n0 + nl < N) {
@@ -643,7 +655,7 @@ __device__ __forceinline__ void store_block_lds(const v16i &acc, const uint8_t *
                 if (t < T) {
                     const int a4 = qb_a4(acc[r], rx[r]);
                     const size_t at = (size_t)t * N + n0 + nl;
-                    Y[at] = asym_value(a4, rh[r], asym_L, hx, dn, zn) + bv;
+                    Y[at] = asym_value(a4, rh[r], asym_L, hr[r], dn, zn) + bv;
                     if (A4out) A4out[at] = a4;
                 }
             }
@@ -679,8 +691,7 @@ struct OutQ {
     float clip_out;   // range [-clip_out, +clip_out]
     int act;          // 0 none, 1 GELU
     const float *hx_rows;  // fp32 output only: one activation scale per token (dynamic range) instead of hx, or null
-    const float *q0;       // fp32 output only: asymmetric group ranges (h holds Delta, q0 the lower ends), or null;
-                           // not together with hx_rows (its values take the same place in the parameter block)
+    const float *q0;       // fp32 output only: asymmetric group ranges (h holds Delta, q0 the lower ends), or null
 };
 
 // One linear layer of a launch of the role-split kernel, and the list of them that one launch walks through.
@@ -815,9 +826,8 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(con
     constexpr int A_BYTES = BM * BK, B_BYTES = (BN / 32) * LPAIR, STAGE_BYTES = A_BYTES + B_BYTES;
     static_assert((D - 1) * PERP + 2 * (BM / 64) + 4 * ((BN + 63) / 64) < 64, "vmcnt has six bits");
     constexpr int BNP = (BN + 63) / 64 * 64;        // per-neuron parameter arrays are filled 64 entries at a time
-    constexpr int PARAM_BYTES = (2 * BM + 3 * BNP) * 4;  // rs_x | rs_w | h of the neuron's group | bias | per-token scales
-                                                         // (or, in their place, q0 of the neuron's group)
-    static_assert(OUT != 2 || BNP <= BM, "the per-neuron q0 values take the place of the per-token scales");
+    // rs_x | rs_w | h of the neuron's group | bias | per-token scales | q0 of the neuron's group (asymmetric ranges)
+    constexpr int PARAM_BYTES = (2 * BM + (OUT == 2 ? 4 : 3) * BNP) * 4;
     static_assert(!SIMD3 || (NC == 6 && NPROD == 2), "SIMD3: six MFMA wavefronts on SIMDs 0..2, two copy wavefronts on SIMD 3");
 
     // A tile's parameter block is read in its write-out, which ends before the consumers pass the first
@@ -917,7 +927,7 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(con
                     copy4_to_lds(rs_w + n, pbase + BM * 4 + c * 256);
                     copy4_to_lds(h + n / rows_per_group, pbase + (BM + BNP) * 4 + c * 256);
                     if (bias) copy4_to_lds(bias + n, pbase + (BM + 2 * BNP) * 4 + c * 256);
-                    if constexpr (ASYM) copy4_to_lds(oq.q0 + n / rows_per_group, pbase + (BM + 3 * BNP) * 4 + c * 256);
+                    if constexpr (ASYM) copy4_to_lds(oq.q0 + n / rows_per_group, pbase + (2 * BM + 3 * BNP) * 4 + c * 256);
                 }
             }
             pb ^= 1;
@@ -1190,7 +1200,6 @@ void launch_ws(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, con
                int grid_cap, const float *hx_rows = nullptr, const float *q0 = nullptr)
 {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    static_assert((BN + 63) / 64 * 64 <= BM, "the asymmetric variant needs room for q0 in the parameter block");
     const OutQ oq{nullptr, nullptr, 1.0f, 0, hx_rows, q0};
     Group g;
     g.n = 0;
@@ -1473,6 +1482,27 @@ extern "C" qb_status qb_qlinear_fwd_asym(const int8_t *Xq, const int32_t *rs_x, 
         case 3: launch_bits<3>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
         case 4: launch_bits<4>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
         default: launch_bits<8>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, hx, st, nullptr, q0); break;
+    }
+    return launch_status();
+}
+
+extern "C" qb_status qb_qlinear_fwd_asym_dyn(const int8_t *Xq, const int32_t *rs_x, const float *hx_rows, const void *packed,
+                                             const float *delta, const float *q0, const int32_t *rs_w, int bits, int groups,
+                                             int64_t T, int64_t N, int64_t K, const float *bias, float *Y,
+                                             int32_t *A4_debug, void *stream)
+{
+    if (!Xq || !rs_x || !hx_rows || !packed || !delta || !q0 || !rs_w || !Y) return QB_ERR_NULL;
+    if (!bits_ok(bits)) return QB_ERR_BITS;
+    if (T <= 0 || T > (1 << 24) || N <= 0 || N > (1 << 24) || !k_ok(K) || groups <= 0 || N % groups != 0)
+        return QB_ERR_SHAPE;
+    const int rpg = (int)(N / groups);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *p = static_cast<const uint8_t *>(packed);
+    switch (bits) {
+        case 2: launch_bits<2>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows, q0); break;
+        case 3: launch_bits<3>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows, q0); break;
+        case 4: launch_bits<4>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows, q0); break;
+        default: launch_bits<8>(Xq, rs_x, p, delta, rs_w, bias, Y, A4_debug, (int)T, (int)N, (int)K, rpg, 0.0f, st, hx_rows, q0); break;
     }
     return launch_status();
 }

@@ -375,3 +375,60 @@ def test_quantize_batched_work_items(qb):
     # and a single small matrix (few items: one group per item)
     job = {"W": wl.weight(768, 768, seed=7).to(DEV), "bits": 3, "groups": 128}
     _check_quant_job(qb, job, qb.qb_quantize_groupwise_batched([job])[0])
+
+
+def _shifted_weight(N, K, G, seed):
+    """Weights whose groups sit at different offsets (what asymmetric ranges are for)."""
+    W = wl.weight(N, K, seed=seed)
+    rows = N // G
+    off = torch.linspace(-0.05, 0.08, G).repeat_interleave(rows)[:, None]
+    return (W + off).contiguous()
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
+@pytest.mark.parametrize("shape", [(300, 160, 192, 8), (1, 32, 64, 1), (129, 130, 320, 10), (513, 768, 768, 128),
+                                   (2048, 1024, 128, 128), (2304, 1536, 128, 128), (4096, 768, 256, 128)])
+def test_forward_asymmetric_ranges_with_per_token_scales(qb, bits, shape):
+    """qb_qlinear_fwd_asym_dyn: asymmetric group ranges and one activation scale per token, through the register-staged
+    kernel and both role-split layouts, ragged T and N, with and without bias; rows of very different magnitude and an
+    all-zero row.  Y against the oracle within 1e-6 of h_x[t]*(Delta*|S| + |q0|*|R|), A4 bit for bit; a constant scale
+    vector gives the fixed-clip call's bits."""
+    T, N, K, G = shape
+    say("fwd asym x per-token", shape, "bits", bits)
+    W = _shifted_weight(N, K, G, seed=5 * N + K + bits)
+    g = torch.Generator(device="cpu").manual_seed(T + 7 * K + bits)
+    X = (wl.activation(T, K, seed=T + K + bits) * (0.05 + 4.0 * torch.rand(T, 1, generator=g))).contiguous()
+    if T > 4:
+        X[3] = 0.0
+    bias = (0.3 * wl.activation(1, N, seed=13)[0]).contiguous()
+    packed, delta, q0, rs_w = qb.qb_quantize_groupwise_asym(W.to(DEV), bits, G)
+    Xq, rs_x, hx = qb.qb_quantize_act_dyn(X.to(DEV))
+    oc, od, oq0, _ = oracle.quantize_groupwise_asym(W.numpy(), bits, G)
+    oq, ors_x, ohx = oracle.quantize_act_dyn(X.numpy())
+    assert (Xq.cpu().numpy() == oq).all() and (hx.cpu().numpy().view(np.uint32) == ohx.view(np.uint32)).all()
+    L = 2 ** bits - 1
+    xi = 2 * oq.astype(np.int64) + 1
+    S = xi @ oc.astype(np.int64).T
+    R = xi.sum(axis=1)[:, None]
+    rows = N // G
+    dn = np.repeat(od.astype(np.float64), rows)[None, :]
+    zn = np.repeat(oq0.astype(np.float64), rows)[None, :]
+    bound = 1e-6 * ohx.astype(np.float64)[:, None] * (dn * np.abs(S) + np.abs(zn) * np.abs(R))
+    for b in (None, bias):
+        Y, A4 = qb.qb_qlinear_fwd_asym_dyn(Xq, rs_x, hx, packed, delta, q0, rs_w, bits, G, N,
+                                           bias=None if b is None else b.to(DEV), want_a4=True)
+        torch.cuda.synchronize()
+        assert (A4.cpu().numpy().astype(np.int64) == 2 * S - L * R).all()
+        ref = oracle.qlinear_fwd_asym_dyn(oq, ohx, oc, od, oq0, bias=None if b is None else b.numpy(), openmp=True)
+        extra = 0 if b is None else 1e-6 * np.abs(b.numpy())[None, :]
+        assert (np.abs(Y.cpu().numpy().astype(np.float64) - ref) <= bound + extra + 1e-30).all()
+        Y2 = qb.qb_qlinear_fwd_asym_dyn(Xq, rs_x, hx, packed, delta, q0, rs_w, bits, G, N, bias=None if b is None else b.to(DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, Y)   # the timed path (no A4 output) gives the same bits
+    # constant scales: the fixed-clip call, bit for bit
+    Xs, rs_s = qb.qb_quantize_act(X.to(DEV), CLIP)
+    const = torch.from_numpy(np.full(T, np.float32(CLIP) / np.float32(255.0), np.float32)).to(DEV)   # fl(clip/255), as the call forms it
+    Ya = qb.qb_qlinear_fwd_asym_dyn(Xs, rs_s, const, packed, delta, q0, rs_w, bits, G, N, bias=bias.to(DEV))
+    Yb = qb.qb_qlinear_fwd_asym(Xs, rs_s, CLIP, packed, delta, q0, rs_w, bits, G, N, bias=bias.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(Ya, Yb)

@@ -821,3 +821,41 @@ def test_given_asymmetric_range_pins(bits):
     assert (np.diff(cc[0][order].astype(int)) >= 0).all()
     cn, _, _, _ = oracle.quantize_groupwise_asym_range(W2[:1], bits, lo2[:1] / 2, hi2[:1] / 2)
     assert ((cn == 0) | (cn == L)).sum() >= ((cc == 0) | (cc == L)).sum()
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_asymmetric_forward_with_per_token_scales(bits):
+    """Asymmetric weights x per-token activation range: against the numpy fp64 product of the de-quantized operands
+    (each row de-quantized with its own scale); a constant scale vector reproduces the fixed-clip asymmetric forward
+    bit for bit; a row whose scale is doubled doubles exactly; an all-zero row (scale 0) gives exactly the bias."""
+    T, N, K, G = 9, 12, 64, 4
+    r = rng(140 + bits)
+    W = (r.uniform(-0.02, 0.09, (N, K))).astype(np.float32)
+    X = (r.standard_normal((T, K)) * r.uniform(0.1, 4.0, (T, 1))).astype(np.float32)
+    X[4] = 0.0
+    bias = r.standard_normal(N).astype(np.float32)
+    codes, delta, q0, _ = oracle.quantize_groupwise_asym(W, bits, G)
+    xq, rs_x, hx = oracle.quantize_act_dyn(X)
+    What = oracle.dequantize_groupwise_asym(codes, delta, q0)
+    Xhat = hx.astype(np.float64)[:, None] * (2.0 * xq.astype(np.float64) + 1.0)
+    Y = oracle.qlinear_fwd_asym_dyn(xq, hx, codes, delta, q0)
+    ref = Xhat @ What.T
+    # the two terms Delta*S and q0*R may cancel: the bound is relative to their magnitudes
+    R = (2 * xq.astype(np.int64) + 1).sum(axis=1)
+    S = (2 * xq.astype(np.int64) + 1) @ codes.astype(np.int64).T
+    rows = N // G
+    mag = np.abs(hx.astype(np.float64))[:, None] * (np.abs(np.repeat(delta, rows).astype(np.float64))[None, :] * np.abs(S)
+                                                     + np.abs(np.repeat(q0, rows).astype(np.float64))[None, :] * np.abs(R)[:, None])
+    assert (np.abs(Y - ref) <= 1e-6 * mag + 1e-30).all()
+    Yb = oracle.qlinear_fwd_asym_dyn(xq, hx, codes, delta, q0, bias=bias)
+    assert (Yb[4] == bias).all() and (Y[4] == 0).all()
+    # constant scales = the fixed clip
+    xs, _ = oracle.quantize_act(X, 6.0)
+    const = np.full(T, np.float32(6.0) / np.float32(255.0), np.float32)
+    assert (oracle.qlinear_fwd_asym_dyn(xs, const, codes, delta, q0, bias=bias).view(np.uint32)
+            == oracle.qlinear_fwd_asym(xs, 6.0, codes, delta, q0, bias=bias).view(np.uint32)).all()
+    # a power of two on one row's scale
+    hx2 = hx.copy()
+    hx2[2] *= np.float32(2.0)
+    Y2 = oracle.qlinear_fwd_asym_dyn(xq, hx2, codes, delta, q0)
+    assert (Y2[2] == 2.0 * Y[2]).all() and (np.delete(Y2, 2, 0) == np.delete(Y, 2, 0)).all()
