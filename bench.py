@@ -354,7 +354,8 @@ def per_shape(torch, qb, wl, dev):
     res = []
     cases = [(T_TOKENS, N, K, 4) for (_, N, K) in wl.BERT_BASE_LINEARS] + [(T_TOKENS, 768, 3072, b) for b in (2, 3, 8)]
     cases += [(32768, 1024, 4096, 2), (32768, 4096, 1024, 3)]
-    cases += [(1024, 768, 768, 4), (128, 768, 3072, 4)]  # configs[0]; a 128-token inference batch (launch-bound)
+    # configs[0]; few-token inference batches (launch-bound: a batched call runs its four problems in one launch)
+    cases += [(1024, 768, 768, 4), (128, 768, 3072, 4), (128, 2304, 768, 4), (16, 3072, 768, 2)]
     for (T, N, K, b) in cases:
         nprob = 4 if T <= 4096 else 1
         jobs = []

@@ -48,12 +48,13 @@ __device__ __forceinline__ float asym_value(int a4, int rh, int L, float hx, flo
     return hx * (delta * (float)S + q0 * (float)(2 * rh));
 }
 
+// bid: the workgroup's number among the tiles_m * tiles_n workgroups of this problem
 template <int BITS, int TM, int TN, int WM, int WN, int KU>
-__global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
+__device__ __forceinline__ void qgemm_i8_body(
     const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
     const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
     float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
-    int tiles_m, int tiles_n, const float *__restrict__ hx_rows, const float *__restrict__ q0)
+    int tiles_m, int tiles_n, const float *__restrict__ hx_rows, const float *__restrict__ q0, const int bid)
 {
     // hx_rows: one activation scale per token (dynamic range) instead of hx, or null
     // q0: asymmetric group ranges: h holds Delta and q0 the lower end of every group, or null
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
     const int nwg = tiles_m * tiles_n;
     int logical;
     {
-        const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
+        const int xcd = bid & 7, idx = bid >> 3;
         const int q = nwg >> 3, r = nwg & 7;
         logical = xcd * q + (xcd < r ? xcd : r) + idx;
     }
@@ -252,6 +253,49 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
             }
         }
     }
+}
+
+template <int BITS, int TM, int TN, int WM, int WN, int KU>
+__global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_kernel(
+    const int8_t *__restrict__ Xq, const int32_t *__restrict__ rs_x, const uint8_t *__restrict__ packed,
+    const float *__restrict__ h, const int32_t *__restrict__ rs_w, const float *__restrict__ bias,
+    float *__restrict__ Y, int32_t *__restrict__ A4out, int T, int N, int K, int rows_per_group, float hx,
+    int tiles_m, int tiles_n, const float *__restrict__ hx_rows, const float *__restrict__ q0)
+{
+    qgemm_i8_body<BITS, TM, TN, WM, WN, KU>(Xq, rs_x, packed, h, rs_w, bias, Y, A4out, T, N, K, rows_per_group, hx, tiles_m,
+                                            tiles_n, hx_rows, q0, blockIdx.x);
+}
+
+// Several few-tile problems (small token counts: the inference regime, where a launch costs more than its work) in one
+// launch of the 32x64-tile form: workgroup w serves tile w - first_wg[j] of problem j; a problem's workgroups start at
+// a multiple of 8, so that its tiles keep their XCD (the fill-up workgroups leave at once).
+struct SmallProblem {
+    const int8_t *Xq;
+    const int32_t *rs_x;
+    const uint8_t *packed;
+    const float *h;
+    const int32_t *rs_w;
+    const float *bias;
+    float *Y;
+    int T, N, K, rows_per_group;
+    float hx;
+    int tiles_m, tiles_n;
+};
+struct SmallGroup {
+    int n;
+    int first_wg[QB_MAX_BATCH + 1];
+    SmallProblem p[QB_MAX_BATCH];
+};
+template <int BITS, int KU>
+__global__ __launch_bounds__(128) void qgemm_i8_small_group_kernel(const SmallGroup g)
+{
+    int j = 0;
+    while (j + 1 < g.n && (int)blockIdx.x >= g.first_wg[j + 1]) ++j;
+    const SmallProblem &p = g.p[j];
+    const int local = blockIdx.x - g.first_wg[j];
+    if (local >= p.tiles_m * p.tiles_n) return;  // (uniform over the workgroup)
+    qgemm_i8_body<BITS, 1, 1, 1, 2, KU>(p.Xq, p.rs_x, p.packed, p.h, p.rs_w, p.bias, p.Y, nullptr, p.T, p.N, p.K,
+                                        p.rows_per_group, p.hx, p.tiles_m, p.tiles_n, nullptr, nullptr, local);
 }
 
 // global -> LDS copy by the load unit: the global address of a lane is a wavefront-uniform base (in SGPRs) plus
@@ -1358,6 +1402,17 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
 {
     Group g96, g128;
     g96.n = g128.n = 0;
+    SmallGroup small[3];  // few-tile problems, by features per step (64, 128, 256)
+    small[0].n = small[1].n = small[2].n = 0;
+    auto flush_small = [&](int c) {
+        SmallGroup &sg = small[c];
+        if (sg.n == 0) return;
+        const dim3 grid(sg.first_wg[sg.n]);
+        if (c == 0) hipLaunchKernelGGL((qgemm_i8_small_group_kernel<BITS, 1>), grid, dim3(128), 0, st, sg);
+        else if (c == 1) hipLaunchKernelGGL((qgemm_i8_small_group_kernel<BITS, 2>), grid, dim3(128), 0, st, sg);
+        else hipLaunchKernelGGL((qgemm_i8_small_group_kernel<BITS, 4>), grid, dim3(128), 0, st, sg);
+        sg.n = 0;
+    };
     const OutQ none{nullptr, nullptr, 1.0f, 0, nullptr, nullptr};
     for (int i = 0; i < n_jobs; ++i) {
         const qb_fwd_job &j = jobs[i];
@@ -1375,7 +1430,21 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
         // workgroups per CU stay 3-5 % ahead)
         const bool use96 = 86 * rounds96 < 100 * rounds128 || (!few128 && j.N % 96 == 0 && tiles96 <= 1280);
         const bool use128 = !use96 && few128;
-        if (j.K % 128 != 0 || tiles128 <= 160 || !(use96 || use128)) {
+        if (tiles128 <= 160) {  // few tiles: the 32x64-tile form, the step width of the single call, one launch per width
+            const int c = (j.K % 256 == 0 && j.K >= 2048) ? 2 : (j.K % 128 == 0) ? 1 : 0;
+            SmallGroup &sg = small[c];
+            if (sg.n == QB_MAX_BATCH) flush_small(c);
+            if (sg.n == 0) sg.first_wg[0] = 0;
+            SmallProblem &sp = sg.p[sg.n];
+            sp.Xq = j.Xq; sp.rs_x = j.rs_x; sp.packed = static_cast<const uint8_t *>(j.packed); sp.h = j.h; sp.rs_w = j.rs_w;
+            sp.bias = j.bias; sp.Y = j.Y; sp.T = (int)j.T; sp.N = (int)j.N; sp.K = (int)j.K;
+            sp.rows_per_group = (int)(j.N / j.groups); sp.hx = j.clip / 255.0f;
+            sp.tiles_m = (int)((j.T + 31) / 32); sp.tiles_n = (int)((j.N + 63) / 64);
+            sg.first_wg[sg.n + 1] = sg.first_wg[sg.n] + ((sp.tiles_m * sp.tiles_n + 7) & ~7);
+            ++sg.n;
+            continue;
+        }
+        if (j.K % 128 != 0 || !(use96 || use128)) {
             launch_job<BITS>(j, st);
             continue;
         }
@@ -1398,6 +1467,7 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
     }
     if (g96.n) launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
     if (g128.n) launch_group<BITS, 2, 2, 2, 2, 3, 4, false, 0>(g128, st, 256);
+    for (int c = 0; c < 3; ++c) flush_small(c);
 }
 }  // namespace
 

@@ -432,3 +432,39 @@ def test_forward_asymmetric_ranges_with_per_token_scales(qb, bits, shape):
     Yb = qb.qb_qlinear_fwd_asym(Xs, rs_s, CLIP, packed, delta, q0, rs_w, bits, G, N, bias=bias.to(DEV))
     torch.cuda.synchronize()
     assert torch.equal(Ya, Yb)
+
+
+def test_forward_batched_few_token_jobs_share_launches(qb):
+    """The inference regime: few-token problems of a batched call go through shared launches of the 32x64-tile kernel
+    (one per bit-width and step width).  More jobs of one kind than a launch takes, all three step widths (K = 192,
+    768, 3072), ragged T and N, with and without bias: every Y element by element against the oracle, pre-filled
+    outputs fully written."""
+    jobs, refs = [], []
+    shapes = [(1, 768, 768), (8, 2304, 768), (64, 3072, 768), (128, 768, 3072), (33, 130, 192), (100, 96, 3072), (5, 64, 64)]
+    case = 0
+    for bits in BITS:
+        for rep in range(3 if bits == 4 else 1):        # 21 jobs at 4 bits: more than one launch holds
+            for (T, N, K) in shapes:
+                groups = G if N % G == 0 else (N // 2 if N % 2 == 0 else 1)
+                d = quantized_inputs(qb, N, K, T, bits, seed=31 * N + K + T + bits + 7 * rep, groups=groups)
+                bias = wl.activation(1, N, seed=case)[0].contiguous() if case % 2 == 0 else None
+                jobs.append(dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=bits,
+                                 groups=groups, N=N, bias=None if bias is None else bias.to(DEV),
+                                 Y=torch.full((T, N), float("nan"), dtype=torch.float32, device=DEV)))
+                refs.append((d, bits, bias))
+                case += 1
+    say("fwd batched, few-token jobs:", len(jobs))
+    Ys = qb.qb_qlinear_fwd_batched(jobs)
+    torch.cuda.synchronize()
+    for j, Yb, (d, bits, bias) in zip(jobs, Ys, refs):
+        Yo, _, _ = oracle.qlinear_fwd(d["oq"], CLIP, d["oc"], d["oh"], bits)
+        Yh = Yb.cpu().numpy().astype(np.float64)
+        assert np.isfinite(Yh).all()
+        if bias is not None:
+            b = bias.numpy().astype(np.float64)[None, :]
+            assert (np.abs(Yh - (Yo + b)) <= 1e-6 * np.abs(Yo) + 2.0 ** -23 * np.abs(Yo + b)).all()
+        else:
+            assert_rel(Yh, Yo)
+        Y1 = qb.qb_qlinear_fwd(j["Xq"], j["rs_x"], CLIP, j["packed"], j["h"], j["rs_w"], bits, j["groups"], j["N"], bias=j["bias"])
+        torch.cuda.synchronize()
+        assert torch.equal(Yb, Y1)
