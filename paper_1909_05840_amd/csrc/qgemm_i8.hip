@@ -851,7 +851,7 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
 // OUT: 0 fp32 Y, 1 the 8-bit output (OUTQ), 2 fp32 Y from asymmetric group ranges (ASYM; a variant of its own so
 // that the others carry none of its code)
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, int OUT>
-__global__ __launch_bounds__(64 * (WM * WN + NPROD)) void qgemm_i8_ws_kernel(const Group g)
+__global__ __launch_bounds__(64 * (WM * WN + NPROD), (SIMD3 && OUT == 0 && NSTAGE == 2) ? 4 : 2) void qgemm_i8_ws_kernel(const Group g)
 {
     constexpr bool OUTQ = OUT == 1, ASYM = OUT == 2;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
@@ -1323,7 +1323,13 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
     if (86 * rounds96 < 100 * rounds128)
-        launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows, q0);
+    {
+        // more tiles than CUs: two workgroups per CU, one's write-out under the other's K-loop (LDS and registers allow it
+        // at 2, 3 and 4 bits; at 8 bits with two stages, for the plain fp32 output)
+        if (tiles96 > 256 && BITS < 8) launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512, hx_rows, q0);
+        else if (tiles96 > 256 && !q0) launch_ws<BITS, 2, 1, 2, 3, 2, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 512, hx_rows, q0);
+        else launch_ws<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows, q0);
+    }
     else if (hx_rows || q0 || tiles128 <= 640 || (K >= 2048 && tiles128 <= 1024))  // (per-token scales, asymmetric ranges: role-split kernels only)
         launch_ws<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, Y, A4, T, N, K, rpg, hx, st, 256, hx_rows, q0);
     else
@@ -1395,6 +1401,16 @@ void launch_job(const qb_fwd_job &j, hipStream_t st)
                       (int)j.K, (int)(j.N / j.groups), j.clip / 255.0f, st);
 }
 
+// A shared launch of 128x96 tiles.  Two workgroups per CU (512 resident): while one writes a tile out and starts the
+// next, the other's K-loop keeps the matrix cores busy (the step's GEMM stage 196 -> 171 us).  That needs at most
+// 80 KB of LDS and 128 registers: three stages at 2, 3 and 4 bits (64-73 KB, 102 registers), two stages at 8 bits.
+template <int BITS>
+void launch_g96(const Group &g, hipStream_t st)
+{
+    if constexpr (BITS == 8) launch_group<8, 2, 1, 2, 3, 2, 2, true, 0>(g, st, 512);
+    else launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g, st, 512);
+}
+
 // the jobs of one bit-width: those that the single call would give to a role-split kernel share launches of it
 // (one list per tile shape), the others go one by one
 template <int BITS>
@@ -1453,7 +1469,7 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
         const float hx = j.clip / 255.0f;
         if (use96) {
             if (g96.n == kMaxGroup) {
-                launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
+                launch_g96<BITS>(g96, st);
                 g96.n = 0;
             }
             group_add<128, 96>(g96, j.Xq, j.rs_x, p, j.h, j.rs_w, j.bias, j.Y, nullptr, (int)j.T, (int)j.N, (int)j.K, rpg, hx, none);
@@ -1465,7 +1481,7 @@ void launch_jobs_of_width(const qb_fwd_job *jobs, int n_jobs, hipStream_t st)
             group_add<128, 128>(g128, j.Xq, j.rs_x, p, j.h, j.rs_w, j.bias, j.Y, nullptr, (int)j.T, (int)j.N, (int)j.K, rpg, hx, none);
         }
     }
-    if (g96.n) launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g96, st, 256);
+    if (g96.n) launch_g96<BITS>(g96, st);
     if (g128.n) launch_group<BITS, 2, 2, 2, 2, 3, 4, false, 0>(g128, st, 256);
     for (int c = 0; c < 3; ++c) flush_small(c);
 }
