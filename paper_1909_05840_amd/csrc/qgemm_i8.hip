@@ -851,7 +851,7 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
 // OUT: 0 fp32 Y, 1 the 8-bit output (OUTQ), 2 fp32 Y from asymmetric group ranges (ASYM; a variant of its own so
 // that the others carry none of its code)
 template <int BITS, int TM, int TN, int WM, int WN, int NSTAGE, int NPROD, bool SIMD3, int OUT>
-__global__ __launch_bounds__(64 * (WM * WN + NPROD), (SIMD3 && OUT == 0 && NSTAGE == 2) ? 4 : 2) void qgemm_i8_ws_kernel(const Group g)
+__global__ __launch_bounds__(64 * (WM * WN + NPROD), (SIMD3 && OUT != 2 && NSTAGE == 2) ? 4 : 2) void qgemm_i8_ws_kernel(const Group g)
 {
     constexpr bool OUTQ = OUT == 1, ASYM = OUT == 2;
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2..4 stages");
@@ -1344,9 +1344,12 @@ void launch_bits_q8(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed
     const long tiles128 = (long)((T + 127) / 128) * ((N + 127) / 128);
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
-    if (86 * rounds96 < 100 * rounds128)
-        launch_ws_q8<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 256);
-    else
+    if (86 * rounds96 < 100 * rounds128 || (N % 96 == 0 && tiles96 > 256)) {
+        // more tiles than CUs: two stages, so that two workgroups fit a CU and one's output quantizer runs under the
+        // other's K-loop (then also where 128x128 tiles would need fewer rounds)
+        if (tiles96 > 256) launch_ws_q8<BITS, 2, 1, 2, 3, 2, 2, true>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 512);
+        else launch_ws_q8<BITS, 2, 1, 2, 3, 3, 2, true>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 256);
+    } else
         launch_ws_q8<BITS, 2, 2, 2, 2, 3, 4>(Xq, rs_x, packed, h, rs_w, bias, oq, T, N, K, rpg, hx, st, 256);
 }
 
