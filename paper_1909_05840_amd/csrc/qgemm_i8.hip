@@ -1322,7 +1322,9 @@ void launch_bits(const int8_t *Xq, const int32_t *rs_x, const uint8_t *packed, c
     // Grids are persistent and a multiple of 8, so that a workgroup stays inside its XCD's tile range.
     const long tiles96 = (long)((T + 127) / 128) * ((N + 95) / 96);
     const long rounds128 = (tiles128 + 255) / 256, rounds96 = (tiles96 + 255) / 256;
-    if (86 * rounds96 < 100 * rounds128)
+    // (also where 128x128 tiles would need fewer rounds, for up to five rounds of 128x96 tiles: as two workgroups per CU
+    // they are 3 % ahead of the plain two-workgroup kernel on BERT-base's FFN-up)
+    if (86 * rounds96 < 100 * rounds128 || (N % 96 == 0 && tiles96 > 256 && tiles96 <= 1280))
     {
         // more tiles than CUs: two workgroups per CU, one's write-out under the other's K-loop (LDS and registers allow it
         // at 2, 3 and 4 bits; at 8 bits with two stages, for the plain fp32 output)
