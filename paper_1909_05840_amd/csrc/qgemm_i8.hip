@@ -1412,8 +1412,8 @@ void launch_job(const qb_fwd_job &j, hipStream_t st)
 template <int BITS>
 void launch_g96(const Group &g, hipStream_t st)
 {
-    if constexpr (BITS == 8) launch_group<8, 2, 1, 2, 3, 2, 2, true, 0>(g, st, 512);
-    else launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g, st, 512);
+    if (BITS == 8 && g.tile_start[g.n] > 256) launch_group<BITS, 2, 1, 2, 3, 2, 2, true, 0>(g, st, 512);
+    else launch_group<BITS, 2, 1, 2, 3, 3, 2, true, 0>(g, st, 512);  // (no more than one workgroup per CU at 8 bits)
 }
 
 // the jobs of one bit-width: those that the single call would give to a role-split kernel share launches of it
