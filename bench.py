@@ -12,8 +12,9 @@ One step = one pass of the forward hot path over that batch for every bit-width 
 All inputs are resident in HBM before the timed region.  `value` = int8 GEMM operations of the
 step (2*T*N*K summed) divided by the wall time of the whole step, in TOPS.
 
-The timed region replays ONE captured HIP graph per step (it holds the 6 kernels of the step and
-nothing else); --no-graph launches every kernel eagerly instead.  Before the warm-up steps the step is
+The timed region replays captured HIP graphs that hold nothing but the 6 kernels of a step, five whole steps per
+graph (--steps-per-graph; consecutive replays of a one-step graph leave the GPU idle for about 8 us in between);
+--no-graph launches every kernel eagerly instead.  Before the warm-up steps the step is
 replayed for at least 60 ms so that the clocks have settled whatever --warmup says.  The per-kernel
 averages in `roofline` and `kernels` come from a second pass in the same run, on the same stream: the GEMM
 launches (and the 4 activation quantizers, four times over) as one graph, replayed ten times between two
@@ -51,6 +52,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-graph", action="store_true", help="launch kernels eagerly instead of replaying HIP graphs")
+    ap.add_argument("--steps-per-graph", type=int, default=5,
+                    help="whole steps captured back to back in one HIP graph (1: one graph replay per step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-launches", action="store_true",
                     help="one launch per GEMM (16 qb_qlinear_fwd calls) instead of the batched call")
@@ -156,19 +159,34 @@ def main():
         whole_step()
         stream.synchronize()
         one_step = capture(whole_step) if use_graph else whole_step
+        # Consecutive replays of a one-step graph leave the GPU idle for about 8 us between them (the host's graph launch,
+        # seen in the kernel trace as the only gap of a step).  A training loop captures more than one layer's step at a
+        # time; here a second graph holds GRAPH_STEPS whole steps back to back, and K steps are K // GRAPH_STEPS replays of
+        # it plus K % GRAPH_STEPS replays of the one-step graph.
+        many_steps = None
+        if use_graph and args.steps_per_graph > 1:
+            def several():
+                for _ in range(args.steps_per_graph):
+                    whole_step()
+            many_steps = capture(several)
+
+        def run_steps(k):
+            if many_steps is not None:
+                for _ in range(k // args.steps_per_graph):
+                    many_steps()
+                k %= args.steps_per_graph
+            for _ in range(k):
+                one_step()
         # settle the clocks: the first tens of milliseconds after idle run at other clocks than the steady state
         t_w = time.perf_counter()
         while time.perf_counter() - t_w < 0.06:
-            for _ in range(20):
-                one_step()
+            run_steps(20)
             stream.synchronize()
-        for _ in range(args.warmup):
-            one_step()
+        run_steps(args.warmup)
         stream.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for k in range(args.steps):
-            one_step()
+        run_steps(args.steps)
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -246,6 +264,7 @@ def main():
                                "FFN 768->3072, 3072->768), tokens 32x128=4096, 128 groups, bits {2,3,4,8}, fwd only; "
                                "step = 16 quantize/pack (16 distinct fp32 matrices, 1 launch) + 4 act-quant (1 launch) + 16 int8 GEMM+epilogue",
                    "tokens": T, "groups": GROUPS, "bits": list(BITS_SWEEP), "hip_graph": use_graph,
+                   "steps_per_graph": args.steps_per_graph if use_graph else 0,
                    "gemm_launches_per_step": n_gemm},
         "roofline": {"kernel": "qgemm_i8_ws_kernel (int8 MFMA GEMM + scale epilogue; per bit-width one persistent launch "
                                "walks the 128x96 tiles of QKV, attention-out, FFN-up and FFN-down), "
