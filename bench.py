@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--gemm-only", type=str, default=None, metavar="T,N,K,BITS",
                     help="run only this GEMM shape (30 single launches of qb_qlinear_fwd, then 10 batched calls of four "
                          "independent problems) and print its timing: the command profiled for per-shape counters")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="run only the 12-layer iteration (configs[3]) and print its result: the command profiled for the "
+                         "split of a fine-tuning iteration over its kernels")
     ap.add_argument("--backward-only", action="store_true",
                     help="run only the STE-backward leg (configs[2]) and print its result: the command profiled for "
                          "the backward kernels")
@@ -82,6 +85,9 @@ def main():
     T = T_TOKENS
     if args.backward_only:
         print(json.dumps({"backward": backward_leg(torch, qb, wl, dev)}))
+        return
+    if args.stack_only:
+        print(json.dumps({"stack_12_layers": stack_leg(torch, qb, wl, dev)}))
         return
     if args.gemm_only:
         print(json.dumps({"gemm": gemm_only_leg(torch, qb, wl, dev, [int(v) for v in args.gemm_only.split(",")])}))
