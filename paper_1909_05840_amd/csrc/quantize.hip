@@ -2,9 +2,10 @@
 // max-abs range per token), the unpack test hook and the 4/8-bit column-grouped embedding table.
 //
 // All of them are bound by HBM traffic.  The weight kernel therefore reads each fp32 weight
-// from memory exactly once: one workgroup owns one group (a contiguous block of N/G rows),
-// keeps it in registers between the max-abs reduction and the quantization, and routes the
-// codes through LDS only to regroup them into the 32-code slots of the packed layout.
+// from memory exactly once: a team of threads (a workgroup, or a half or a quarter of one) owns
+// one group (a contiguous block of N/G rows), keeps it in registers between the max-abs reduction
+// and the quantization, and routes the codes through LDS only to regroup them into the 32-code
+// slots of the packed layout; resident workgroups walk over the groups of up to 48 matrices.
 //
 // Every floating-point step that decides a code is a single correctly rounded binary32
 // operation (add, divide, round-half-even), in the order the paper's appendix gives them
