@@ -16,9 +16,12 @@
 //   qgemm_i8_dma_kernel both operands copied global -> LDS by the load unit itself (global_load_lds_dwordx4, no
 //                       registers involved) through a ring of stages; every wavefront copies and multiplies; two
 //                       workgroups per CU.
-//   qgemm_i8_ws_kernel  the same data path with the work split by role (copy wavefronts / MFMA wavefronts), one
-//                       persistent workgroup per CU, epilogue parameters staged in LDS; optionally with the copy
-//                       wavefronts on a SIMD of their own (128x96 tiles), an 8-bit output, per-token scales.
+//   qgemm_i8_ws_kernel  the same data path with the work split by role (copy wavefronts / MFMA wavefronts), a
+//                       persistent grid that walks the tiles of one or several problems (a table of problems is the
+//                       kernel argument), epilogue parameters staged in LDS; optionally with the copy wavefronts on
+//                       a SIMD of their own (128x96 tiles; two workgroups per CU when there are more tiles than CUs:
+//                       one's write-out runs under the other's K-loop), an 8-bit output, per-token scales,
+//                       asymmetric group ranges.
 // In all of them the token tile sits in LDS as dense 128-byte rows whose 16-byte chunks are XOR-swizzled by the
 // row number, so that the MFMA fragment reads are free of bank conflicts, and the k-bit codes are expanded to
 // int8 with a few byte-parallel shifts and masks in registers, right in front of the MFMA that consumes them.
