@@ -268,7 +268,7 @@ qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
  * successive calls on one stream are safe, whatever their shapes.  Other arguments and errors as
  * qb_qlinear_bwd_ste.
  */
-#define QB_BWD_STATIC_BYTES (36u << 20)
+#define QB_BWD_STATIC_BYTES (60u << 20)
 qb_status qb_qlinear_bwd_ste_static(const uint16_t *dY, const int8_t *Xq, float clip,
                                     const void *packed, const float *h, int bits, int groups,
                                     int64_t T, int64_t N, int64_t K,

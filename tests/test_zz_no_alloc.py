@@ -41,17 +41,19 @@ def one_case(qb, T, N, K, G, bits, seed):
     torch.cuda.synchronize()
     assert torch.equal(dX.view(torch.int16), dX_ref.view(torch.int16)), "dX differs from qb_qlinear_bwd_ste"
     assert torch.equal(dW.view(torch.int32), dW_ref.view(torch.int32)), "dW differs from qb_qlinear_bwd_ste"
-    # one output only
+    # one output only (compared with the existing entry point called the same way: which outputs a call computes
+    # decides how its workgroups share the contraction, and with that the order of the fp32 additions)
+    dX2_ref, _ = qb.qb_qlinear_bwd_ste(dY, Xq, CLIP, packed, h, bits, G, want_dw=False, workspace=ws)
     dX2 = torch.full((T, K), float("nan"), dtype=torch.bfloat16, device=DEV)
     rc = lib.qb_qlinear_bwd_ste_static(vp(dY.data_ptr()), vp(Xq.data_ptr()), ctypes.c_float(CLIP), vp(packed.data_ptr()),
                                        vp(h.data_ptr()), bits, G, T, N, K, vp(dX2.data_ptr()), None, st)
     assert rc == 0
     torch.cuda.synchronize()
-    assert torch.equal(dX2.view(torch.int16), dX_ref.view(torch.int16))
+    assert torch.equal(dX2.view(torch.int16), dX2_ref.view(torch.int16))
 
 
 def test_static_backward_matches_workspace_backward_twice_in_a_row(qb):
-    # a BERT-base linear at configuration-3 size (split-K dW, 34.5 MiB of staging), then smaller ones with ragged
+    # a BERT-base linear at configuration-3 size (58.5 MiB of staging), then smaller ones with ragged
     # sizes that leave most of the array holding the first call's bytes
     one_case(qb, 4096, 768, 3072, 128, 3, seed=41)
     one_case(qb, 300, 160, 192, 8, 4, seed=42)
@@ -61,8 +63,8 @@ def test_static_backward_matches_workspace_backward_twice_in_a_row(qb):
 
 def test_static_backward_refuses_what_does_not_fit(qb):
     lib = qb.load_library()
-    T, N, K = 12288, 3072, 768   # needs 94.5 MiB of staging
-    assert qb.qb_bwd_workspace_nbytes(T, N, K) > (36 << 20)
+    T, N, K = 12288, 3072, 768   # needs 118.5 MiB of staging
+    assert qb.qb_bwd_workspace_nbytes(T, N, K) > (60 << 20)
     dX = torch.full((8,), 3.0, dtype=torch.bfloat16, device=DEV)
     vp = ctypes.c_void_p
     one = vp(dX.data_ptr())   # never dereferenced: the call is refused on the host
