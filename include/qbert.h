@@ -250,6 +250,13 @@ qb_status qb_quantize_act_dyn_tensor(const float *X, int64_t T, int64_t K,
  *   dW   out  [N,K] fp32 or NULL; overwritten, not accumulated into
  *   workspace  qb_bwd_workspace_nbytes(T,N,K) bytes, 256-byte aligned; contents undefined
  *              before and after the call
+ * Two launches on `stream` (operand staging, then one launch that computes both products, its workgroups sharing
+ * the contraction steps evenly and adding the partial sums of a shared tile in a fixed order): the same call gives
+ * the same bits every time.  Which of dX and dW a call computes decides how the steps are shared, so dX of a
+ * dX-only call may differ from dX of a call that also computes dW in the last bf16 bit (order of the fp32
+ * additions).  Inside the launch a workgroup may wait for partial sums of workgroups dispatched before it; the
+ * wait is bounded (about two seconds), after which the tile concerned is written as NaN.  Calls that share a
+ * workspace must not overlap in time.
  */
 qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
                              const void *packed, const float *h, int bits, int groups,
@@ -262,7 +269,7 @@ qb_status qb_qlinear_bwd_ste(const uint16_t *dY, const int8_t *Xq, float clip,
  * results, with the staging area taken from a fixed array inside the library instead of a `workspace`
  * argument.  The call allocates and frees nothing.  The array has QB_BWD_STATIC_BYTES bytes on every GPU the
  * library runs on, for as long as the process lives; shapes that need more (qb_bwd_workspace_nbytes(T,N,K) >
- * QB_BWD_STATIC_BYTES; the limit covers every linear of a BERT-base layer at up to 4096 tokens) are refused with
+ * QB_BWD_STATIC_BYTES; the limit covers every linear of a BERT-base layer at up to 4096 tokens: 58.5 MiB) are refused with
  * QB_ERR_WORKSPACE before anything is enqueued.  All calls on one GPU share that GPU's array: calls that overlap
  * in time on one GPU (different streams, different threads) race on it and must be serialised by the caller;
  * successive calls on one stream are safe, whatever their shapes.  Other arguments and errors as
