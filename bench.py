@@ -197,16 +197,23 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
 
-        # ---- per-kernel pass: each stage on its own, ten replays between two events.
+        # ---- per-kernel pass: each stage on its own, thirty replays between two events.
         # The quantize/pack stage of the step is one launch over 113 MB of weights, which would stay in the 256 MB
         # last-level cache from one repetition to the next (inside a step the GEMM outputs evict them).  Its
         # figure is therefore taken on THREE distinct copies of the step's 16 matrices (48 jobs, 339 MB of weights,
         # still one launch of the same kernel): every repetition then reads its weights from HBM.  For reference
         # the step's own launch is also timed behind a 512 MiB fill, as the difference to the fill alone; that
         # way charges the quantizer with the write-back of the fill's dirty lines.
-        def timed(run, n=10):
-            run()
-            stream.synchronize()
+        def timed(run, n=30, settle_ms=25.0):
+            # the stage is first repeated for settle_ms: after a change of kernel mix the chip's clocks take tens of
+            # milliseconds to settle (a GEMM stage timed right behind the memory-bound stages came out 13 % slow)
+            t_s = time.perf_counter()
+            while True:
+                for _ in range(5):
+                    run()
+                stream.synchronize()
+                if (time.perf_counter() - t_s) * 1e3 >= settle_ms:
+                    break
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(n):
