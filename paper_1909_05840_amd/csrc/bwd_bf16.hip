@@ -547,11 +547,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_sk_kernel(const SkGroup g)
                 }
             }
             stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
-            // The step's last fragment reads are issued above the barrier, and the compiler lets the MFMAs that use
-            // them follow below it, so a wavefront may arrive with those reads still queued in the LDS.  The copy that
-            // overwrites this stage is started by a copy wavefront after the barrier and its data comes back from L2
-            // or HBM: the LDS serves the handful of queued reads (a few hundred cycles at most) long before that.
-            // Holding the MFMAs above the barrier instead was measured 4 % slower per layer.
+            // The stage just read is overwritten by copies that the copy wavefronts start right behind the barrier, so
+            // this wavefront's reads of it must have returned, not only been issued: the compiler lets the MFMAs that
+            // consume the step's last fragments follow below the barrier, and without the explicit wait a wavefront
+            // arrives with those reads still queued in the LDS.  (Found as wrong results when another stream's kernel
+            // kept the CU's LDS busy; the wait costs 1-2 % per layer.)
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");

@@ -497,11 +497,16 @@ __global__ __launch_bounds__(64 * WM * WN) void qgemm_i8_dma_kernel(
 
 // End of a step.  A bare s_barrier, not __syncthreads(): the fence inside the latter would wait
 // for every copy in flight (vmcnt 0) and with that undo the run-ahead.  What the barrier has to
-// order is already ordered: this wavefront's LDS reads of the step have returned (the MFMAs that
-// consume them are issued before it) and its copies for the next step have landed (wait_vmcnt).
+// order: this wavefront's copies for the next step have landed (wait_vmcnt), and its LDS reads of the
+// step have returned: the stage is overwritten by copies that start right behind the barrier.  The
+// second needs the explicit wait for the LDS counter: the compiler is free to let the MFMAs that
+// consume the step's last fragments follow below the barrier, and the reads would then still be
+// queued in the LDS when the wavefront arrives (seen as wrong results in the backward's kernel, which
+// has the same structure, when another stream's kernel kept the CU's LDS busy).
 // The empty asm keeps the compiler from moving LDS reads of the next step above the barrier.
 #define QB_STEP_BARRIER()                                                                                 \
     {                                                                                                     \
+        __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */                                              \
         __builtin_amdgcn_s_barrier();                                                                     \
         asm volatile("" ::: "memory");                                                                    \
     }
@@ -1110,9 +1115,13 @@ __global__ __launch_bounds__(64 * (WM * WN + NPROD), (SIMD3 && OUT != 2 && NSTAG
         }                                                                                                 \
     }
 // a bare barrier (no fence: the producers' vmcnt wait is what makes the copies visible); the empty
-// asm keeps the compiler from moving LDS reads across it
+// asm keeps the compiler from moving LDS reads across it.  The wait for the LDS counter in front of it: the
+// stage just read is overwritten by copies that the producers start right behind the barrier, so this
+// wavefront's reads of it must have returned, not only been issued (the compiler lets the MFMAs that consume
+// the step's last fragments follow below the barrier).
 #define QB_BARRIER()                                                                                      \
     {                                                                                                     \
+        __builtin_amdgcn_s_waitcnt(0xC07F); /* lgkmcnt(0) */                                              \
         asm volatile("" ::: "memory");                                                                    \
         __builtin_amdgcn_s_barrier();                                                                     \
         asm volatile("" ::: "memory");                                                                    \

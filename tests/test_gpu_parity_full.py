@@ -238,6 +238,75 @@ def test_backward_config3_whole_matrices(qb, lin):
     assert not bad.any(), "dW: %d elements outside the bound" % bad.sum()
 
 
+def test_backward_calls_on_two_streams_at_once(qb):
+    """Two backward calls (QKV and FFN-up at 4096 tokens, each its own workspace) enqueued on two streams so that their
+    launches compete for the CUs: inside a launch a workgroup waits for partial sums of workgroups dispatched before it,
+    which must not depend on having the chip to itself.  Each result equals, bit for bit, the same call run alone."""
+    T, bits = 4096, 3
+    say("bwd on two streams")
+    cases = []
+    for i, (name, N, K) in enumerate([wl.BERT_BASE_LINEARS[0], wl.BERT_BASE_LINEARS[2]]):
+        d = quantized_inputs(qb, N, K, T, bits, seed=700 + i)
+        dY = wl.grad_output_bf16(T, N, seed=710 + i).to(DEV)
+        ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=DEV)
+        alone = qb.qb_qlinear_bwd_ste(dY, d["Xq"], CLIP, d["packed"], d["h"], bits, G, workspace=ws)
+        cases.append(dict(d=d, dY=dY, ws=ws, alone=alone, N=N, K=K,
+                          dX=torch.empty((T, K), dtype=torch.bfloat16, device=DEV),
+                          dW=torch.empty((N, K), dtype=torch.float32, device=DEV)))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]   # default priority
+    for rep in range(5):
+        for c in cases:
+            c["dX"].fill_(float("nan"))
+            c["dW"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        for c, st in zip(cases, streams):
+            with torch.cuda.stream(st):
+                for _ in range(3):
+                    qb.qb_qlinear_bwd_ste(c["dY"], c["d"]["Xq"], CLIP, c["d"]["packed"], c["d"]["h"], bits, G, dX=c["dX"],
+                                          dW=c["dW"], workspace=c["ws"])
+        torch.cuda.synchronize()
+        for c in cases:
+            assert torch.equal(c["dX"].view(torch.int16), c["alone"][0].view(torch.int16))
+            assert torch.equal(c["dW"].view(torch.int32), c["alone"][1].view(torch.int32))
+
+
+def test_forward_next_to_another_streams_kernels(qb):
+    """The step's shared forward launch on one stream while another stream runs backward calls (whose staging kernels
+    keep the CUs' LDS busy): Y equals, bit for bit, the same call run alone.  A GEMM wavefront must not pass a step
+    barrier while its LDS reads of the stage are still queued."""
+    T, bits = 4096, 4
+    say("fwd next to another stream's kernels")
+    jobs = []
+    for i, (name, N, K) in enumerate(wl.BERT_BASE_LINEARS):
+        d = quantized_inputs(qb, N, K, T, bits, seed=800 + i)
+        jobs.append(dict(Xq=d["Xq"], rs_x=d["rs_x"], clip=CLIP, packed=d["packed"], h=d["h"], rs_w=d["rs_w"], bits=bits,
+                         groups=G, N=N, Y=torch.empty((T, N), dtype=torch.float32, device=DEV)))
+    qb.qb_qlinear_fwd_batched(jobs)
+    torch.cuda.synchronize()
+    alone = [j["Y"].clone() for j in jobs]
+    name, N, K = wl.BERT_BASE_LINEARS[0]
+    b = quantized_inputs(qb, N, K, T, 3, seed=810)
+    dY = wl.grad_output_bf16(T, N, seed=811).to(DEV)
+    ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=DEV)
+    dX = torch.empty((T, K), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((N, K), dtype=torch.float32, device=DEV)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()   # default priority
+    for rep in range(4):
+        for j in jobs:
+            j["Y"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s2):
+            for _ in range(8):
+                qb.qb_qlinear_bwd_ste(dY, b["Xq"], CLIP, b["packed"], b["h"], 3, G, dX=dX, dW=dW, workspace=ws)
+        with torch.cuda.stream(s1):
+            for _ in range(6):
+                qb.qb_qlinear_fwd_batched(jobs)
+        torch.cuda.synchronize()
+        for j, r in zip(jobs, alone):
+            assert torch.equal(j["Y"].view(torch.int32), r.view(torch.int32))
+
+
 # ---- batched activation quantizer ---------------------------------------------------------------------------------
 def test_quantize_act_batched(qb):
     """The four inputs of a BERT-base layer at 4096 tokens plus ragged and tiny tensors (and two clips) in one call:
