@@ -291,6 +291,11 @@ def test_forward_next_to_another_streams_kernels(qb):
     ws = torch.empty(qb.qb_bwd_workspace_nbytes(T, N, K), dtype=torch.uint8, device=DEV)
     dX = torch.empty((T, K), dtype=torch.bfloat16, device=DEV)
     dW = torch.empty((N, K), dtype=torch.float32, device=DEV)
+    # the other stream also re-quantizes weights and activations; their results are checked as well
+    Wd, Xd = b["W"].to(DEV), b["X"].to(DEV)
+    q_alone = qb.qb_quantize_groupwise(Wd, 3, G)
+    a_alone = qb.qb_quantize_act(Xd, CLIP)
+    torch.cuda.synchronize()
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()   # default priority
     for rep in range(4):
         for j in jobs:
@@ -299,12 +304,16 @@ def test_forward_next_to_another_streams_kernels(qb):
         with torch.cuda.stream(s2):
             for _ in range(8):
                 qb.qb_qlinear_bwd_ste(dY, b["Xq"], CLIP, b["packed"], b["h"], 3, G, dX=dX, dW=dW, workspace=ws)
+                q_now = qb.qb_quantize_groupwise(Wd, 3, G)
+                a_now = qb.qb_quantize_act(Xd, CLIP)
         with torch.cuda.stream(s1):
             for _ in range(6):
                 qb.qb_qlinear_fwd_batched(jobs)
         torch.cuda.synchronize()
         for j, r in zip(jobs, alone):
             assert torch.equal(j["Y"].view(torch.int32), r.view(torch.int32))
+        assert all(torch.equal(x.view(torch.uint8), y.view(torch.uint8)) for x, y in zip(q_now, q_alone))
+        assert all(torch.equal(x.view(torch.uint8), y.view(torch.uint8)) for x, y in zip(a_now, a_alone))
 
 
 # ---- batched activation quantizer ---------------------------------------------------------------------------------
