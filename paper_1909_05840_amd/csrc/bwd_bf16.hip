@@ -203,15 +203,15 @@ __device__ __forceinline__ void wait_vmcnt()
 // four SIMDs of the CU in turn (wavefront w on SIMD w%4), and a global -> LDS copy issued on a SIMD that is
 // busy with 32x32 MFMAs runs at about half speed (and slows the MFMAs), while one issued on a SIMD without
 // MFMAs does not.  Hence: wavefronts 3 and 7 (SIMD 3) do nothing but copy, wavefronts 0,1,2,4,5,6 multiply,
-// 64 x 32 outputs each in a 2 x 3 grid: tiles of 128 x 96.  Per step and tile, 28 KB are copied for 522
-// cycles of MFMAs on each of three SIMDs.  (Roles depend on the wavefront number only: a different
-// placement by the hardware would cost speed, not correctness.)
+// in a 2 x 3 grid, 64 x 32 outputs each (tiles of 128 x 96: per step 28 KB copied for 512 cycles of MFMAs on each
+// of three SIMDs) or 64 x 64 (tiles of 128 x 192: 40 KB for 1024 cycles).  (Roles depend on the wavefront number
+// only: a different placement by the hardware would cost speed, not correctness.)
 // Protocol per run of n steps (ring of NSTAGE stages, copies run D = NSTAGE-1 steps ahead); every wavefront
 // executes n+1 barriers:
 //   copy wavefronts: start copies 0..D-1; wait copy 0; BARRIER;
 //                    for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
 //                           wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
-//   MFMA wavefronts: BARRIER; for s: multiply stage s % NSTAGE; BARRIER
+//   MFMA wavefronts: BARRIER; for s: multiply stage s % NSTAGE; wait until the stage's LDS reads have returned; BARRIER
 //
 // Division of the work.  The products of a call (dX, dW or both) form one sequence of units, a unit being one
 // 64-wide contraction step of one tile: problem after problem, tile after tile (the tiles of one row of tiles

@@ -852,7 +852,7 @@ __device__ __forceinline__ void quant_block_lds(const v16i &acc, const uint8_t *
 //   producer: start copies 0..D-1; wait copy 0; BARRIER;
 //             for s: start copy s+D (its stage was read in step s-1, finished at the last barrier);
 //                    wait copy s+1 (vmcnt leaves the younger ones in flight); BARRIER
-//   consumer: BARRIER; for s: MMA on stage s % NSTAGE; BARRIER
+//   consumer: BARRIER; for s: MMA on stage s % NSTAGE; wait until the stage's LDS reads have returned; BARRIER
 // OUTQ: instead of Y the tile is quantized to 8 bits (quant_block_lds) into an LDS staging tile and, after one
 // more barrier per tile (E, executed by the producers once the next tile's first copies are on their way), written
 // out in whole rows; the rows' sums are collected in LDS and added to rs_y one tile later.
